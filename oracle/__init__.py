@@ -1,0 +1,11 @@
+"""fp64 CPU oracle for Ring Self-Attention.  Test infrastructure only.
+
+Only tests, the smoke check and the CPU-baseline leg of the benchmark may
+import this package.  It shares nothing with the HIP library.
+"""
+from .rsa_oracle import (  # noqa: F401
+    build,
+    forward,
+    backward,
+    threads,
+)
