@@ -1,0 +1,142 @@
+/*
+ * rsa.h -- C ABI of the Ring Self-Attention (RSA) library for AMD MI355X (gfx950).
+ *
+ * RSA (paper section 3.1) splits a sequence of L tokens into N chunks of
+ * c = L/N rows; device ("rank") n holds Q^n, K^n, V^n and obtains
+ * Attention^n(Q^n, K, V) = softmax(Q^n K^T / sqrt(d_k)) V (Eq. 1) by letting
+ * the K chunks, then the V chunks, travel round the ring (Eq. 3).  This
+ * library runs the ranks of the ring on ONE GPU: the chunks of K and V are
+ * resident in device memory and "ring step t of rank n" is the visit of chunk
+ * j = (n - t) mod N, local chunk first.  There is no inter-GPU traffic.
+ *
+ * Conventions for every entry point
+ *  - All tensor pointers are DEVICE pointers, dense row-major, last index
+ *    contiguous, 16-byte aligned.  The caller owns every buffer; the library
+ *    never allocates, frees or keeps a pointer.
+ *  - K, V, dK, dV are (B, Z, L, A).  Q, O, dO, dQ are (B, Z, Lq, A) with
+ *    Lq = (rank_end - rank_begin) * c: the rows of ranks [rank_begin,
+ *    rank_end) only.  LSE and D are (B, Z, Lq) fp32.
+ *  - With a sub-range of ranks, dK and dV are that range's partial sums (what
+ *    the ring's all-reduce of section 3.2.2 would add up).  dQ, dK, dV are
+ *    overwritten, not accumulated into.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Work is enqueued asynchronously; no call synchronises.
+ *  - Every call returns an rsa_status.  Arguments are validated on the host
+ *    before anything is launched; on error nothing has been enqueued.
+ *  - dtype RSA_BF16: bf16 storage, fp32 accumulation and fp32 softmax, one
+ *    round-to-nearest-even per stored element.  dtype RSA_F32: fp32
+ *    throughout (staged mode only).
+ *  - Supported: A = 64; L divisible by N (section 4.2: the sequence length
+ *    must be divisible by the sequence-parallel size); c divisible by 64.
+ */
+#ifndef RSA_H
+#define RSA_H
+#include <stddef.h>
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  RSA_OK = 0,
+  RSA_ERR_NULL = -1,        /* a required pointer is NULL                    */
+  RSA_ERR_SHAPE = -2,       /* non-positive size, L % N != 0, bad rank range */
+  RSA_ERR_UNSUPPORTED = -3, /* A, dtype, chunk granularity, alignment, mode  */
+  RSA_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than required       */
+  RSA_ERR_HIP = -5          /* a HIP launch reported an error                */
+} rsa_status;
+
+typedef enum { RSA_F32 = 0, RSA_BF16 = 1 } rsa_dtype;
+
+/* flags */
+#define RSA_MODE_FUSED 0u  /* online-softmax kernels, no score strip in HBM   */
+#define RSA_MODE_STAGED 1u /* the paper's two-pass layout: strip S^n in HBM   */
+
+typedef struct {
+  int32_t B, Z, A;   /* batch, heads, head size                              */
+  int64_t L;         /* total sequence length                                */
+  int32_t N;         /* ring size; c = L / N                                 */
+  int32_t rank_begin, rank_end; /* simulated ranks [begin, end), 0-based     */
+  int32_t causal;    /* 0: bidirectional (the paper); 1: key j visible to    */
+                     /* query i iff j <= i in global token index (extension) */
+  int32_t dtype;     /* rsa_dtype of Q, K, V, O, dO, dQ, dK, dV              */
+  float scale;       /* 1/sqrt(d_k) of Eq. 1; 0 selects 1/sqrt(A)            */
+  uint32_t flags;    /* RSA_MODE_FUSED or RSA_MODE_STAGED                    */
+} rsa_desc;
+
+int rsa_version(void);
+const char *rsa_strerror(int status);
+
+/* Bytes of device workspace rsa_forward (pass 0) or rsa_backward (pass 1)
+ * needs for this descriptor; 0 if the descriptor is invalid. */
+size_t rsa_workspace_bytes(const rsa_desc *d, int pass);
+
+/*
+ * RSA forward (section 3.1, Eq. 1 and Eq. 3): for every simulated rank n in
+ * [rank_begin, rank_end) and ring step t, visit chunk j = (n - t) mod N:
+ * scores of Q^n against K^j, full-row softmax over all L keys, O^n = sum_j
+ * P^n_j V^j.  Writes O (dtype) and LSE_i = log sum_j exp(S_ij) (fp32).
+ * ws: workspace of at least rsa_workspace_bytes(d, 0) bytes (may be NULL if
+ * that is 0).
+ */
+int rsa_forward(const rsa_desc *d, const void *Q, const void *K, const void *V,
+                void *O, float *LSE, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * RSA backward: the derivative of Eq. 1 with the ring structure of section
+ * 3.2.2 (a V pass for dP, a K pass for dQ, sums over ranks for dK and dV):
+ *   dV^j = sum_n (P^n_j)^T dO^n,  dP^n_j = dO^n (V^j)^T,
+ *   D_i = sum_a dO_ia O_ia,       dS = P o (dP - D),
+ *   dQ^n = s sum_j dS^n_j K^j,    dK^j = s sum_n (dS^n_j)^T Q^n.
+ * O and LSE are the forward's outputs.
+ */
+int rsa_backward(const rsa_desc *d, const void *dO, const void *Q,
+                 const void *K, const void *V, const void *O, const float *LSE,
+                 void *dQ, void *dK, void *dV, void *ws, size_t ws_bytes,
+                 void *stream);
+
+/*
+ * Step-level entry points: one ring step of one simulated rank, the paper's
+ * two-pass layout (Table 2, rows Ring-QK^T and Ring-AV).  n is the rank (in
+ * [rank_begin, rank_end)), j the chunk visited.  A "strip" is rank n's
+ * (B, Z, c, L) matrix; column block j is columns [j*c, (j+1)*c).  Strips S and
+ * dP are fp32; strips P and dS are in d->dtype.  Accumulators Oacc, dQacc
+ * (B, Z, c, A) and dKacc, dVacc (B, Z, L, A) are fp32; `accumulate` = 0
+ * overwrites the addressed block, 1 adds to it.
+ */
+
+/* Stage 1 (section 3.1): S^n_j = s Q^n (K^j)^T, masked entries -inf. */
+int rsa_qk_step(const rsa_desc *d, int n, int j, const void *Q, const void *K,
+                float *S, void *stream);
+/* Eq. 1's softmax over the full row of L keys: P = softmax(S), LSE. */
+int rsa_row_softmax(const rsa_desc *d, int n, const float *S, void *P,
+                    float *LSE, void *stream);
+/* Stage 2 (Eq. 3): Oacc (+)= P^n_j V^j. */
+int rsa_av_step(const rsa_desc *d, int n, int j, const void *P, const void *V,
+                float *Oacc, int accumulate, void *stream);
+/* D_i = sum_a dO_ia O_ia for the rows of rank n. */
+int rsa_bwd_rowdot(const rsa_desc *d, int n, const void *dO, const void *O,
+                   float *D, void *stream);
+/* dVacc^j (+)= (P^n_j)^T dO^n. */
+int rsa_dv_step(const rsa_desc *d, int n, int j, const void *P, const void *dO,
+                float *dVacc, int accumulate, void *stream);
+/* dP^n_j = dO^n (V^j)^T. */
+int rsa_dp_step(const rsa_desc *d, int n, int j, const void *dO, const void *V,
+                float *dP, void *stream);
+/* dS = P o (dP - D) over the whole strip of rank n. */
+int rsa_softmax_bwd(const rsa_desc *d, int n, const void *P, const float *dP,
+                    const float *D, void *dS, void *stream);
+/* dQacc^n (+)= s dS^n_j K^j. */
+int rsa_dq_step(const rsa_desc *d, int n, int j, const void *dS, const void *K,
+                float *dQacc, int accumulate, void *stream);
+/* dKacc^j (+)= s (dS^n_j)^T Q^n. */
+int rsa_dk_step(const rsa_desc *d, int n, int j, const void *dS, const void *Q,
+                float *dKacc, int accumulate, void *stream);
+/* dst (d->dtype) = src (fp32), `count` elements: stores an accumulator. */
+int rsa_store(const rsa_desc *d, const float *src, void *dst, size_t count,
+              void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

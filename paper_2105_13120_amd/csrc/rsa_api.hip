@@ -1,0 +1,291 @@
+// C ABI of the RSA library: argument validation and dispatch (declared in rsa.h).
+#include <cmath>
+#include <cstring>
+
+#include "rsa_kernels.h"
+
+namespace {
+
+using rsa::Dims;
+
+int validate(const rsa_desc *d, Dims *out) {
+  if (!d) return RSA_ERR_NULL;
+  if (d->B < 1 || d->Z < 1 || d->A < 1 || d->L < 1 || d->N < 1) return RSA_ERR_SHAPE;
+  if (d->L % d->N != 0) return RSA_ERR_SHAPE;  // section 4.2: L divisible by the ring size
+  if (d->rank_begin < 0 || d->rank_end > d->N || d->rank_begin >= d->rank_end) return RSA_ERR_SHAPE;
+  if (d->A != 64) return RSA_ERR_UNSUPPORTED;
+  if (d->dtype != RSA_F32 && d->dtype != RSA_BF16) return RSA_ERR_UNSUPPORTED;
+  if (d->flags != RSA_MODE_FUSED && d->flags != RSA_MODE_STAGED) return RSA_ERR_UNSUPPORTED;
+  if (d->flags == RSA_MODE_FUSED && d->dtype != RSA_BF16) return RSA_ERR_UNSUPPORTED;
+  const int64_t c = d->L / d->N;
+  if (c % 64 != 0) return RSA_ERR_UNSUPPORTED;
+  if (!(d->scale >= 0.0f) || !std::isfinite(d->scale)) return RSA_ERR_SHAPE;
+  if ((int64_t)d->B * d->Z > 65535) return RSA_ERR_UNSUPPORTED;  // heads ride on gridDim.z
+  out->B = d->B; out->Z = d->Z; out->A = d->A; out->N = d->N;
+  out->rank_begin = d->rank_begin; out->rank_end = d->rank_end;
+  out->causal = d->causal ? 1 : 0;
+  out->L = d->L; out->c = c; out->Lq = (int64_t)(d->rank_end - d->rank_begin) * c;
+  out->scale = d->scale > 0.0f ? d->scale : 1.0f / std::sqrt((float)d->A);
+  return RSA_OK;
+}
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Workspace layout of the staged mode (offsets in bytes, each block 256-aligned).
+struct StagedWs {
+  size_t strip32, strip32b, strip16, strip16b, acc_q, acc_k, acc_v, dvec, total;
+};
+StagedWs staged_layout(const Dims &d, int dtype, int pass) {
+  const size_t heads = (size_t)d.B * d.Z;
+  const size_t strip = heads * (size_t)d.c * (size_t)d.L;
+  const size_t es = dtype == RSA_BF16 ? 2 : 4;
+  StagedWs w{};
+  size_t off = 0;
+  w.strip32 = off; off += align256(strip * 4);                 // S (fp32)
+  w.strip16 = off; off += align256(strip * es);                // P (dtype)
+  w.acc_q = off; off += align256(heads * d.c * d.A * 4);       // Oacc or dQacc
+  if (pass == 1) {
+    w.strip32b = off; off += align256(strip * 4);              // dP (fp32)
+    w.strip16b = off; off += align256(strip * es);             // dS (dtype)
+    w.acc_k = off; off += align256(heads * d.L * d.A * 4);     // dKacc
+    w.acc_v = off; off += align256(heads * d.L * d.A * 4);     // dVacc
+    w.dvec = off; off += align256(heads * d.Lq * 4);           // D
+  }
+  w.total = off;
+  return w;
+}
+
+size_t workspace_bytes(const Dims &d, int dtype, unsigned flags, int pass) {
+  if (flags == RSA_MODE_STAGED) return staged_layout(d, dtype, pass).total;
+  if (pass == 1) return align256((size_t)d.B * d.Z * d.Lq * 4);  // D
+  return 0;
+}
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? RSA_OK : RSA_ERR_HIP; }
+
+#define RSA_TRY(expr)                             \
+  do {                                            \
+    hipError_t e_ = (expr);                       \
+    if (e_ != hipSuccess) return RSA_ERR_HIP;     \
+  } while (0)
+
+int check_rank_chunk(const Dims &d, int n, int j) {
+  if (n < d.rank_begin || n >= d.rank_end) return RSA_ERR_SHAPE;
+  if (j < 0 || j >= d.N) return RSA_ERR_SHAPE;
+  return RSA_OK;
+}
+
+// The paper's two-pass forward for the simulated ranks, one after the other.
+int staged_forward(const Dims &d, int dtype, const void *Q, const void *K, const void *V, void *O,
+                   float *LSE, char *ws, hipStream_t st) {
+  const StagedWs w = staged_layout(d, dtype, 0);
+  float *S = reinterpret_cast<float *>(ws + w.strip32);
+  void *P = ws + w.strip16;
+  float *Oacc = reinterpret_cast<float *>(ws + w.acc_q);
+  const size_t es = dtype == RSA_BF16 ? 2 : 4;
+  for (int n = d.rank_begin; n < d.rank_end; ++n) {
+    for (int t = 0; t < d.N; ++t) {  // K ring pass, local chunk first
+      const int j = (n - t + d.N) % d.N;
+      RSA_TRY(rsa::staged_qk_step(d, dtype, n, j, Q, K, S, st));
+    }
+    RSA_TRY(rsa::staged_row_softmax(d, dtype, n, S, P, LSE, st));
+    int first = 1;
+    for (int t = 0; t < d.N; ++t) {  // V ring pass
+      const int j = (n - t + d.N) % d.N;
+      if (d.causal && j > n) continue;  // all-zero probabilities
+      RSA_TRY(rsa::staged_av_step(d, dtype, n, j, P, V, Oacc, !first, st));
+      first = 0;
+    }
+    char *On = static_cast<char *>(O) + (size_t)(n - d.rank_begin) * d.c * d.A * es;
+    RSA_TRY(rsa::store_rows(dtype, Oacc, On, (int64_t)d.B * d.Z, d.c, d.A, d.c * d.A, d.Lq * d.A, st));
+  }
+  return RSA_OK;
+}
+
+int staged_backward(const Dims &d, int dtype, const void *dO, const void *Q, const void *K,
+                    const void *V, const void *O, void *dQ, void *dK, void *dV, char *ws,
+                    hipStream_t st) {
+  const StagedWs w = staged_layout(d, dtype, 1);
+  float *S = reinterpret_cast<float *>(ws + w.strip32);
+  void *P = ws + w.strip16;
+  float *dP = reinterpret_cast<float *>(ws + w.strip32b);
+  void *dS = ws + w.strip16b;
+  float *dQacc = reinterpret_cast<float *>(ws + w.acc_q);
+  float *dKacc = reinterpret_cast<float *>(ws + w.acc_k);
+  float *dVacc = reinterpret_cast<float *>(ws + w.acc_v);
+  float *D = reinterpret_cast<float *>(ws + w.dvec);
+  const size_t es = dtype == RSA_BF16 ? 2 : 4;
+  const int64_t heads = (int64_t)d.B * d.Z;
+  // chunks that no simulated rank looks at keep a zero gradient
+  RSA_TRY(hipMemsetAsync(dKacc, 0, (size_t)heads * d.L * d.A * 4, st));
+  RSA_TRY(hipMemsetAsync(dVacc, 0, (size_t)heads * d.L * d.A * 4, st));
+  RSA_TRY(rsa::rowdot(d, dtype, 0, d.Lq, dO, O, D, st));
+  // the softmax statistics are recomputed; the LSE written here is scratch
+  float *lse_scratch = dQacc;  // (heads * c) floats fit in (heads * c * A)
+  for (int n = d.rank_begin; n < d.rank_end; ++n) {
+    Dims dn = d;  // a view in which rank n is the only rank, for the scratch LSE rows
+    for (int t = 0; t < d.N; ++t) {
+      const int j = (n - t + d.N) % d.N;
+      RSA_TRY(rsa::staged_qk_step(d, dtype, n, j, Q, K, S, st));
+    }
+    dn.rank_begin = n; dn.rank_end = n + 1; dn.Lq = d.c;
+    RSA_TRY(rsa::staged_row_softmax(dn, dtype, n, S, P, lse_scratch, st));
+    for (int t = 0; t < d.N; ++t) {  // V ring pass of the backward: dP
+      const int j = (n - t + d.N) % d.N;
+      RSA_TRY(rsa::staged_dp_step(d, dtype, n, j, dO, V, dP, st));
+    }
+    RSA_TRY(rsa::staged_softmax_bwd(d, dtype, n, P, dP, D, dS, st));
+    int first = 1;
+    for (int t = 0; t < d.N; ++t) {  // K ring pass of the backward: dQ; partial dK, dV
+      const int j = (n - t + d.N) % d.N;
+      if (d.causal && j > n) continue;
+      RSA_TRY(rsa::staged_dq_step(d, dtype, n, j, dS, K, dQacc, !first, st));
+      RSA_TRY(rsa::staged_dk_step(d, dtype, n, j, dS, Q, dKacc, 1, st));
+      RSA_TRY(rsa::staged_dv_step(d, dtype, n, j, P, dO, dVacc, 1, st));
+      first = 0;
+    }
+    char *dQn = static_cast<char *>(dQ) + (size_t)(n - d.rank_begin) * d.c * d.A * es;
+    RSA_TRY(rsa::store_rows(dtype, dQacc, dQn, heads, d.c, d.A, d.c * d.A, d.Lq * d.A, st));
+  }
+  RSA_TRY(rsa::store_rows(dtype, dKacc, dK, heads, d.L, d.A, d.L * d.A, d.L * d.A, st));
+  RSA_TRY(rsa::store_rows(dtype, dVacc, dV, heads, d.L, d.A, d.L * d.A, d.L * d.A, st));
+  return RSA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rsa_version(void) { return 100; }
+
+const char *rsa_strerror(int status) {
+  switch (status) {
+    case RSA_OK: return "ok";
+    case RSA_ERR_NULL: return "a required pointer is NULL";
+    case RSA_ERR_SHAPE: return "bad shape: sizes must be positive, L divisible by N, ranks within [0, N)";
+    case RSA_ERR_UNSUPPORTED: return "unsupported: need A = 64, L/N divisible by 64, 16-byte aligned pointers, bf16 for the fused mode";
+    case RSA_ERR_WORKSPACE: return "workspace missing or too small";
+    case RSA_ERR_HIP: return "a HIP call failed";
+    default: return "unknown status";
+  }
+}
+
+size_t rsa_workspace_bytes(const rsa_desc *d, int pass) {
+  Dims dm;
+  if (validate(d, &dm) != RSA_OK || (pass != 0 && pass != 1)) return 0;
+  return workspace_bytes(dm, d->dtype, d->flags, pass);
+}
+
+int rsa_forward(const rsa_desc *d, const void *Q, const void *K, const void *V, void *O, float *LSE,
+                void *ws, size_t ws_bytes, void *stream) {
+  Dims dm;
+  int rc = validate(d, &dm);
+  if (rc != RSA_OK) return rc;
+  if (!Q || !K || !V || !O || !LSE) return RSA_ERR_NULL;
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(LSE) || misaligned(ws))
+    return RSA_ERR_UNSUPPORTED;
+  const size_t need = workspace_bytes(dm, d->dtype, d->flags, 0);
+  if (need > 0 && (!ws || ws_bytes < need)) return RSA_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (d->flags == RSA_MODE_STAGED)
+    return staged_forward(dm, d->dtype, Q, K, V, O, LSE, static_cast<char *>(ws), st);
+  return hip_status(rsa::fused_forward(dm, Q, K, V, O, LSE, st));
+}
+
+int rsa_backward(const rsa_desc *d, const void *dO, const void *Q, const void *K, const void *V,
+                 const void *O, const float *LSE, void *dQ, void *dK, void *dV, void *ws,
+                 size_t ws_bytes, void *stream) {
+  Dims dm;
+  int rc = validate(d, &dm);
+  if (rc != RSA_OK) return rc;
+  if (!dO || !Q || !K || !V || !O || !LSE || !dQ || !dK || !dV) return RSA_ERR_NULL;
+  if (misaligned(dO) || misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) ||
+      misaligned(LSE) || misaligned(dQ) || misaligned(dK) || misaligned(dV) || misaligned(ws))
+    return RSA_ERR_UNSUPPORTED;
+  const size_t need = workspace_bytes(dm, d->dtype, d->flags, 1);
+  if (!ws || ws_bytes < need) return RSA_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (d->flags == RSA_MODE_STAGED)
+    return staged_backward(dm, d->dtype, dO, Q, K, V, O, dQ, dK, dV, static_cast<char *>(ws), st);
+  return hip_status(rsa::fused_backward(dm, dO, Q, K, V, O, LSE, dQ, dK, dV,
+                                        static_cast<float *>(ws), st));
+}
+
+// ------------------------------------------------------------ step level ----
+#define RSA_STEP_PROLOGUE(ptr_ok, ...)                            \
+  Dims dm;                                                        \
+  int rc = validate(d, &dm);                                      \
+  if (rc != RSA_OK) return rc;                                    \
+  if (!(ptr_ok)) return RSA_ERR_NULL;                             \
+  { const void *ps_[] = {__VA_ARGS__};                            \
+    for (const void *p_ : ps_) if (misaligned(p_)) return RSA_ERR_UNSUPPORTED; } \
+  hipStream_t st = static_cast<hipStream_t>(stream)
+
+int rsa_qk_step(const rsa_desc *d, int n, int j, const void *Q, const void *K, float *S, void *stream) {
+  RSA_STEP_PROLOGUE(Q && K && S, Q, K, S);
+  if ((rc = check_rank_chunk(dm, n, j)) != RSA_OK) return rc;
+  return hip_status(rsa::staged_qk_step(dm, d->dtype, n, j, Q, K, S, st));
+}
+
+int rsa_row_softmax(const rsa_desc *d, int n, const float *S, void *P, float *LSE, void *stream) {
+  RSA_STEP_PROLOGUE(S && P && LSE, S, P, LSE);
+  if ((rc = check_rank_chunk(dm, n, 0)) != RSA_OK) return rc;
+  return hip_status(rsa::staged_row_softmax(dm, d->dtype, n, S, P, LSE, st));
+}
+
+int rsa_av_step(const rsa_desc *d, int n, int j, const void *P, const void *V, float *Oacc,
+                int accumulate, void *stream) {
+  RSA_STEP_PROLOGUE(P && V && Oacc, P, V, Oacc);
+  if ((rc = check_rank_chunk(dm, n, j)) != RSA_OK) return rc;
+  return hip_status(rsa::staged_av_step(dm, d->dtype, n, j, P, V, Oacc, accumulate != 0, st));
+}
+
+int rsa_bwd_rowdot(const rsa_desc *d, int n, const void *dO, const void *O, float *D, void *stream) {
+  RSA_STEP_PROLOGUE(dO && O && D, dO, O, D);
+  if ((rc = check_rank_chunk(dm, n, 0)) != RSA_OK) return rc;
+  return hip_status(rsa::rowdot(dm, d->dtype, (int64_t)(n - dm.rank_begin) * dm.c, dm.c, dO, O, D, st));
+}
+
+int rsa_dv_step(const rsa_desc *d, int n, int j, const void *P, const void *dO, float *dVacc,
+                int accumulate, void *stream) {
+  RSA_STEP_PROLOGUE(P && dO && dVacc, P, dO, dVacc);
+  if ((rc = check_rank_chunk(dm, n, j)) != RSA_OK) return rc;
+  return hip_status(rsa::staged_dv_step(dm, d->dtype, n, j, P, dO, dVacc, accumulate != 0, st));
+}
+
+int rsa_dp_step(const rsa_desc *d, int n, int j, const void *dO, const void *V, float *dP, void *stream) {
+  RSA_STEP_PROLOGUE(dO && V && dP, dO, V, dP);
+  if ((rc = check_rank_chunk(dm, n, j)) != RSA_OK) return rc;
+  return hip_status(rsa::staged_dp_step(dm, d->dtype, n, j, dO, V, dP, st));
+}
+
+int rsa_softmax_bwd(const rsa_desc *d, int n, const void *P, const float *dP, const float *D,
+                    void *dS, void *stream) {
+  RSA_STEP_PROLOGUE(P && dP && D && dS, P, dP, D, dS);
+  if ((rc = check_rank_chunk(dm, n, 0)) != RSA_OK) return rc;
+  return hip_status(rsa::staged_softmax_bwd(dm, d->dtype, n, P, dP, D, dS, st));
+}
+
+int rsa_dq_step(const rsa_desc *d, int n, int j, const void *dS, const void *K, float *dQacc,
+                int accumulate, void *stream) {
+  RSA_STEP_PROLOGUE(dS && K && dQacc, dS, K, dQacc);
+  if ((rc = check_rank_chunk(dm, n, j)) != RSA_OK) return rc;
+  return hip_status(rsa::staged_dq_step(dm, d->dtype, n, j, dS, K, dQacc, accumulate != 0, st));
+}
+
+int rsa_dk_step(const rsa_desc *d, int n, int j, const void *dS, const void *Q, float *dKacc,
+                int accumulate, void *stream) {
+  RSA_STEP_PROLOGUE(dS && Q && dKacc, dS, Q, dKacc);
+  if ((rc = check_rank_chunk(dm, n, j)) != RSA_OK) return rc;
+  return hip_status(rsa::staged_dk_step(dm, d->dtype, n, j, dS, Q, dKacc, accumulate != 0, st));
+}
+
+int rsa_store(const rsa_desc *d, const float *src, void *dst, size_t count, void *stream) {
+  RSA_STEP_PROLOGUE(src && dst, src, dst);
+  if (count % 4 != 0) return RSA_ERR_SHAPE;
+  return hip_status(rsa::store_rows(d->dtype, src, dst, 1, 1, (int64_t)count, 0, 0, st));
+}
+
+}  // extern "C"

@@ -1,0 +1,105 @@
+// Shared device helpers for the RSA kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rsa.h"
+
+namespace rsa {
+
+typedef __bf16 bf16_t;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// D = A(32x16) * B(16x32) + C on the matrix core.  Lane l supplies
+// A[l%32][(l/32)*8 .. +8] and B[(l/32)*8 .. +8][l%32]; it receives
+// C[(v/4)*8 + (l/32)*4 + v%4][l%32] in element v of the accumulator.
+__device__ __forceinline__ f32x16 mfma_32x32x16(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Two fp32 -> packed bf16 (round to nearest even), low half = x.
+__device__ __forceinline__ uint32_t pack_bf16(float x, float y) {
+  f32x2 v = {x, y};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+  return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+
+// LDS transpose read (ds_read_b64_tr_b16).  Within each group of 16 lanes,
+// lane j passes the address of 4 consecutive 16-bit elements ("row j/4,
+// columns (j%4)*4 .. +4" of a 4 x 16 block); lane i receives column i of that
+// block: element k of the result is element i%4 of the row passed by lane
+// 4*k + i/4.
+__device__ __forceinline__ u32x2 lds_read_tr16(const void *lds_ptr) {
+  typedef __attribute__((__vector_size__(4 * sizeof(short)))) short s16x4;
+  typedef __attribute__((address_space(3))) s16x4 *lds_s16x4_ptr;
+  s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds_ptr));
+  return __builtin_bit_cast(u32x2, r);
+}
+
+// Exchange between the two lanes l and l^32 (the two halves of a 32x32
+// accumulator column).  v_permlane32_swap a, b swaps a[32..63] with b[0..31];
+// with a = b = x on entry, lanes 0-31 end with (a, b) = (x[l], x[l+32]) and
+// lanes 32-63 with (x[l-32], x[l]).  Written as inline asm because the
+// compiler's builtin for this instruction folds its two results into one when
+// both operands carry the same value.  The s_nop covers the wait states the
+// instruction needs after a VALU write of its operands.
+__device__ __forceinline__ void xhalf_pair(float x, float &lo, float &hi) {
+  uint32_t a = __builtin_bit_cast(uint32_t, x), b = a;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+  lo = __builtin_bit_cast(float, a);
+  hi = __builtin_bit_cast(float, b);
+}
+__device__ __forceinline__ float xhalf_max(float x) {
+  float lo, hi;
+  xhalf_pair(x, lo, hi);
+  return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float xhalf_sum(float x) {
+  float lo, hi;
+  xhalf_pair(x, lo, hi);
+  return lo + hi;
+}
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+  return x;
+}
+
+// Work-group id remap for the 8 XCDs: hardware hands consecutive work-group
+// ids to XCDs round-robin, so id i runs on XCD i % 8.  Returns a logical id
+// such that each XCD gets one contiguous range of logical ids (work-groups
+// that share K/V then share that XCD's L2).  `n` must be the grid size.
+__device__ __forceinline__ uint32_t xcd_remap(uint32_t id, uint32_t n) {
+  const uint32_t per = n >> 3;
+  if (per == 0 || id >= per * 8) return id;  // tail keeps its id
+  return (id & 7) * per + (id >> 3);
+}
+
+// Derived sizes of a validated descriptor, shared by host code and kernels.
+struct Dims {
+  int B, Z, A, N, rank_begin, rank_end, causal;
+  int64_t L, c, Lq;
+  float scale;
+};
+
+}  // namespace rsa

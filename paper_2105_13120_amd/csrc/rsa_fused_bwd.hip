@@ -1,0 +1,421 @@
+// Fused Ring Self-Attention backward (bf16, A = 64): the derivative of Eq. 1
+// with the ring structure of section 3.2.2, without the score strip in memory.
+// P is recomputed from Q, K and the forward's LSE: P = exp(s QK^T - LSE).
+//
+//   dkdv kernel: a work-group owns 4*64 keys and walks the query tiles of every
+//     simulated rank, starting with the rank that holds those keys (ring
+//     order); the sum over ranks that the ring would all-reduce is its loop.
+//       S = Q K^T, dP = dO V^T   (A operand: Q / dO rows from LDS; B: K / V in registers)
+//       P = exp2(S cl2 - LSE log2e), dS = P o (dP - D)
+//       dV^T += dO^T P, dK^T += Q^T dS   (A operand: LDS transpose reads; B: P / dS registers)
+//   dq kernel: a work-group owns 4*R query rows and walks the K/V tiles in ring
+//     order (the paper's second K ring pass):
+//       S^T = K Q^T, dP^T = V dO^T, dS^T = P^T o (dP^T - D), dQ^T += K^T dS^T
+#include "rsa_fused_tile.h"
+#include "rsa_kernels.h"
+
+namespace rsa {
+
+struct BwdArgs {
+  const uint16_t *Q, *K, *V, *dO;
+  const float *LSE, *D;
+  uint16_t *dQ, *dK, *dV;
+  int64_t L, c, Lq, q0;
+  int N, tiles_per_head;
+  float cl2, scale;
+};
+
+// ------------------------------------------------------------------ dK, dV ---
+template <bool CAUSAL>
+__global__ void __launch_bounds__(256, 1) fused_bwd_dkdv_kernel(BwdArgs a) {
+  constexpr int KW = 64;      // keys per wave
+  constexpr int BK = 4 * KW;  // keys per work-group
+  __shared__ __attribute__((aligned(16))) unsigned char Qs[2][kTileBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char dOs[2][kTileBytes];
+  __shared__ __attribute__((aligned(16))) float lse_s[2][64];
+  __shared__ __attribute__((aligned(16))) float d_s[2][64];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int64_t head = wg / a.tiles_per_head;
+  const int64_t key0 = (wg % a.tiles_per_head) * BK;  // first key of the work-group
+  const int64_t wkey0 = key0 + wave * KW;             // first key of this wave
+
+  const uint16_t *Qh = a.Q + head * a.Lq * 64;
+  const uint16_t *dOh = a.dO + head * a.Lq * 64;
+  const uint16_t *Kh = a.K + head * a.L * 64;
+  const uint16_t *Vh = a.V + head * a.L * 64;
+  const float *LSEh = a.LSE + head * a.Lq;
+  const float *Dh = a.D + head * a.Lq;
+
+  // K and V of this wave's keys as B operands: lane (col, half) holds row
+  // key = wkey0 + kb*32 + col, elements dk*16 + half*8 .. +8.
+  bf16x8 kreg[2][4], vreg[2][4];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int dk = 0; dk < 4; ++dk) {
+      int64_t key = wkey0 + kb * 32 + col;
+      if (key >= a.L) key = a.L - 1;  // ragged tail: clamped here, not stored below
+      const int64_t off = key * 64 + dk * 16 + half * 8;
+      kreg[kb][dk] = *reinterpret_cast<const bf16x8 *>(Kh + off);
+      vreg[kb][dk] = *reinterpret_cast<const bf16x8 *>(Vh + off);
+    }
+
+  const TileLanes tl(lane);
+  const int ld_row = tid >> 3, ld_ch = tid & 7;
+
+  f32x16 dv[2][2], dk_[2][2];  // [db][kb], transposed: rows = head dim, columns = keys
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { dv[db][kb][v] = 0.f; dk_[db][kb][v] = 0.f; }
+
+  // Query tiles (64 rows) in ring order: start at the rank that owns key0.
+  const int nqt = (int)(a.Lq / 64);
+  int start = 0;
+  {
+    const int64_t r = (key0 / a.c) * a.c - a.q0;  // local row of that rank's first query
+    if (r >= 0 && r < a.Lq) start = (int)(r / 64);
+  }
+  auto qt_of = [&](int i) { int q = start + i; return q >= nqt ? q - nqt : q; };
+  // a query tile matters if its last row can see the first key of the work-group
+  auto visible = [&](int i) { return !CAUSAL || a.q0 + (int64_t)qt_of(i) * 64 + 63 >= key0; };
+  auto advance = [&](int i) { ++i; while (i < nqt && !visible(i)) ++i; return i; };
+
+  u32x4 qr[2], gr[2];
+  float lr = 0.f, dr = 0.f;
+  auto load_tile = [&](int i) {
+    const int64_t r0 = (int64_t)qt_of(i) * 64;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int64_t off = (r0 + ld_row + it * 32) * 64 + ld_ch * 8;
+      qr[it] = *reinterpret_cast<const u32x4 *>(Qh + off);
+      gr[it] = *reinterpret_cast<const u32x4 *>(dOh + off);
+    }
+    if (tid < 64) lr = LSEh[r0 + tid] * kLog2e;
+    else if (tid < 128) dr = Dh[r0 + tid - 64];
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int off = tile_off(ld_row + it * 32, ld_ch);
+      *reinterpret_cast<u32x4 *>(Qs[buf] + off) = qr[it];
+      *reinterpret_cast<u32x4 *>(dOs[buf] + off) = gr[it];
+    }
+    if (tid < 64) lse_s[buf][tid] = lr;
+    else if (tid < 128) d_s[buf][tid - 64] = dr;
+  };
+
+  int i = visible(0) ? 0 : advance(0);
+  int buf = 0;
+  if (i < nqt) {
+    load_tile(i);
+    store_tile(0);
+  }
+  __syncthreads();
+  while (i < nqt) {
+    const int inext = advance(i);
+    if (inext < nqt) load_tile(inext);
+    const int64_t qf = a.q0 + (int64_t)qt_of(i) * 64;  // global index of the tile's first row
+
+    if (!CAUSAL || qf + 63 >= wkey0) {
+      const bool domask = CAUSAL && qf < wkey0 + KW - 1;
+      bf16x8 pf[2][4], sf[2][4];  // [kb][kk]: P and dS as B operands, k = query
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        f32x16 s[2], dp[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) { s[kb][v] = 0.f; dp[kb][v] = 0.f; }
+#pragma unroll
+        for (int dk = 0; dk < 4; ++dk) {
+          const bf16x8 qa = tl.read_rows(Qs[buf], qb * 32, dk);
+          const bf16x8 ga = tl.read_rows(dOs[buf], qb * 32, dk);
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb) {
+            s[kb] = mfma_32x32x16(qa, kreg[kb][dk], s[kb]);
+            dp[kb] = mfma_32x32x16(ga, vreg[kb][dk], dp[kb]);
+          }
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&lse_s[buf][qb * 32 + g * 8 + half * 4]);
+          const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&d_s[buf][qb * 32 + g * 8 + half * 4]);
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int v = g * 4 + e;
+              float x = s[kb][v];
+              if (domask) {
+                const int64_t qg = qf + qb * 32 + g * 8 + half * 4 + e;
+                const int64_t kg = wkey0 + kb * 32 + col;
+                if (kg > qg) x = -INFINITY;
+              }
+              const float p = __builtin_amdgcn_exp2f(fmaf(x, a.cl2, -l4[e]));
+              s[kb][v] = p;
+              dp[kb][v] = p * (dp[kb][v] - d4[e]);
+            }
+        }
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            u32x4 w = {pack_bf16(s[kb][u * 8 + 0], s[kb][u * 8 + 1]), pack_bf16(s[kb][u * 8 + 2], s[kb][u * 8 + 3]),
+                       pack_bf16(s[kb][u * 8 + 4], s[kb][u * 8 + 5]), pack_bf16(s[kb][u * 8 + 6], s[kb][u * 8 + 7])};
+            pf[kb][qb * 2 + u] = __builtin_bit_cast(bf16x8, w);
+            u32x4 x = {pack_bf16(dp[kb][u * 8 + 0], dp[kb][u * 8 + 1]), pack_bf16(dp[kb][u * 8 + 2], dp[kb][u * 8 + 3]),
+                       pack_bf16(dp[kb][u * 8 + 4], dp[kb][u * 8 + 5]), pack_bf16(dp[kb][u * 8 + 6], dp[kb][u * 8 + 7])};
+            sf[kb][qb * 2 + u] = __builtin_bit_cast(bf16x8, x);
+          }
+      }
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const bf16x8 ga = tl.read_cols(dOs[buf], kk * 16, db);
+          const bf16x8 qa = tl.read_cols(Qs[buf], kk * 16, db);
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb) {
+            dv[db][kb] = mfma_32x32x16(ga, pf[kb][kk], dv[db][kb]);
+            dk_[db][kb] = mfma_32x32x16(qa, sf[kb][kk], dk_[db][kb]);
+          }
+        }
+    }
+
+    if (inext < nqt) store_tile(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+    i = inext;
+  }
+
+  uint16_t *dKh = a.dK + head * a.L * 64;
+  uint16_t *dVh = a.dV + head * a.L * 64;
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+    const int64_t key = wkey0 + kb * 32 + col;
+    if (key >= a.L) continue;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int64_t off = key * 64 + db * 32 + g * 8 + half * 4;
+        u32x2 w = {pack_bf16(dv[db][kb][g * 4 + 0], dv[db][kb][g * 4 + 1]),
+                   pack_bf16(dv[db][kb][g * 4 + 2], dv[db][kb][g * 4 + 3])};
+        *reinterpret_cast<u32x2 *>(dVh + off) = w;
+        u32x2 x = {pack_bf16(dk_[db][kb][g * 4 + 0] * a.scale, dk_[db][kb][g * 4 + 1] * a.scale),
+                   pack_bf16(dk_[db][kb][g * 4 + 2] * a.scale, dk_[db][kb][g * 4 + 3] * a.scale)};
+        *reinterpret_cast<u32x2 *>(dKh + off) = x;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------- dQ ---
+template <int R, bool CAUSAL>
+__global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdArgs a) {
+  constexpr int QB = R / 32;
+  constexpr int BM = 4 * R;
+  __shared__ __attribute__((aligned(16))) unsigned char Ks[2][kTileBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Vs[2][kTileBytes];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int64_t head = wg / a.tiles_per_head;
+  const int64_t row0 = (wg % a.tiles_per_head) * BM;
+  const int64_t q_first = a.q0 + row0;
+  const int64_t q_last = a.q0 + (row0 + BM < a.Lq ? row0 + BM : a.Lq) - 1;
+  const int n = (int)(q_first / a.c);
+  const int tpc = (int)(a.c / kTileKeys);
+
+  const uint16_t *Qh = a.Q + head * a.Lq * 64;
+  const uint16_t *dOh = a.dO + head * a.Lq * 64;
+  const uint16_t *Kh = a.K + head * a.L * 64;
+  const uint16_t *Vh = a.V + head * a.L * 64;
+
+  bf16x8 qreg[QB][4], greg[QB][4];
+  int64_t qrow[QB];
+  float lse2[QB], dd[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int64_t r = row0 + wave * R + qb * 32 + col;
+    qrow[qb] = r < a.Lq ? r : a.Lq - 1;
+#pragma unroll
+    for (int dk = 0; dk < 4; ++dk) {
+      qreg[qb][dk] = *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * 64 + dk * 16 + half * 8);
+      greg[qb][dk] = *reinterpret_cast<const bf16x8 *>(dOh + qrow[qb] * 64 + dk * 16 + half * 8);
+    }
+    lse2[qb] = a.LSE[head * a.Lq + qrow[qb]] * kLog2e;
+    dd[qb] = a.D[head * a.Lq + qrow[qb]];
+  }
+  const int64_t wq_first = a.q0 + (row0 + wave * R < a.Lq ? row0 + wave * R : a.Lq - 1);
+  const int64_t wq_last = a.q0 + (row0 + wave * R + R - 1 < a.Lq ? row0 + wave * R + R - 1 : a.Lq - 1);
+
+  const TileLanes tl(lane);
+  const int ld_row = tid >> 3, ld_ch = tid & 7;
+
+  f32x16 dq[2][QB];
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) dq[db][qb][v] = 0.f;
+
+  auto k0_of = [&](int t, int kt) -> int64_t {
+    int j = n - t;
+    if (j < 0) j += a.N;
+    return (int64_t)j * a.c + (int64_t)kt * kTileKeys;
+  };
+  auto advance = [&](int &t, int &kt) -> bool {
+    ++kt;
+    for (;;) {
+      if (kt >= tpc) { ++t; kt = 0; }
+      if (t >= a.N) return false;
+      if (!CAUSAL || k0_of(t, kt) <= q_last) return true;
+      kt = tpc;
+    }
+  };
+  u32x4 kr[2], vr[2];
+  auto load_tile = [&](int64_t k0) {
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int64_t off = (k0 + ld_row + it * 32) * 64 + ld_ch * 8;
+      kr[it] = *reinterpret_cast<const u32x4 *>(Kh + off);
+      vr[it] = *reinterpret_cast<const u32x4 *>(Vh + off);
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int off = tile_off(ld_row + it * 32, ld_ch);
+      *reinterpret_cast<u32x4 *>(Ks[buf] + off) = kr[it];
+      *reinterpret_cast<u32x4 *>(Vs[buf] + off) = vr[it];
+    }
+  };
+
+  int t = 0, kt = 0, buf = 0;
+  load_tile(k0_of(0, 0));
+  store_tile(0);
+  __syncthreads();
+  bool have = true;
+  while (have) {
+    const int64_t k0 = k0_of(t, kt);
+    int t2 = t, kt2 = kt;
+    const bool have_next = advance(t2, kt2);
+    if (have_next) load_tile(k0_of(t2, kt2));
+
+    if (!CAUSAL || k0 <= wq_last) {
+      const bool domask = CAUSAL && k0 + kTileKeys - 1 > wq_first;
+      bf16x8 sf[QB][4];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        f32x16 s[QB], dp[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) { s[qb][v] = 0.f; dp[qb][v] = 0.f; }
+#pragma unroll
+        for (int dk = 0; dk < 4; ++dk) {
+          const bf16x8 ka = tl.read_rows(Ks[buf], kb * 32, dk);
+          const bf16x8 va = tl.read_rows(Vs[buf], kb * 32, dk);
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) {
+            s[qb] = mfma_32x32x16(ka, qreg[qb][dk], s[qb]);
+            dp[qb] = mfma_32x32x16(va, greg[qb][dk], dp[qb]);
+          }
+        }
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+          const int64_t qg = a.q0 + qrow[qb];
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            float x = s[qb][v];
+            if (domask) {
+              const int64_t kg = k0 + kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+              if (kg > qg) x = -INFINITY;
+            }
+            const float p = __builtin_amdgcn_exp2f(fmaf(x, a.cl2, -lse2[qb]));
+            dp[qb][v] = p * (dp[qb][v] - dd[qb]);
+          }
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            u32x4 w = {pack_bf16(dp[qb][u * 8 + 0], dp[qb][u * 8 + 1]), pack_bf16(dp[qb][u * 8 + 2], dp[qb][u * 8 + 3]),
+                       pack_bf16(dp[qb][u * 8 + 4], dp[qb][u * 8 + 5]), pack_bf16(dp[qb][u * 8 + 6], dp[qb][u * 8 + 7])};
+            sf[qb][kb * 2 + u] = __builtin_bit_cast(bf16x8, w);
+          }
+        }
+      }
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const bf16x8 ka = tl.read_cols(Ks[buf], kk * 16, db);
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) dq[db][qb] = mfma_32x32x16(ka, sf[qb][kk], dq[db][qb]);
+        }
+    }
+
+    if (have_next) store_tile(buf ^ 1);
+    __syncthreads();
+    buf ^= 1; t = t2; kt = kt2; have = have_next;
+  }
+
+  uint16_t *dQh = a.dQ + head * a.Lq * 64;
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int64_t r = row0 + wave * R + qb * 32 + col;
+    if (r < a.Lq) {
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          u32x2 w = {pack_bf16(dq[db][qb][g * 4 + 0] * a.scale, dq[db][qb][g * 4 + 1] * a.scale),
+                     pack_bf16(dq[db][qb][g * 4 + 2] * a.scale, dq[db][qb][g * 4 + 3] * a.scale)};
+          *reinterpret_cast<u32x2 *>(dQh + r * 64 + db * 32 + g * 8 + half * 4) = w;
+        }
+    }
+  }
+}
+
+hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const void *K,
+                          const void *V, const void *O, const float *LSE, void *dQ, void *dK,
+                          void *dV, float *D, hipStream_t st) {
+  hipError_t e = rowdot(d, RSA_BF16, 0, d.Lq, dO, O, D, st);
+  if (e != hipSuccess) return e;
+  BwdArgs a;
+  a.Q = (const uint16_t *)Q; a.K = (const uint16_t *)K; a.V = (const uint16_t *)V;
+  a.dO = (const uint16_t *)dO; a.LSE = LSE; a.D = D;
+  a.dQ = (uint16_t *)dQ; a.dK = (uint16_t *)dK; a.dV = (uint16_t *)dV;
+  a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.q0 = (int64_t)d.rank_begin * d.c;
+  a.N = d.N; a.cl2 = d.scale * kLog2e; a.scale = d.scale;
+  const int64_t heads = (int64_t)d.B * d.Z;
+
+  a.tiles_per_head = (int)((d.L + 255) / 256);
+  {
+    dim3 grid((unsigned)(heads * a.tiles_per_head));
+    if (d.causal)
+      hipLaunchKernelGGL((fused_bwd_dkdv_kernel<true>), grid, dim3(256), 0, st, a);
+    else
+      hipLaunchKernelGGL((fused_bwd_dkdv_kernel<false>), grid, dim3(256), 0, st, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  a.tiles_per_head = (int)((d.Lq + 127) / 128);
+  {
+    dim3 grid((unsigned)(heads * a.tiles_per_head));
+    if (d.causal)
+      hipLaunchKernelGGL((fused_bwd_dq_kernel<32, true>), grid, dim3(256), 0, st, a);
+    else
+      hipLaunchKernelGGL((fused_bwd_dq_kernel<32, false>), grid, dim3(256), 0, st, a);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace rsa

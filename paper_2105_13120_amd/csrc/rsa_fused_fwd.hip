@@ -1,0 +1,270 @@
+// Fused Ring Self-Attention forward (bf16, A = 64).
+//
+// One work-group owns 4*R query rows of one head and walks the K/V chunks in
+// ring order -- step t of rank n visits chunk j = (n - t) mod N, local chunk
+// first (section 3.1) -- keeping a running row max and row sum, so the score
+// strip S^n of Table 2 never reaches device memory.  The result is Eq. 1 /
+// Eq. 3 exactly, up to summation order.
+//
+// Data flow per 64-key tile and wave (R query rows):
+//   S^T = K Q^T    A operand: K tile rows from LDS, B operand: Q^T in registers
+//   softmax update on S^T: lane l owns query column l%32, so the row max and
+//                  row sum are in-lane reductions plus one cross-half exchange
+//   O^T += V^T P^T A operand: V^T through LDS transpose reads, B operand: P^T
+//                  straight from the S^T accumulator registers (packed to bf16)
+#include "rsa_fused_tile.h"
+#include "rsa_kernels.h"
+
+namespace rsa {
+
+struct FwdArgs {
+  const uint16_t *Q, *K, *V;
+  uint16_t *O;
+  float *LSE;
+  int64_t L, c, Lq, q0;  // q0: global token index of Q row 0
+  int N, tiles_per_head;
+  float cl2;             // scale * log2(e)
+};
+
+template <int R, bool CAUSAL>
+__global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
+  constexpr int QB = R / 32;
+  constexpr int BM = 4 * R;
+  __shared__ __attribute__((aligned(16))) unsigned char Ks[2][kTileBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Vs[2][kTileBytes];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int64_t head = wg / a.tiles_per_head;
+  const int64_t qt = wg % a.tiles_per_head;
+  const int64_t row0 = qt * BM;  // first local row of this work-group
+  const int64_t q_first = a.q0 + row0;
+  const int64_t q_last = a.q0 + (row0 + BM < a.Lq ? row0 + BM : a.Lq) - 1;
+  const int n = (int)(q_first / a.c);  // rank that owns the first row
+  const int tpc = (int)(a.c / kTileKeys);
+
+  const uint16_t *Qh = a.Q + head * a.Lq * 64;
+  const uint16_t *Kh = a.K + head * a.L * 64;
+  const uint16_t *Vh = a.V + head * a.L * 64;
+
+  // Q^T operand: lane (col, half) holds Q[row][dk*16 + half*8 .. +8]
+  bf16x8 qreg[QB][4];
+  int64_t qrow[QB];  // local row (clamped to the last row for a ragged tail)
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    int64_t r = row0 + wave * R + qb * 32 + col;
+    qrow[qb] = r < a.Lq ? r : a.Lq - 1;
+#pragma unroll
+    for (int dk = 0; dk < 4; ++dk)
+      qreg[qb][dk] = *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * 64 + dk * 16 + half * 8);
+  }
+  const int64_t wq_first = a.q0 + (row0 + wave * R < a.Lq ? row0 + wave * R : a.Lq - 1);
+  const int64_t wq_last = a.q0 + (row0 + wave * R + R - 1 < a.Lq ? row0 + wave * R + R - 1 : a.Lq - 1);
+
+  const TileLanes tl(lane);
+  const int ld_row = tid >> 3, ld_ch = tid & 7;  // this thread's 16-byte pieces of a tile
+
+  f32x16 o[2][QB];
+  float m[QB], mc[QB], l[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    m[qb] = -INFINITY; mc[qb] = 0.f; l[qb] = 0.f;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[db][qb][v] = 0.f;
+  }
+
+  auto k0_of = [&](int t, int kt) -> int64_t {
+    int j = n - t;
+    if (j < 0) j += a.N;
+    return (int64_t)j * a.c + (int64_t)kt * kTileKeys;
+  };
+  // next tile of the ring walk that holds a visible key for some row of this work-group
+  auto advance = [&](int &t, int &kt) -> bool {
+    ++kt;
+    for (;;) {
+      if (kt >= tpc) { ++t; kt = 0; }
+      if (t >= a.N) return false;
+      if (!CAUSAL || k0_of(t, kt) <= q_last) return true;
+      kt = tpc;  // later tiles of this chunk start even further right
+    }
+  };
+
+  u32x4 kr[2], vr[2];
+  auto load_tile = [&](int64_t k0) {
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int64_t off = (k0 + ld_row + it * 32) * 64 + ld_ch * 8;
+      kr[it] = *reinterpret_cast<const u32x4 *>(Kh + off);
+      vr[it] = *reinterpret_cast<const u32x4 *>(Vh + off);
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int off = tile_off(ld_row + it * 32, ld_ch);
+      *reinterpret_cast<u32x4 *>(Ks[buf] + off) = kr[it];
+      *reinterpret_cast<u32x4 *>(Vs[buf] + off) = vr[it];
+    }
+  };
+
+  int t = 0, kt = 0, buf = 0;
+  load_tile(k0_of(0, 0));
+  store_tile(0);
+  __syncthreads();
+  bool have = true;
+  while (have) {
+    const int64_t k0 = k0_of(t, kt);
+    int t2 = t, kt2 = kt;
+    const bool have_next = advance(t2, kt2);
+    if (have_next) load_tile(k0_of(t2, kt2));
+
+    if (!CAUSAL || k0 <= wq_last) {
+      // ---- S^T = K Q^T
+      f32x16 s[2][QB];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        bf16x8 ka[4];
+#pragma unroll
+        for (int dk = 0; dk < 4; ++dk) ka[dk] = tl.read_rows(Ks[buf], kb * 32, dk);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) s[kb][qb][v] = 0.f;
+#pragma unroll
+          for (int dk = 0; dk < 4; ++dk) s[kb][qb] = mfma_32x32x16(ka[dk], qreg[qb][dk], s[kb][qb]);
+        }
+      }
+      if (CAUSAL && k0 + kTileKeys - 1 > wq_first) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+          const int64_t qg = a.q0 + qrow[qb];
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int64_t kg = k0 + kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+              if (kg > qg) s[kb][qb][v] = -INFINITY;
+            }
+        }
+      }
+      // ---- running max; the accumulators are rescaled only when some row's max
+      // grew by more than 2^8 in the exp2 domain (exact: l and O share the stale max)
+      float tm[QB];
+      bool need = false;
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        float x = s[0][qb][0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) x = fmaxf(x, s[0][qb][v]);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) x = fmaxf(x, s[1][qb][v]);
+        tm[qb] = xhalf_max(x);
+        need |= (tm[qb] - m[qb]) * a.cl2 > 8.0f;
+      }
+      if (__builtin_amdgcn_ballot_w64(need) != 0) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+          const float mn = fmaxf(m[qb], tm[qb]);
+          const float alpha = __builtin_amdgcn_exp2f((m[qb] - mn) * a.cl2);
+          m[qb] = mn;
+          mc[qb] = mn * a.cl2;
+          l[qb] *= alpha;
+#pragma unroll
+          for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][qb][v] *= alpha;
+        }
+      }
+      // ---- P^T = exp2(S^T cl2 - m cl2), packed to bf16 as the B operand
+      bf16x8 pf[QB][4];
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        float ls = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          float p[16];
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            p[v] = __builtin_amdgcn_exp2f(fmaf(s[kb][qb][v], a.cl2, -mc[qb]));
+            ls += p[v];
+          }
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            u32x4 w = {pack_bf16(p[u * 8 + 0], p[u * 8 + 1]), pack_bf16(p[u * 8 + 2], p[u * 8 + 3]),
+                       pack_bf16(p[u * 8 + 4], p[u * 8 + 5]), pack_bf16(p[u * 8 + 6], p[u * 8 + 7])};
+            pf[qb][kb * 2 + u] = __builtin_bit_cast(bf16x8, w);
+          }
+        }
+        l[qb] += ls;
+      }
+      // ---- O^T += V^T P^T
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const bf16x8 va = tl.read_cols(Vs[buf], kk * 16, db);
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) o[db][qb] = mfma_32x32x16(va, pf[qb][kk], o[db][qb]);
+        }
+    }
+
+    if (have_next) store_tile(buf ^ 1);
+    __syncthreads();
+    buf ^= 1; t = t2; kt = kt2; have = have_next;
+  }
+
+  // ---- epilogue: O = O^T / l, LSE = s m + ln l
+  uint16_t *Oh = a.O + head * a.Lq * 64;
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const float lt = xhalf_sum(l[qb]);
+    const float inv = 1.0f / lt;
+    const int64_t r = row0 + wave * R + qb * 32 + col;
+    if (r < a.Lq) {
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          u32x2 w = {pack_bf16(o[db][qb][g * 4 + 0] * inv, o[db][qb][g * 4 + 1] * inv),
+                     pack_bf16(o[db][qb][g * 4 + 2] * inv, o[db][qb][g * 4 + 3] * inv)};
+          *reinterpret_cast<u32x2 *>(Oh + r * 64 + db * 32 + g * 8 + half * 4) = w;
+        }
+      if (half == 0) a.LSE[head * a.Lq + r] = (mc[qb] + __builtin_amdgcn_logf(lt)) * kLn2;
+    }
+  }
+}
+
+template <int R>
+static hipError_t launch_fwd(const Dims &d, const FwdArgs &a, int64_t heads, hipStream_t st) {
+  dim3 grid((unsigned)(heads * a.tiles_per_head));
+  if (d.causal)
+    hipLaunchKernelGGL((fused_fwd_kernel<R, true>), grid, dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL((fused_fwd_kernel<R, false>), grid, dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void *V, void *O,
+                         float *LSE, hipStream_t st) {
+  FwdArgs a;
+  a.Q = (const uint16_t *)Q; a.K = (const uint16_t *)K; a.V = (const uint16_t *)V;
+  a.O = (uint16_t *)O; a.LSE = LSE;
+  a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.q0 = (int64_t)d.rank_begin * d.c;
+  a.N = d.N;
+  a.cl2 = d.scale * kLog2e;
+  const int64_t heads = (int64_t)d.B * d.Z;
+  // 64 rows per wave halves the LDS traffic per flop; 32 rows per wave gives
+  // twice the work-groups when the problem is too small to fill 256 CUs twice over.
+  const bool big = (d.Lq % 256 == 0) && heads * (d.Lq / 256) >= 512;
+  if (big) {
+    a.tiles_per_head = (int)(d.Lq / 256);
+    return launch_fwd<64>(d, a, heads, st);
+  }
+  a.tiles_per_head = (int)((d.Lq + 127) / 128);
+  return launch_fwd<32>(d, a, heads, st);
+}
+
+}  // namespace rsa

@@ -1,0 +1,66 @@
+// LDS tile layout shared by the fused RSA kernels: a tile is 64 rows (tokens)
+// by 64 bf16 (the head dimension A), 8 KiB, with no padding.  Row r occupies
+// bytes [128 r, 128 r + 128); inside the row the eight 16-byte chunks are
+// permuted: logical chunk cc sits at position cc ^ rot3((r >> 1) & 7), where
+// rot3 rotates a 3-bit value right by one.  With 64 four-byte banks this makes
+// all three access patterns conflict-free:
+//   * the 16-byte stores of the global->LDS copy (a 16-lane phase is 2 rows x 8 chunks),
+//   * 16-byte MFMA operand reads along a row (a phase is 16 consecutive rows, one chunk),
+//   * 8-byte transpose reads (a 32-lane phase is 4 rows x 4 chunks).
+#pragma once
+#include "rsa_common.h"
+
+namespace rsa {
+
+constexpr int kTileKeys = 64;
+constexpr int kTileBytes = 64 * 64 * 2;
+
+__device__ __forceinline__ int swz_rot(int row) {
+  const int t = (row >> 1) & 7;
+  return ((t & 1) << 2) | (t >> 1);
+}
+// byte offset of 16-byte chunk `cc` (elements 8 cc .. 8 cc + 7) of row `row`
+__device__ __forceinline__ int tile_off(int row, int cc) {
+  return row * 128 + ((cc ^ swz_rot(row)) << 4);
+}
+
+// Per-lane byte offsets for the two kinds of MFMA operand fetch from a tile.
+struct TileLanes {
+  int rows_off[4];     // [dk]
+  int cols_off[2][2];  // [db][e8]
+
+  __device__ __forceinline__ explicit TileLanes(int lane) {
+    const int col = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int dk = 0; dk < 4; ++dk) rows_off[dk] = tile_off(col, dk * 2 + half);
+    const int g = lane >> 4, j = lane & 15;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int e8 = 0; e8 < 2; ++e8) {
+        const int row = e8 * 8 + half * 4 + (j >> 2);
+        const int cc = db * 4 + (g & 1) * 2 + ((j >> 1) & 1);
+        cols_off[db][e8] = tile_off(row, cc) + (j & 1) * 8;
+      }
+  }
+
+  // Operand whose MFMA row/column index runs over tile rows: lane (col, half)
+  // gets tile[row_base + col][dk*16 + half*8 .. +8].  row_base: multiple of 32.
+  __device__ __forceinline__ bf16x8 read_rows(const unsigned char *tile, int row_base, int dk) const {
+    return *reinterpret_cast<const bf16x8 *>(tile + row_base * 128 + rows_off[dk]);
+  }
+
+  // Operand whose MFMA row index runs over the head dimension and whose k
+  // index runs over 16 tile rows: lane (col, half) gets, for e = 0..7,
+  //   tile[row_base + (e>>2)*8 + half*4 + (e&3)][db*32 + col],
+  // which is the k order in which a 32x32 accumulator holds its rows
+  // (elements u*8 .. u*8+7 of lane-half `half`).  row_base: multiple of 16.
+  __device__ __forceinline__ bf16x8 read_cols(const unsigned char *tile, int row_base, int db) const {
+    const u32x2 lo = lds_read_tr16(tile + row_base * 128 + cols_off[db][0]);
+    const u32x2 hi = lds_read_tr16(tile + row_base * 128 + cols_off[db][1]);
+    const u32x4 w = {lo[0], lo[1], hi[0], hi[1]};
+    return __builtin_bit_cast(bf16x8, w);
+  }
+};
+
+}  // namespace rsa

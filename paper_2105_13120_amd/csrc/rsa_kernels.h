@@ -1,0 +1,40 @@
+// Internal launch functions of the RSA library (host side).  Each returns the
+// hipError_t of its launch.  Arguments are assumed validated by the C ABI layer.
+#pragma once
+#include "rsa_common.h"
+
+namespace rsa {
+
+// --- staged (two-pass) steps: section 3.1 stage 1, Eq. 1's softmax, Eq. 3 ---
+hipError_t staged_qk_step(const Dims &d, int dtype, int n, int j, const void *Q, const void *K,
+                          float *S, hipStream_t st);
+hipError_t staged_row_softmax(const Dims &d, int dtype, int n, const float *S, void *P, float *LSE,
+                              hipStream_t st);
+hipError_t staged_av_step(const Dims &d, int dtype, int n, int j, const void *P, const void *V,
+                          float *Oacc, int accumulate, hipStream_t st);
+hipError_t staged_dv_step(const Dims &d, int dtype, int n, int j, const void *P, const void *dO,
+                          float *dVacc, int accumulate, hipStream_t st);
+hipError_t staged_dp_step(const Dims &d, int dtype, int n, int j, const void *dO, const void *V,
+                          float *dP, hipStream_t st);
+hipError_t staged_softmax_bwd(const Dims &d, int dtype, int n, const void *P, const float *dP,
+                              const float *D, void *dS, hipStream_t st);
+hipError_t staged_dq_step(const Dims &d, int dtype, int n, int j, const void *dS, const void *K,
+                          float *dQacc, int accumulate, hipStream_t st);
+hipError_t staged_dk_step(const Dims &d, int dtype, int n, int j, const void *dS, const void *Q,
+                          float *dKacc, int accumulate, hipStream_t st);
+// D rows [row_off, row_off + rows_per_head) of every head: D_i = sum_a dO_ia O_ia
+hipError_t rowdot(const Dims &d, int dtype, int64_t row_off, int64_t rows_per_head, const void *dO,
+                  const void *O, float *D, hipStream_t st);
+// dst[b][r][:] (dtype) = src[b][r][:] (fp32); rows of `cols` elements, batch strides in elements
+hipError_t store_rows(int dtype, const float *src, void *dst, int64_t batches,
+                      int64_t rows_per_batch, int64_t cols, int64_t src_batch, int64_t dst_batch,
+                      hipStream_t st);
+
+// --- fused (online-softmax) path, bf16, A = 64 ---
+hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void *V, void *O,
+                         float *LSE, hipStream_t st);
+hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const void *K,
+                          const void *V, const void *O, const float *LSE, void *dQ, void *dK,
+                          void *dV, float *D, hipStream_t st);
+
+}  // namespace rsa

@@ -1,0 +1,192 @@
+"""ctypes binding of the RSA C ABI (include/rsa.h): argument marshalling only.
+
+Every step of the path runs in the HIP library.  PyTorch supplies device
+memory and the current stream; nothing here computes.  If the library has not
+been built the calls raise -- there is no fallback.
+"""
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "librsa_hip.so")
+
+RSA_F32, RSA_BF16 = 0, 1
+MODE_FUSED, MODE_STAGED = 0, 1
+
+EXPORTS = (
+    "rsa_version", "rsa_strerror", "rsa_workspace_bytes", "rsa_forward", "rsa_backward",
+    "rsa_qk_step", "rsa_row_softmax", "rsa_av_step", "rsa_bwd_rowdot", "rsa_dv_step",
+    "rsa_dp_step", "rsa_softmax_bwd", "rsa_dq_step", "rsa_dk_step", "rsa_store",
+)
+
+
+class RSADesc(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("Z", ctypes.c_int32), ("A", ctypes.c_int32),
+        ("L", ctypes.c_int64), ("N", ctypes.c_int32),
+        ("rank_begin", ctypes.c_int32), ("rank_end", ctypes.c_int32),
+        ("causal", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("scale", ctypes.c_float), ("flags", ctypes.c_uint32),
+    ]
+
+
+class RSAError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"rsa status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """The loaded HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                "(python -m paper_2105_13120_amd.build); there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        dp = ctypes.POINTER(RSADesc)
+        L.rsa_version.restype = i
+        L.rsa_strerror.restype = ctypes.c_char_p
+        L.rsa_strerror.argtypes = [i]
+        L.rsa_workspace_bytes.restype = sz
+        L.rsa_workspace_bytes.argtypes = [dp, i]
+        L.rsa_forward.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.rsa_backward.argtypes = [dp] + [vp] * 10 + [sz, vp]
+        L.rsa_qk_step.argtypes = [dp, i, i, vp, vp, vp, vp]
+        L.rsa_row_softmax.argtypes = [dp, i, vp, vp, vp, vp]
+        L.rsa_av_step.argtypes = [dp, i, i, vp, vp, vp, i, vp]
+        L.rsa_bwd_rowdot.argtypes = [dp, i, vp, vp, vp, vp]
+        L.rsa_dv_step.argtypes = [dp, i, i, vp, vp, vp, i, vp]
+        L.rsa_dp_step.argtypes = [dp, i, i, vp, vp, vp, vp]
+        L.rsa_softmax_bwd.argtypes = [dp, i, vp, vp, vp, vp, vp]
+        L.rsa_dq_step.argtypes = [dp, i, i, vp, vp, vp, i, vp]
+        L.rsa_dk_step.argtypes = [dp, i, i, vp, vp, vp, i, vp]
+        L.rsa_store.argtypes = [dp, vp, vp, sz, vp]
+        for name in EXPORTS[3:]:
+            getattr(L, name).restype = i
+        _lib = L
+    return _lib
+
+
+def strerror(status):
+    return lib().rsa_strerror(int(status)).decode()
+
+
+def _check(status):
+    if status != 0:
+        raise RSAError(status, strerror(status))
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _p(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _dtype_code(t):
+    if t.dtype == torch.bfloat16:
+        return RSA_BF16
+    if t.dtype == torch.float32:
+        return RSA_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def make_desc(K, N, causal=False, rank_begin=0, rank_end=None, mode=MODE_FUSED, scale=0.0):
+    """Descriptor for K of shape (B, Z, L, A)."""
+    B, Z, L, A = K.shape
+    return RSADesc(B, Z, A, L, N, rank_begin, N if rank_end is None else rank_end,
+                   int(bool(causal)), _dtype_code(K), float(scale), int(mode))
+
+
+def workspace_bytes(desc, backward):
+    return int(lib().rsa_workspace_bytes(ctypes.byref(desc), 1 if backward else 0))
+
+
+def _workspace(desc, backward, device):
+    n = workspace_bytes(desc, backward)
+    ws = torch.empty(max(n, 16), dtype=torch.uint8, device=device)
+    return ws, n
+
+
+def forward(desc, Q, K, V, O=None, LSE=None, ws=None):
+    """rsa_forward.  Q: (B,Z,Lq,A); K, V: (B,Z,L,A).  Returns (O, LSE)."""
+    for t in (Q, K, V):
+        assert t.is_cuda and t.is_contiguous()
+    if O is None:
+        O = torch.empty_like(Q)
+    if LSE is None:
+        LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device)
+    if ws is None:
+        ws, n = _workspace(desc, False, Q.device)
+    else:
+        n = ws.numel()
+    _check(lib().rsa_forward(ctypes.byref(desc), _p(Q), _p(K), _p(V), _p(O), _p(LSE),
+                             _p(ws), n, _stream()))
+    return O, LSE
+
+
+def backward(desc, dO, Q, K, V, O, LSE, dQ=None, dK=None, dV=None, ws=None):
+    """rsa_backward.  Returns (dQ, dK, dV)."""
+    for t in (dO, Q, K, V, O, LSE):
+        assert t.is_cuda and t.is_contiguous()
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dK = torch.empty_like(K) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    if ws is None:
+        ws, n = _workspace(desc, True, Q.device)
+    else:
+        n = ws.numel()
+    _check(lib().rsa_backward(ctypes.byref(desc), _p(dO), _p(Q), _p(K), _p(V), _p(O), _p(LSE),
+                              _p(dQ), _p(dK), _p(dV), _p(ws), n, _stream()))
+    return dQ, dK, dV
+
+
+# ---- step-level calls (one ring step of one simulated rank) ----
+
+def qk_step(desc, n, j, Q, K, S):
+    _check(lib().rsa_qk_step(ctypes.byref(desc), n, j, _p(Q), _p(K), _p(S), _stream()))
+
+
+def row_softmax(desc, n, S, P, LSE):
+    _check(lib().rsa_row_softmax(ctypes.byref(desc), n, _p(S), _p(P), _p(LSE), _stream()))
+
+
+def av_step(desc, n, j, P, V, Oacc, accumulate):
+    _check(lib().rsa_av_step(ctypes.byref(desc), n, j, _p(P), _p(V), _p(Oacc), int(accumulate), _stream()))
+
+
+def bwd_rowdot(desc, n, dO, O, D):
+    _check(lib().rsa_bwd_rowdot(ctypes.byref(desc), n, _p(dO), _p(O), _p(D), _stream()))
+
+
+def dv_step(desc, n, j, P, dO, dVacc, accumulate):
+    _check(lib().rsa_dv_step(ctypes.byref(desc), n, j, _p(P), _p(dO), _p(dVacc), int(accumulate), _stream()))
+
+
+def dp_step(desc, n, j, dO, V, dP):
+    _check(lib().rsa_dp_step(ctypes.byref(desc), n, j, _p(dO), _p(V), _p(dP), _stream()))
+
+
+def softmax_bwd(desc, n, P, dP, D, dS):
+    _check(lib().rsa_softmax_bwd(ctypes.byref(desc), n, _p(P), _p(dP), _p(D), _p(dS), _stream()))
+
+
+def dq_step(desc, n, j, dS, K, dQacc, accumulate):
+    _check(lib().rsa_dq_step(ctypes.byref(desc), n, j, _p(dS), _p(K), _p(dQacc), int(accumulate), _stream()))
+
+
+def dk_step(desc, n, j, dS, Q, dKacc, accumulate):
+    _check(lib().rsa_dk_step(ctypes.byref(desc), n, j, _p(dS), _p(Q), _p(dKacc), int(accumulate), _stream()))
+
+
+def store(desc, src, dst):
+    _check(lib().rsa_store(ctypes.byref(desc), _p(src), _p(dst), src.numel(), _stream()))

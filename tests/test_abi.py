@@ -1,0 +1,84 @@
+"""The C-ABI library loads, exports every symbol the header declares, and
+rejects bad arguments on the host before anything is launched (CPU only)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2105_13120_amd import rsa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "rsa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rsa_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert set(names) == set(rsa.EXPORTS)
+    L = rsa.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert L.rsa_version() >= 100
+
+
+def desc(**kw):
+    d = dict(B=1, Z=2, A=64, L=256, N=4, rank_begin=0, rank_end=4, causal=0,
+             dtype=rsa.RSA_BF16, scale=0.0, flags=rsa.MODE_FUSED)
+    d.update(kw)
+    return rsa.RSADesc(**d)
+
+
+def fwd_status(d, ptr=0x1000, ws=0x1000, ws_bytes=1 << 40):
+    p = ctypes.c_void_p(ptr)
+    return rsa.lib().rsa_forward(ctypes.byref(d), p, p, p, p, p, ctypes.c_void_p(ws), ws_bytes, None)
+
+
+def test_validation_happens_before_any_launch():
+    # every call below must return on the host: the pointers are not device memory
+    assert fwd_status(desc(N=3)) == -2                       # L % N != 0
+    assert fwd_status(desc(L=0)) == -2
+    assert fwd_status(desc(rank_begin=2, rank_end=2)) == -2
+    assert fwd_status(desc(rank_end=5)) == -2
+    assert fwd_status(desc(A=128)) == -3
+    assert fwd_status(desc(L=128, N=4)) == -3                # c = 32 not a multiple of 64
+    assert fwd_status(desc(dtype=7)) == -3
+    assert fwd_status(desc(dtype=rsa.RSA_F32)) == -3         # fused mode is bf16 only
+    assert fwd_status(desc(flags=9)) == -3
+    assert fwd_status(desc(), ptr=0) == -1
+    assert fwd_status(desc(), ptr=0x1008) == -3              # misaligned
+    staged = desc(flags=rsa.MODE_STAGED)
+    assert rsa.workspace_bytes(staged, False) > 0
+    assert fwd_status(staged, ws=0) == -4
+    assert fwd_status(staged, ws_bytes=16) == -4
+    assert rsa.lib().rsa_forward(None, None, None, None, None, None, None, 0, None) == -1
+    p = ctypes.c_void_p(0x1000)
+    bwd = rsa.lib().rsa_backward(ctypes.byref(desc()), p, p, p, p, p, p, p, p, p, None, 0, None)
+    assert bwd == -4                                          # backward always needs D
+    step = rsa.lib().rsa_qk_step(ctypes.byref(staged), 4, 0, p, p, p, None)
+    assert step == -2                                         # rank outside [begin, end)
+    step = rsa.lib().rsa_qk_step(ctypes.byref(staged), 0, 7, p, p, p, None)
+    assert step == -2
+
+
+def test_workspace_sizes_follow_table2():
+    # staged forward keeps the rank's strip: B*Z*(L/N)*L scores (Table 2, Ring-QK^T row)
+    d = desc(B=2, Z=3, L=512, N=4, flags=rsa.MODE_STAGED)
+    strip = 2 * 3 * 128 * 512
+    assert rsa.workspace_bytes(d, False) >= strip * 4 + strip * 2
+    assert rsa.workspace_bytes(desc(), False) == 0            # fused forward: no strip
+    assert rsa.workspace_bytes(desc(), True) == 1 * 2 * 256 * 4
+    assert rsa.workspace_bytes(desc(N=3), True) == 0          # invalid descriptor
+    for s in range(-5, 1):
+        assert rsa.strerror(s)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(rsa, "_lib", None)
+    monkeypatch.setattr(rsa, "LIB_PATH", "/nonexistent/librsa_hip.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        rsa.lib()

@@ -1,0 +1,65 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import (BF16_REL_RMS, LSE_ATOL, check, compare_heads, download, gpu_forward_backward,
+                     heads_view)
+from paper_2105_13120_amd import inputs, rsa
+
+pytestmark = pytest.mark.gpu
+
+
+def test_bert_base_all_heads_sampled():
+    cfg = inputs.CONFIGS["bert_base"]
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x)
+    heads = [0, 1, 11, 12, 95, 96, 190, 191]
+    print(compare_heads(cfg, x, out, heads))
+
+
+def test_bert_large_sampled_heads():
+    cfg = inputs.CONFIGS["bert_large"]
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x)
+    print(compare_heads(cfg, x, out, [0, 15, 64, 127]))
+
+
+def sampled_check(cfg, x, out, head, row_blocks, cols):
+    """One head of a long configuration: O/LSE/dQ on row blocks, dK/dV on key columns."""
+    Kh, Vh = heads_view(x["K"], [head]), heads_view(x["V"], [head])
+    Qh, dOh = heads_view(x["Q"], [head]), heads_view(x["dO"], [head])
+    O, LSE, dQ = (download(out[k]) for k in ("O", "LSE", "dQ"))
+    O = O.reshape(-1, cfg.Lq, 64)[head]
+    dQ = dQ.reshape(-1, cfg.Lq, 64)[head]
+    LSE = LSE.reshape(-1, cfg.Lq)[head]
+    # the RMS that normalises the error is that of the whole head, from the full backward below
+    dQ_ref, dK_ref, dV_ref = oracle.backward(Qh, Kh, Vh, dOh, q0=cfg.q0, causal=cfg.causal, cols=cols)
+    check("dQ", dQ[None, None], dQ_ref, cfg.dtype)
+    dK = download(out["dK"]).reshape(-1, cfg.L, 64)[head][cols]
+    dV = download(out["dV"]).reshape(-1, cfg.L, 64)[head][cols]
+    check("dK", dK[None, None], dK_ref, cfg.dtype)
+    check("dV", dV[None, None], dV_ref, cfg.dtype)
+    for r0, nr in row_blocks:
+        O_ref, LSE_ref = oracle.forward(Qh[:, :, r0:r0 + nr], Kh, Vh, q0=cfg.q0 + r0, causal=cfg.causal)
+        check("O", O[None, None, r0:r0 + nr], O_ref, cfg.dtype)
+        assert np.abs(LSE[r0:r0 + nr] - LSE_ref[0, 0]).max() <= LSE_ATOL
+
+
+def test_long_32k_sampled():
+    cfg = inputs.CONFIGS["long_32k"]
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x)
+    rng = np.random.Generator(np.random.PCG64(1))
+    cols = np.concatenate([[0, 63, 64, 2047, 2048, 32767], rng.integers(0, cfg.L, 250)])
+    sampled_check(cfg, x, out, head=5, row_blocks=[(0, 64), (2016, 64), (32768 - 96, 96)], cols=cols)
+
+
+def test_rank15_of_64k_causal_sampled():
+    cfg = inputs.CONFIGS["rank15_64k_causal"]
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x)
+    rng = np.random.Generator(np.random.PCG64(2))
+    cols = np.concatenate([[0, 4095, 4096, 61439, 61440, 61503, 65535],
+                           rng.integers(0, cfg.L, 150), rng.integers(61440, cfg.L, 100)])
+    sampled_check(cfg, x, out, head=11, row_blocks=[(0, 64), (2000, 100), (4096 - 64, 64)], cols=cols)
