@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the RSA hot path on one MI355X: one step = rsa_forward + rsa_backward
+(fused mode) over one batch of synthetic BERT-shaped Q, K, V, dO resident in HBM.
+
+Prints ONE JSON line.  `value` is algorithmic TFLOP/s: 12 * B * Z * A * (visible
+query-key pairs) flops per step (4 forward: QK^T, PV; 8 backward: dV, dP, dQ, dK;
+recomputation and softmax flops are not credited) over the wall time of the timed
+steps.  `roofline` prices the dominant kernel (the fused dK/dV kernel) against
+the bf16 dense MFMA peak; `cpu_baseline` times the fp64 oracle on the host cores
+on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs (see profiles/); None until measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="bert_large",
+                    choices=["bert_base", "bert_large", "long_32k", "rank15_64k_causal"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all", action="store_true", help="also time the other workloads briefly")
+    return ap.parse_args()
+
+
+def event_ms(fn, iters, torch):
+    """Average duration of fn() in ms, HIP events on the current stream."""
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    s.record()
+    for _ in range(iters):
+        fn()
+    e.record()
+    e.synchronize()
+    return s.elapsed_time(e) / iters
+
+
+def setup(cfg, torch, rsa, inputs):
+    x = inputs.make_inputs(cfg)
+    dt = torch.bfloat16
+    t = {k: torch.from_numpy(v).to(dt).cuda().contiguous() for k, v in x.items()}
+    rb, re = cfg.ranks
+    desc = rsa.make_desc(t["K"], cfg.N, causal=cfg.causal, rank_begin=rb, rank_end=re)
+    buf = dict(
+        O=torch.empty_like(t["Q"]), LSE=torch.empty(t["Q"].shape[:3], dtype=torch.float32, device="cuda"),
+        dQ=torch.empty_like(t["Q"]), dK=torch.empty_like(t["K"]), dV=torch.empty_like(t["V"]),
+        ws=torch.empty(max(rsa.workspace_bytes(desc, True), 16), dtype=torch.uint8, device="cuda"),
+    )
+    return x, t, desc, buf
+
+
+def time_workload(cfg, steps, warmup, torch, rsa, inputs, per_kernel=True):
+    x, t, desc, b = setup(cfg, torch, rsa, inputs)
+
+    def fwd():
+        rsa.forward(desc, t["Q"], t["K"], t["V"], O=b["O"], LSE=b["LSE"])
+
+    def bwd():
+        rsa.backward(desc, t["dO"], t["Q"], t["K"], t["V"], b["O"], b["LSE"],
+                     dQ=b["dQ"], dK=b["dK"], dV=b["dV"], ws=b["ws"])
+
+    def step():
+        fwd()
+        bwd()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    res = {"ms_per_step": ms, "tflops": cfg.flops() / (ms * 1e-3) / 1e12,
+           "tokens_per_s": cfg.B * cfg.Lq / (ms * 1e-3)}
+    if per_kernel:
+        D = b["ws"][: cfg.B * cfg.Z * cfg.Lq * 4].view(torch.float32)
+        it = max(3, min(steps, 20))
+        k = {
+            "fwd": event_ms(fwd, it, torch),
+            "bwd_rowdot": event_ms(lambda: rsa.bwd_rowdot(desc, -1, t["dO"], b["O"], D), it, torch),
+            "bwd_dkdv": event_ms(lambda: rsa.bwd_dkdv(desc, t["dO"], t["Q"], t["K"], t["V"], b["LSE"], D,
+                                                      b["dK"], b["dV"]), it, torch),
+            "bwd_dq": event_ms(lambda: rsa.bwd_dq(desc, t["dO"], t["Q"], t["K"], t["V"], b["LSE"], D,
+                                                  b["dQ"]), it, torch),
+        }
+        res["kernel_ms"] = k
+    return res, x
+
+
+def cpu_baseline(cfg, x, inputs):
+    """The fp64 oracle, as it stands, on a bounded head sample of the same workload."""
+    import numpy as np
+    import oracle
+    heads_total = cfg.B * cfg.Z
+    per_head = 18.0 * cfg.A * cfg.visible_pairs()        # fp64 flops the oracle executes per head
+    heads = int(max(1, min(heads_total, round(2.5e12 / per_head))))   # about 10-30 s of host work
+    sel = lambda a: np.ascontiguousarray(
+        a.reshape(heads_total, a.shape[2], a.shape[3])[:heads][None].astype(np.float64))
+    Q, K, V, dO = (sel(x[k]) for k in ("Q", "K", "V", "dO"))
+    t0 = time.perf_counter()
+    oracle.forward(Q, K, V, q0=cfg.q0, causal=cfg.causal)
+    oracle.backward(Q, K, V, dO, q0=cfg.q0, causal=cfg.causal)
+    dt = time.perf_counter() - t0
+    flops = 12.0 * heads * cfg.A * cfg.visible_pairs()
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"first {heads} of {heads_total} (batch, head) pairs of {cfg.name}, fwd+bwd, "
+                      f"fp64, {dt:.1f} s"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only; the ring's ranks are simulated as chunk "
+              "iterations on that GPU (--gpus must be 1)", file=sys.stderr)
+        return 2
+    import torch
+    from paper_2105_13120_amd import inputs, rsa
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    rsa.lib()   # fails loudly if the HIP library is not built
+    cfg = inputs.CONFIGS[a.workload]
+    res, x = time_workload(cfg, a.steps, a.warmup, torch, rsa, inputs)
+    k = res["kernel_ms"]
+    # dominant kernel: dK/dV.  Algorithmic flops per launch: the dV, dK and dP
+    # contractions, 3 * 2 * B*Z*A*pairs (its S recompute is not credited).
+    dkdv_flops = 6.0 * cfg.B * cfg.Z * cfg.A * cfg.visible_pairs()
+    achieved = dkdv_flops / (k["bwd_dkdv"] * 1e-3) / 1e12
+    out = {
+        "metric": "rsa_fwd_bwd_tflops", "value": round(res["tflops"], 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(res["ms_per_step"], 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "B": cfg.B, "Z": cfg.Z, "L": cfg.L, "A": cfg.A, "N": cfg.N,
+                   "chunk": cfg.c, "causal": cfg.causal, "ranks": list(cfg.ranks), "mode": "fused"},
+        "frac_of_bf16_peak": round(res["tflops"] / PEAK_BF16_TFLOPS, 4),
+        "tokens_per_s": round(res["tokens_per_s"], 1),
+        "kernel_ms": {n: round(v, 4) for n, v in k.items()},
+        "roofline": {"bound": "mfma", "kernel": "fused_bwd_dkdv_kernel", "achieved": round(achieved, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name)},
+    }
+    if a.all:
+        other = {}
+        for name in ("bert_base", "bert_large", "long_32k", "rank15_64k_causal"):
+            if name == cfg.name:
+                continue
+            c2 = inputs.CONFIGS[name]
+            r2, _ = time_workload(c2, 5, 2, torch, rsa, inputs)
+            other[name] = {"tflops": round(r2["tflops"], 2), "ms_per_step": round(r2["ms_per_step"], 4),
+                           "kernel_ms": {n: round(v, 4) for n, v in r2["kernel_ms"].items()}}
+        out["other_workloads"] = other
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, x, inputs)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

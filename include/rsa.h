@@ -114,7 +114,8 @@ int rsa_row_softmax(const rsa_desc *d, int n, const float *S, void *P,
 /* Stage 2 (Eq. 3): Oacc (+)= P^n_j V^j. */
 int rsa_av_step(const rsa_desc *d, int n, int j, const void *P, const void *V,
                 float *Oacc, int accumulate, void *stream);
-/* D_i = sum_a dO_ia O_ia for the rows of rank n. */
+/* D_i = sum_a dO_ia O_ia for the rows of rank n; n = -1: every rank in
+ * [rank_begin, rank_end). */
 int rsa_bwd_rowdot(const rsa_desc *d, int n, const void *dO, const void *O,
                    float *D, void *stream);
 /* dVacc^j (+)= (P^n_j)^T dO^n. */
@@ -135,6 +136,22 @@ int rsa_dk_step(const rsa_desc *d, int n, int j, const void *dS, const void *Q,
 /* dst (d->dtype) = src (fp32), `count` elements: stores an accumulator. */
 int rsa_store(const rsa_desc *d, const float *src, void *dst, size_t count,
               void *stream);
+
+/*
+ * The two kernels of the fused backward on their own (bf16, fused mode), for
+ * profiling and tests; rsa_backward = rsa_bwd_rowdot(n = -1) + these two.
+ * Both recompute P = exp(s Q K^T - LSE) tile by tile.
+ *  rsa_bwd_dkdv: for every key chunk, the walk over the query rows of all
+ *    simulated ranks -- dV = sum_n P^T dO, dK = s sum_n dS^T Q (the sums the
+ *    ring all-reduces, section 3.2.2).  Also forms dP = dO V^T for its tiles.
+ *  rsa_bwd_dq: for every rank, the K ring pass dQ^n = s sum_j dS^n_j K^j.
+ */
+int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *Q, const void *K,
+                 const void *V, const float *LSE, const float *D, void *dK,
+                 void *dV, void *stream);
+int rsa_bwd_dq(const rsa_desc *d, const void *dO, const void *Q, const void *K,
+               const void *V, const float *LSE, const float *D, void *dQ,
+               void *stream);
 
 #ifdef __cplusplus
 }

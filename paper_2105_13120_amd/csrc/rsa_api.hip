@@ -244,6 +244,7 @@ int rsa_av_step(const rsa_desc *d, int n, int j, const void *P, const void *V, f
 
 int rsa_bwd_rowdot(const rsa_desc *d, int n, const void *dO, const void *O, float *D, void *stream) {
   RSA_STEP_PROLOGUE(dO && O && D, dO, O, D);
+  if (n == -1) return hip_status(rsa::rowdot(dm, d->dtype, 0, dm.Lq, dO, O, D, st));
   if ((rc = check_rank_chunk(dm, n, 0)) != RSA_OK) return rc;
   return hip_status(rsa::rowdot(dm, d->dtype, (int64_t)(n - dm.rank_begin) * dm.c, dm.c, dO, O, D, st));
 }
@@ -286,6 +287,20 @@ int rsa_store(const rsa_desc *d, const float *src, void *dst, size_t count, void
   RSA_STEP_PROLOGUE(src && dst, src, dst);
   if (count % 4 != 0) return RSA_ERR_SHAPE;
   return hip_status(rsa::store_rows(d->dtype, src, dst, 1, 1, (int64_t)count, 0, 0, st));
+}
+
+int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *Q, const void *K, const void *V,
+                 const float *LSE, const float *D, void *dK, void *dV, void *stream) {
+  RSA_STEP_PROLOGUE(dO && Q && K && V && LSE && D && dK && dV, dO, Q, K, V, LSE, D, dK, dV);
+  if (d->dtype != RSA_BF16 || d->flags != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
+  return hip_status(rsa::fused_bwd_dkdv(dm, dO, Q, K, V, LSE, D, dK, dV, st));
+}
+
+int rsa_bwd_dq(const rsa_desc *d, const void *dO, const void *Q, const void *K, const void *V,
+               const float *LSE, const float *D, void *dQ, void *stream) {
+  RSA_STEP_PROLOGUE(dO && Q && K && V && LSE && D && dQ, dO, Q, K, V, LSE, D, dQ);
+  if (d->dtype != RSA_BF16 || d->flags != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
+  return hip_status(rsa::fused_bwd_dq(dm, dO, Q, K, V, LSE, D, dQ, st));
 }
 
 }  // extern "C"

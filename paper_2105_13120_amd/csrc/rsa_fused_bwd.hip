@@ -383,39 +383,52 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   }
 }
 
-hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const void *K,
-                          const void *V, const void *O, const float *LSE, void *dQ, void *dK,
-                          void *dV, float *D, hipStream_t st) {
-  hipError_t e = rowdot(d, RSA_BF16, 0, d.Lq, dO, O, D, st);
-  if (e != hipSuccess) return e;
+static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const void *K,
+                             const void *V, const float *LSE, const float *D, void *dQ, void *dK,
+                             void *dV) {
   BwdArgs a;
   a.Q = (const uint16_t *)Q; a.K = (const uint16_t *)K; a.V = (const uint16_t *)V;
   a.dO = (const uint16_t *)dO; a.LSE = LSE; a.D = D;
   a.dQ = (uint16_t *)dQ; a.dK = (uint16_t *)dK; a.dV = (uint16_t *)dV;
   a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.q0 = (int64_t)d.rank_begin * d.c;
   a.N = d.N; a.cl2 = d.scale * kLog2e; a.scale = d.scale;
-  const int64_t heads = (int64_t)d.B * d.Z;
+  a.tiles_per_head = 0;
+  return a;
+}
 
+hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Q, const void *K,
+                          const void *V, const float *LSE, const float *D, void *dK, void *dV,
+                          hipStream_t st) {
+  BwdArgs a = make_bwd_args(d, dO, Q, K, V, LSE, D, nullptr, dK, dV);
   a.tiles_per_head = (int)((d.L + 255) / 256);
-  {
-    dim3 grid((unsigned)(heads * a.tiles_per_head));
-    if (d.causal)
-      hipLaunchKernelGGL((fused_bwd_dkdv_kernel<true>), grid, dim3(256), 0, st, a);
-    else
-      hipLaunchKernelGGL((fused_bwd_dkdv_kernel<false>), grid, dim3(256), 0, st, a);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
+  dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head));
+  if (d.causal)
+    hipLaunchKernelGGL((fused_bwd_dkdv_kernel<true>), grid, dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL((fused_bwd_dkdv_kernel<false>), grid, dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void *K, const void *V,
+                        const float *LSE, const float *D, void *dQ, hipStream_t st) {
+  BwdArgs a = make_bwd_args(d, dO, Q, K, V, LSE, D, dQ, nullptr, nullptr);
   a.tiles_per_head = (int)((d.Lq + 127) / 128);
-  {
-    dim3 grid((unsigned)(heads * a.tiles_per_head));
-    if (d.causal)
-      hipLaunchKernelGGL((fused_bwd_dq_kernel<32, true>), grid, dim3(256), 0, st, a);
-    else
-      hipLaunchKernelGGL((fused_bwd_dq_kernel<32, false>), grid, dim3(256), 0, st, a);
-    e = hipGetLastError();
-  }
-  return e;
+  dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head));
+  if (d.causal)
+    hipLaunchKernelGGL((fused_bwd_dq_kernel<32, true>), grid, dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL((fused_bwd_dq_kernel<32, false>), grid, dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const void *K,
+                          const void *V, const void *O, const float *LSE, void *dQ, void *dK,
+                          void *dV, float *D, hipStream_t st) {
+  hipError_t e = rowdot(d, RSA_BF16, 0, d.Lq, dO, O, D, st);
+  if (e != hipSuccess) return e;
+  e = fused_bwd_dkdv(d, dO, Q, K, V, LSE, D, dK, dV, st);
+  if (e != hipSuccess) return e;
+  return fused_bwd_dq(d, dO, Q, K, V, LSE, D, dQ, st);
 }
 
 }  // namespace rsa
