@@ -89,14 +89,14 @@ def time_workload(cfg, steps, warmup, torch, rsa, inputs, per_kernel=True):
     res = {"ms_per_step": ms, "tflops": cfg.flops() / (ms * 1e-3) / 1e12,
            "tokens_per_s": cfg.B * cfg.Lq / (ms * 1e-3)}
     if per_kernel:
-        D = b["ws"][: cfg.B * cfg.Z * cfg.Lq * 4].view(torch.float32)
         it = max(3, min(steps, 20))
         k = {
             "fwd": event_ms(fwd, it, torch),
-            "bwd_rowdot": event_ms(lambda: rsa.bwd_rowdot(desc, -1, t["dO"], b["O"], D), it, torch),
-            "bwd_dkdv": event_ms(lambda: rsa.bwd_dkdv(desc, t["dO"], t["Q"], t["K"], t["V"], b["LSE"], D,
+            "bwd_preprocess": event_ms(lambda: rsa.bwd_preprocess(desc, t["dO"], b["O"], t["Q"], b["ws"]),
+                                       it, torch),
+            "bwd_dkdv": event_ms(lambda: rsa.bwd_dkdv(desc, t["dO"], t["K"], t["V"], b["LSE"], b["ws"],
                                                       b["dK"], b["dV"]), it, torch),
-            "bwd_dq": event_ms(lambda: rsa.bwd_dq(desc, t["dO"], t["Q"], t["K"], t["V"], b["LSE"], D,
+            "bwd_dq": event_ms(lambda: rsa.bwd_dq(desc, t["dO"], t["Q"], t["K"], t["V"], b["LSE"], b["ws"],
                                                   b["dQ"]), it, torch),
         }
         res["kernel_ms"] = k

@@ -2,22 +2,24 @@
 // with the ring structure of section 3.2.2, without the score strip in memory.
 // P is recomputed from Q, K and the forward's LSE: P = exp(s QK^T - LSE).
 //
-//   dkdv kernel: a work-group owns 4*64 keys and walks the query tiles of every
+//   preprocess: D = rowsum(dO o O) and Qs = bf16(Q * s * log2 e).
+//   dkdv kernel: a work-group owns 4*32 keys and walks the query tiles of every
 //     simulated rank, starting with the rank that holds those keys (ring
 //     order); the sum over ranks that the ring would all-reduce is its loop.
-//       S = Q K^T, dP = dO V^T   (A operand: Q / dO rows from LDS; B: K / V in registers)
-//       P = exp2(S cl2 - LSE log2e), dS = P o (dP - D)
-//       dV^T += dO^T P, dK^T += Q^T dS   (A operand: LDS transpose reads; B: P / dS registers)
+//       S' = Qs K^T - LSE log2e, dP' = dO V^T - D   (A: Qs / dO rows from LDS; B: K / V registers;
+//                                                    the row terms are the accumulators' start)
+//       P = exp2(S'), dS = P o dP'
+//       dV^T += dO^T P, dK^T += Qs^T dS   (A operand: LDS transpose reads; B: P / dS registers)
 //   dq kernel: a work-group owns 4*R query rows and walks the K/V tiles in ring
 //     order (the paper's second K ring pass):
-//       S^T = K Q^T, dP^T = V dO^T, dS^T = P^T o (dP^T - D), dQ^T += K^T dS^T
+//       S'^T = K Qs^T - LSE log2e, dP'^T = V dO^T - D, dS^T = P^T o dP'^T, dQ^T += K^T dS^T
 #include "rsa_fused_tile.h"
 #include "rsa_kernels.h"
 
 namespace rsa {
 
 struct BwdArgs {
-  const uint16_t *Q, *K, *V, *dO;
+  const uint16_t *Q, *Qs, *K, *V, *dO;  // Qs = bf16(Q * scale * log2 e)
   const float *LSE, *D;
   uint16_t *dQ, *dK, *dV;
   int64_t L, c, Lq, q0;
@@ -25,10 +27,43 @@ struct BwdArgs {
   float cl2, scale;
 };
 
+// ------------------------------------------------------------- preprocess ---
+// D_i = sum_a dO_ia O_ia and Qs = bf16(Q * scale * log2 e): 8 lanes x 8 elements per row.
+__global__ void __launch_bounds__(256) bwd_preprocess_kernel(const uint16_t *dO, const uint16_t *O,
+                                                             const uint16_t *Q, float *D,
+                                                             uint16_t *Qs, int64_t rows, float cl2) {
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t row = gid >> 3;
+  const int sub = (int)(gid & 7);
+  float acc = 0.f;
+  if (row < rows) {
+    const int64_t off = row * 64 + sub * 8;
+    const u32x4 x = *reinterpret_cast<const u32x4 *>(dO + off);
+    const u32x4 y = *reinterpret_cast<const u32x4 *>(O + off);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      acc = fmaf(bf16_to_f32(x[e] & 0xffffu), bf16_to_f32(y[e] & 0xffffu), acc);
+      acc = fmaf(bf16_to_f32(x[e] >> 16), bf16_to_f32(y[e] >> 16), acc);
+    }
+    const bf16x8 q = *reinterpret_cast<const bf16x8 *>(Q + off);
+    *reinterpret_cast<bf16x8 *>(Qs + off) = scale_bf16x8(q, cl2);
+  }
+  acc += __shfl_xor(acc, 1);
+  acc += __shfl_xor(acc, 2);
+  acc += __shfl_xor(acc, 4);
+  if (row < rows && sub == 0) D[row] = acc;
+}
+
 // ------------------------------------------------------------------ dK, dV ---
+// Work-group: 4 waves x 32 keys.  K and V of a wave's keys stay in registers as B
+// operands; the work-group walks 64-row tiles of Qs (pre-scaled Q) and dO through LDS.
+// The row terms of the softmax backward ride on the accumulator init of the MFMAs:
+//   S'  = Qs K^T - LSE log2e   (so P = exp2(S') needs no multiply or subtract)
+//   dP' = dO V^T - D           (so dS = P dP' is one multiply)
+// dK is formed from Qs as well: dK = ln2 * sum_i dS_ij Qs_i.
 template <bool CAUSAL>
-__global__ void __launch_bounds__(256, 1) fused_bwd_dkdv_kernel(BwdArgs a) {
-  constexpr int KW = 64;      // keys per wave
+__global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
+  constexpr int KW = 32;      // keys per wave
   constexpr int BK = 4 * KW;  // keys per work-group
   __shared__ __attribute__((aligned(16))) unsigned char Qs[2][kTileBytes];
   __shared__ __attribute__((aligned(16))) unsigned char dOs[2][kTileBytes];
@@ -42,37 +77,34 @@ __global__ void __launch_bounds__(256, 1) fused_bwd_dkdv_kernel(BwdArgs a) {
   const int64_t key0 = (wg % a.tiles_per_head) * BK;  // first key of the work-group
   const int64_t wkey0 = key0 + wave * KW;             // first key of this wave
 
-  const uint16_t *Qh = a.Q + head * a.Lq * 64;
+  const uint16_t *Qh = a.Qs + head * a.Lq * 64;
   const uint16_t *dOh = a.dO + head * a.Lq * 64;
   const uint16_t *Kh = a.K + head * a.L * 64;
   const uint16_t *Vh = a.V + head * a.L * 64;
   const float *LSEh = a.LSE + head * a.Lq;
   const float *Dh = a.D + head * a.Lq;
 
-  // K and V of this wave's keys as B operands: lane (col, half) holds row
-  // key = wkey0 + kb*32 + col, elements dk*16 + half*8 .. +8.
-  bf16x8 kreg[2][4], vreg[2][4];
-#pragma unroll
-  for (int kb = 0; kb < 2; ++kb)
+  // K and V rows of this wave as B operands: lane (col, half) holds row
+  // key = wkey0 + col, elements dk*16 + half*8 .. +8.
+  bf16x8 kreg[4], vreg[4];
+  {
+    int64_t key = wkey0 + col;
+    if (key >= a.L) key = a.L - 1;  // ragged tail: clamped here, not stored below
 #pragma unroll
     for (int dk = 0; dk < 4; ++dk) {
-      int64_t key = wkey0 + kb * 32 + col;
-      if (key >= a.L) key = a.L - 1;  // ragged tail: clamped here, not stored below
-      const int64_t off = key * 64 + dk * 16 + half * 8;
-      kreg[kb][dk] = *reinterpret_cast<const bf16x8 *>(Kh + off);
-      vreg[kb][dk] = *reinterpret_cast<const bf16x8 *>(Vh + off);
+      kreg[dk] = *reinterpret_cast<const bf16x8 *>(Kh + key * 64 + dk * 16 + half * 8);
+      vreg[dk] = *reinterpret_cast<const bf16x8 *>(Vh + key * 64 + dk * 16 + half * 8);
     }
+  }
 
   const TileLanes tl(lane);
   const int ld_row = tid >> 3, ld_ch = tid & 7;
 
-  f32x16 dv[2][2], dk_[2][2];  // [db][kb], transposed: rows = head dim, columns = keys
+  f32x16 dv[2], dk_[2];  // [db], transposed: rows = head dim, columns = keys
 #pragma unroll
   for (int db = 0; db < 2; ++db)
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) { dv[db][kb][v] = 0.f; dk_[db][kb][v] = 0.f; }
+    for (int v = 0; v < 16; ++v) { dv[db][v] = 0.f; dk_[db][v] = 0.f; }
 
   // Query tiles (64 rows) in ring order: start at the rank that owns key0.
   const int nqt = (int)(a.Lq / 64);
@@ -96,8 +128,8 @@ __global__ void __launch_bounds__(256, 1) fused_bwd_dkdv_kernel(BwdArgs a) {
       qr[it] = *reinterpret_cast<const u32x4 *>(Qh + off);
       gr[it] = *reinterpret_cast<const u32x4 *>(dOh + off);
     }
-    if (tid < 64) lr = LSEh[r0 + tid] * kLog2e;
-    else if (tid < 128) dr = Dh[r0 + tid - 64];
+    if (tid < 64) lr = -LSEh[r0 + tid] * kLog2e;
+    else if (tid < 128) dr = -Dh[r0 + tid - 64];
   };
   auto store_tile = [&](int buf) {
 #pragma unroll
@@ -124,55 +156,45 @@ __global__ void __launch_bounds__(256, 1) fused_bwd_dkdv_kernel(BwdArgs a) {
 
     if (!CAUSAL || qf + 63 >= wkey0) {
       const bool domask = CAUSAL && qf < wkey0 + KW - 1;
-      bf16x8 pf[2][4], sf[2][4];  // [kb][kk]: P and dS as B operands, k = query
+      bf16x8 pf[4], sf[4];  // [kk]: P and dS as B operands, k = query
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
-        f32x16 s[2], dp[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) { s[kb][v] = 0.f; dp[kb][v] = 0.f; }
-#pragma unroll
-        for (int dk = 0; dk < 4; ++dk) {
-          const bf16x8 qa = tl.read_rows(Qs[buf], qb * 32, dk);
-          const bf16x8 ga = tl.read_rows(dOs[buf], qb * 32, dk);
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb) {
-            s[kb] = mfma_32x32x16(qa, kreg[kb][dk], s[kb]);
-            dp[kb] = mfma_32x32x16(ga, vreg[kb][dk], dp[kb]);
-          }
-        }
+        // accumulators start from -LSE log2e and -D of their rows (same for all lanes of a half)
+        f32x16 s, dp;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&lse_s[buf][qb * 32 + g * 8 + half * 4]);
           const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&d_s[buf][qb * 32 + g * 8 + half * 4]);
 #pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int v = g * 4 + e;
-              float x = s[kb][v];
-              if (domask) {
-                const int64_t qg = qf + qb * 32 + g * 8 + half * 4 + e;
-                const int64_t kg = wkey0 + kb * 32 + col;
-                if (kg > qg) x = -INFINITY;
-              }
-              const float p = __builtin_amdgcn_exp2f(fmaf(x, a.cl2, -l4[e]));
-              s[kb][v] = p;
-              dp[kb][v] = p * (dp[kb][v] - d4[e]);
-            }
+          for (int e = 0; e < 4; ++e) { s[g * 4 + e] = l4[e]; dp[g * 4 + e] = d4[e]; }
         }
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int dk = 0; dk < 4; ++dk) {
+          const bf16x8 qa = tl.read_rows(Qs[buf], qb * 32, dk);
+          const bf16x8 ga = tl.read_rows(dOs[buf], qb * 32, dk);
+          s = mfma_32x32x16(qa, kreg[dk], s);
+          dp = mfma_32x32x16(ga, vreg[dk], dp);
+        }
+        if (domask) {
 #pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            u32x4 w = {pack_bf16(s[kb][u * 8 + 0], s[kb][u * 8 + 1]), pack_bf16(s[kb][u * 8 + 2], s[kb][u * 8 + 3]),
-                       pack_bf16(s[kb][u * 8 + 4], s[kb][u * 8 + 5]), pack_bf16(s[kb][u * 8 + 6], s[kb][u * 8 + 7])};
-            pf[kb][qb * 2 + u] = __builtin_bit_cast(bf16x8, w);
-            u32x4 x = {pack_bf16(dp[kb][u * 8 + 0], dp[kb][u * 8 + 1]), pack_bf16(dp[kb][u * 8 + 2], dp[kb][u * 8 + 3]),
-                       pack_bf16(dp[kb][u * 8 + 4], dp[kb][u * 8 + 5]), pack_bf16(dp[kb][u * 8 + 6], dp[kb][u * 8 + 7])};
-            sf[kb][qb * 2 + u] = __builtin_bit_cast(bf16x8, x);
+          for (int v = 0; v < 16; ++v) {
+            const int64_t qg = qf + qb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+            if (wkey0 + col > qg) s[v] = -INFINITY;
           }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          u32x4 w, x;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float p0 = __builtin_amdgcn_exp2f(s[u * 8 + 2 * e]);
+            const float p1 = __builtin_amdgcn_exp2f(s[u * 8 + 2 * e + 1]);
+            w[e] = pack_bf16(p0, p1);
+            x[e] = pack_bf16(p0 * dp[u * 8 + 2 * e], p1 * dp[u * 8 + 2 * e + 1]);
+          }
+          pf[qb * 2 + u] = __builtin_bit_cast(bf16x8, w);
+          sf[qb * 2 + u] = __builtin_bit_cast(bf16x8, x);
+        }
       }
 #pragma unroll
       for (int db = 0; db < 2; ++db)
@@ -180,11 +202,8 @@ __global__ void __launch_bounds__(256, 1) fused_bwd_dkdv_kernel(BwdArgs a) {
         for (int kk = 0; kk < 4; ++kk) {
           const bf16x8 ga = tl.read_cols(dOs[buf], kk * 16, db);
           const bf16x8 qa = tl.read_cols(Qs[buf], kk * 16, db);
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb) {
-            dv[db][kb] = mfma_32x32x16(ga, pf[kb][kk], dv[db][kb]);
-            dk_[db][kb] = mfma_32x32x16(qa, sf[kb][kk], dk_[db][kb]);
-          }
+          dv[db] = mfma_32x32x16(ga, pf[kk], dv[db]);
+          dk_[db] = mfma_32x32x16(qa, sf[kk], dk_[db]);
         }
     }
 
@@ -196,20 +215,18 @@ __global__ void __launch_bounds__(256, 1) fused_bwd_dkdv_kernel(BwdArgs a) {
 
   uint16_t *dKh = a.dK + head * a.L * 64;
   uint16_t *dVh = a.dV + head * a.L * 64;
-#pragma unroll
-  for (int kb = 0; kb < 2; ++kb) {
-    const int64_t key = wkey0 + kb * 32 + col;
-    if (key >= a.L) continue;
+  const int64_t key = wkey0 + col;
+  if (key < a.L) {
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int64_t off = key * 64 + db * 32 + g * 8 + half * 4;
-        u32x2 w = {pack_bf16(dv[db][kb][g * 4 + 0], dv[db][kb][g * 4 + 1]),
-                   pack_bf16(dv[db][kb][g * 4 + 2], dv[db][kb][g * 4 + 3])};
+        u32x2 w = {pack_bf16(dv[db][g * 4 + 0], dv[db][g * 4 + 1]),
+                   pack_bf16(dv[db][g * 4 + 2], dv[db][g * 4 + 3])};
         *reinterpret_cast<u32x2 *>(dVh + off) = w;
-        u32x2 x = {pack_bf16(dk_[db][kb][g * 4 + 0] * a.scale, dk_[db][kb][g * 4 + 1] * a.scale),
-                   pack_bf16(dk_[db][kb][g * 4 + 2] * a.scale, dk_[db][kb][g * 4 + 3] * a.scale)};
+        u32x2 x = {pack_bf16(dk_[db][g * 4 + 0] * kLn2, dk_[db][g * 4 + 1] * kLn2),
+                   pack_bf16(dk_[db][g * 4 + 2] * kLn2, dk_[db][g * 4 + 3] * kLn2)};
         *reinterpret_cast<u32x2 *>(dKh + off) = x;
       }
   }
@@ -238,20 +255,26 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   const uint16_t *Kh = a.K + head * a.L * 64;
   const uint16_t *Vh = a.V + head * a.L * 64;
 
+  // Q (pre-multiplied by scale * log2 e, rounded to bf16 exactly as the preprocess
+  // kernel does) and dO as B operands; -LSE log2e and -D of the lane's row, broadcast
+  // over an accumulator, are what S'^T and dP'^T start from.
   bf16x8 qreg[QB][4], greg[QB][4];
   int64_t qrow[QB];
-  float lse2[QB], dd[QB];
+  f32x16 negl[QB], negd[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int64_t r = row0 + wave * R + qb * 32 + col;
     qrow[qb] = r < a.Lq ? r : a.Lq - 1;
 #pragma unroll
     for (int dk = 0; dk < 4; ++dk) {
-      qreg[qb][dk] = *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * 64 + dk * 16 + half * 8);
+      qreg[qb][dk] = scale_bf16x8(
+          *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * 64 + dk * 16 + half * 8), a.cl2);
       greg[qb][dk] = *reinterpret_cast<const bf16x8 *>(dOh + qrow[qb] * 64 + dk * 16 + half * 8);
     }
-    lse2[qb] = a.LSE[head * a.Lq + qrow[qb]] * kLog2e;
-    dd[qb] = a.D[head * a.Lq + qrow[qb]];
+    const float l2 = -a.LSE[head * a.Lq + qrow[qb]] * kLog2e;
+    const float dd = -a.D[head * a.Lq + qrow[qb]];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { negl[qb][v] = l2; negd[qb][v] = dd; }
   }
   const int64_t wq_first = a.q0 + (row0 + wave * R < a.Lq ? row0 + wave * R : a.Lq - 1);
   const int64_t wq_last = a.q0 + (row0 + wave * R + R - 1 < a.Lq ? row0 + wave * R + R - 1 : a.Lq - 1);
@@ -317,17 +340,13 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
       for (int kb = 0; kb < 2; ++kb) {
         f32x16 s[QB], dp[QB];
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) { s[qb][v] = 0.f; dp[qb][v] = 0.f; }
-#pragma unroll
         for (int dk = 0; dk < 4; ++dk) {
           const bf16x8 ka = tl.read_rows(Ks[buf], kb * 32, dk);
           const bf16x8 va = tl.read_rows(Vs[buf], kb * 32, dk);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) {
-            s[qb] = mfma_32x32x16(ka, qreg[qb][dk], s[qb]);
-            dp[qb] = mfma_32x32x16(va, greg[qb][dk], dp[qb]);
+            s[qb] = mfma_32x32x16(ka, qreg[qb][dk], dk == 0 ? negl[qb] : s[qb]);
+            dp[qb] = mfma_32x32x16(va, greg[qb][dk], dk == 0 ? negd[qb] : dp[qb]);
           }
         }
 #pragma unroll
@@ -340,8 +359,7 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
               const int64_t kg = k0 + kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
               if (kg > qg) x = -INFINITY;
             }
-            const float p = __builtin_amdgcn_exp2f(fmaf(x, a.cl2, -lse2[qb]));
-            dp[qb][v] = p * (dp[qb][v] - dd[qb]);
+            dp[qb][v] *= __builtin_amdgcn_exp2f(x);
           }
 #pragma unroll
           for (int u = 0; u < 2; ++u) {
@@ -383,11 +401,12 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   }
 }
 
-static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const void *K,
-                             const void *V, const float *LSE, const float *D, void *dQ, void *dK,
-                             void *dV) {
+static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const void *Qs,
+                             const void *K, const void *V, const float *LSE, const float *D,
+                             void *dQ, void *dK, void *dV) {
   BwdArgs a;
-  a.Q = (const uint16_t *)Q; a.K = (const uint16_t *)K; a.V = (const uint16_t *)V;
+  a.Q = (const uint16_t *)Q; a.Qs = (const uint16_t *)Qs;
+  a.K = (const uint16_t *)K; a.V = (const uint16_t *)V;
   a.dO = (const uint16_t *)dO; a.LSE = LSE; a.D = D;
   a.dQ = (uint16_t *)dQ; a.dK = (uint16_t *)dK; a.dV = (uint16_t *)dV;
   a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.q0 = (int64_t)d.rank_begin * d.c;
@@ -396,11 +415,21 @@ static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const
   return a;
 }
 
-hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Q, const void *K,
+hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, const void *Q,
+                                float *D, void *Qs, hipStream_t st) {
+  const int64_t rows = (int64_t)d.B * d.Z * d.Lq;
+  dim3 grid((unsigned)((rows * 8 + 255) / 256));
+  hipLaunchKernelGGL(bwd_preprocess_kernel, grid, dim3(256), 0, st, (const uint16_t *)dO,
+                     (const uint16_t *)O, (const uint16_t *)Q, D, (uint16_t *)Qs, rows,
+                     d.scale * kLog2e);
+  return hipGetLastError();
+}
+
+hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Qs, const void *K,
                           const void *V, const float *LSE, const float *D, void *dK, void *dV,
                           hipStream_t st) {
-  BwdArgs a = make_bwd_args(d, dO, Q, K, V, LSE, D, nullptr, dK, dV);
-  a.tiles_per_head = (int)((d.L + 255) / 256);
+  BwdArgs a = make_bwd_args(d, dO, nullptr, Qs, K, V, LSE, D, nullptr, dK, dV);
+  a.tiles_per_head = (int)((d.L + 127) / 128);
   dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head));
   if (d.causal)
     hipLaunchKernelGGL((fused_bwd_dkdv_kernel<true>), grid, dim3(256), 0, st, a);
@@ -411,7 +440,7 @@ hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Q, const vo
 
 hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void *K, const void *V,
                         const float *LSE, const float *D, void *dQ, hipStream_t st) {
-  BwdArgs a = make_bwd_args(d, dO, Q, K, V, LSE, D, dQ, nullptr, nullptr);
+  BwdArgs a = make_bwd_args(d, dO, Q, nullptr, K, V, LSE, D, dQ, nullptr, nullptr);
   a.tiles_per_head = (int)((d.Lq + 127) / 128);
   dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head));
   if (d.causal)
@@ -423,10 +452,10 @@ hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void
 
 hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const void *K,
                           const void *V, const void *O, const float *LSE, void *dQ, void *dK,
-                          void *dV, float *D, hipStream_t st) {
-  hipError_t e = rowdot(d, RSA_BF16, 0, d.Lq, dO, O, D, st);
+                          void *dV, float *D, void *Qs, hipStream_t st) {
+  hipError_t e = fused_bwd_preprocess(d, dO, O, Q, D, Qs, st);
   if (e != hipSuccess) return e;
-  e = fused_bwd_dkdv(d, dO, Q, K, V, LSE, D, dK, dV, st);
+  e = fused_bwd_dkdv(d, dO, Qs, K, V, LSE, D, dK, dV, st);
   if (e != hipSuccess) return e;
   return fused_bwd_dq(d, dO, Q, K, V, LSE, D, dQ, st);
 }

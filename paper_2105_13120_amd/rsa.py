@@ -19,7 +19,7 @@ EXPORTS = (
     "rsa_version", "rsa_strerror", "rsa_workspace_bytes", "rsa_forward", "rsa_backward",
     "rsa_qk_step", "rsa_row_softmax", "rsa_av_step", "rsa_bwd_rowdot", "rsa_dv_step",
     "rsa_dp_step", "rsa_softmax_bwd", "rsa_dq_step", "rsa_dk_step", "rsa_store",
-    "rsa_bwd_dkdv", "rsa_bwd_dq",
+    "rsa_bwd_preprocess", "rsa_bwd_dkdv", "rsa_bwd_dq",
 )
 
 
@@ -70,7 +70,8 @@ def lib():
         L.rsa_dq_step.argtypes = [dp, i, i, vp, vp, vp, i, vp]
         L.rsa_dk_step.argtypes = [dp, i, i, vp, vp, vp, i, vp]
         L.rsa_store.argtypes = [dp, vp, vp, sz, vp]
-        L.rsa_bwd_dkdv.argtypes = [dp] + [vp] * 9
+        L.rsa_bwd_preprocess.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        L.rsa_bwd_dkdv.argtypes = [dp] + [vp] * 8
         L.rsa_bwd_dq.argtypes = [dp] + [vp] * 8
         for name in EXPORTS[3:]:
             getattr(L, name).restype = i
@@ -195,11 +196,16 @@ def store(desc, src, dst):
     _check(lib().rsa_store(ctypes.byref(desc), _p(src), _p(dst), src.numel(), _stream()))
 
 
-def bwd_dkdv(desc, dO, Q, K, V, LSE, D, dK, dV):
-    _check(lib().rsa_bwd_dkdv(ctypes.byref(desc), _p(dO), _p(Q), _p(K), _p(V), _p(LSE), _p(D),
+def bwd_preprocess(desc, dO, O, Q, ws):
+    _check(lib().rsa_bwd_preprocess(ctypes.byref(desc), _p(dO), _p(O), _p(Q), _p(ws), ws.numel(),
+                                    _stream()))
+
+
+def bwd_dkdv(desc, dO, K, V, LSE, ws, dK, dV):
+    _check(lib().rsa_bwd_dkdv(ctypes.byref(desc), _p(dO), _p(K), _p(V), _p(LSE), _p(ws),
                               _p(dK), _p(dV), _stream()))
 
 
-def bwd_dq(desc, dO, Q, K, V, LSE, D, dQ):
-    _check(lib().rsa_bwd_dq(ctypes.byref(desc), _p(dO), _p(Q), _p(K), _p(V), _p(LSE), _p(D),
+def bwd_dq(desc, dO, Q, K, V, LSE, ws, dQ):
+    _check(lib().rsa_bwd_dq(ctypes.byref(desc), _p(dO), _p(Q), _p(K), _p(V), _p(LSE), _p(ws),
                             _p(dQ), _stream()))
