@@ -63,6 +63,17 @@ __device__ __forceinline__ u32x2 lds_read_tr16(const void *lds_ptr) {
   return __builtin_bit_cast(u32x2, r);
 }
 
+// Direct 16-byte global->LDS load (global_load_lds_dwordx4): lane l of the wave fetches
+// 16 bytes from its own global address and the hardware writes them to LDS at
+// lds_base + 16 l; lds_base must be the same for the whole wave.  Completion is tracked
+// by vmcnt: wait_vmem() before the barrier that publishes the data.
+__device__ __forceinline__ void lds_dma16(const void *gsrc, void *lds_base) {
+  typedef __attribute__((address_space(1))) const void *gptr_t;
+  typedef __attribute__((address_space(3))) void *lptr_t;
+  __builtin_amdgcn_global_load_lds((gptr_t)gsrc, (lptr_t)lds_base, 16, 0, 0);
+}
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0)
+
 // Exchange between the two lanes l and l^32 (the two halves of a 32x32
 // accumulator column).  v_permlane32_swap a, b swaps a[32..63] with b[0..31];
 // with a = b = x on entry, lanes 0-31 end with (a, b) = (x[l], x[l+32]) and

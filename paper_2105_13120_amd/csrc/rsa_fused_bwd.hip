@@ -56,21 +56,24 @@ __global__ void __launch_bounds__(256) bwd_preprocess_kernel(const uint16_t *dO,
 
 // ------------------------------------------------------------------ dK, dV ---
 // Work-group: 4 waves x 32 keys.  K and V of a wave's keys stay in registers as B
-// operands; the work-group walks 64-row tiles of Qs (pre-scaled Q) and dO through LDS.
+// operands; the work-group walks the query rows in stages of NQ tiles of 64 rows of Qs
+// (pre-scaled Q) and dO, double-buffered in LDS and filled by direct global->LDS loads
+// (no staging registers), one barrier per stage.
 // The row terms of the softmax backward ride on the accumulator init of the MFMAs:
 //   S'  = Qs K^T - LSE log2e   (so P = exp2(S') needs no multiply or subtract)
 //   dP' = dO V^T - D           (so dS = P dP' is one multiply)
 // dK is formed from Qs as well: dK = ln2 * sum_i dS_ij Qs_i.
-template <bool CAUSAL>
+template <int NQ, bool CAUSAL>
 __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
   constexpr int KW = 32;      // keys per wave
   constexpr int BK = 4 * KW;  // keys per work-group
-  __shared__ __attribute__((aligned(16))) unsigned char Qs[2][kTileBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char dOs[2][kTileBytes];
-  __shared__ __attribute__((aligned(16))) float lse_s[2][64];
-  __shared__ __attribute__((aligned(16))) float d_s[2][64];
+  __shared__ __attribute__((aligned(16))) unsigned char Qs[2][NQ][kTileBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char dOs[2][NQ][kTileBytes];
+  __shared__ __attribute__((aligned(16))) float lse_s[2][NQ][64];
+  __shared__ __attribute__((aligned(16))) float d_s[2][NQ][64];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
   const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x);
   const int64_t head = wg / a.tiles_per_head;
@@ -98,7 +101,6 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
   }
 
   const TileLanes tl(lane);
-  const int ld_row = tid >> 3, ld_ch = tid & 7;
 
   f32x16 dv[2], dk_[2];  // [db], transposed: rows = head dim, columns = keys
 #pragma unroll
@@ -106,108 +108,116 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) { dv[db][v] = 0.f; dk_[db][v] = 0.f; }
 
-  // Query tiles (64 rows) in ring order: start at the rank that owns key0.
+  // Stages of NQ query tiles in ring order: start at the rank that owns key0.
   const int nqt = (int)(a.Lq / 64);
+  const int nst = (nqt + NQ - 1) / NQ;
   int start = 0;
   {
     const int64_t r = (key0 / a.c) * a.c - a.q0;  // local row of that rank's first query
-    if (r >= 0 && r < a.Lq) start = (int)(r / 64);
+    if (r >= 0 && r < a.Lq) start = (int)(r / (64 * NQ));
   }
-  auto qt_of = [&](int i) { int q = start + i; return q >= nqt ? q - nqt : q; };
-  // a query tile matters if its last row can see the first key of the work-group
-  auto visible = [&](int i) { return !CAUSAL || a.q0 + (int64_t)qt_of(i) * 64 + 63 >= key0; };
-  auto advance = [&](int i) { ++i; while (i < nqt && !visible(i)) ++i; return i; };
-
-  u32x4 qr[2], gr[2];
-  float lr = 0.f, dr = 0.f;
-  auto load_tile = [&](int i) {
-    const int64_t r0 = (int64_t)qt_of(i) * 64;
-#pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const int64_t off = (r0 + ld_row + it * 32) * 64 + ld_ch * 8;
-      qr[it] = *reinterpret_cast<const u32x4 *>(Qh + off);
-      gr[it] = *reinterpret_cast<const u32x4 *>(dOh + off);
-    }
-    if (tid < 64) lr = -LSEh[r0 + tid] * kLog2e;
-    else if (tid < 128) dr = -Dh[r0 + tid - 64];
+  auto st_of = [&](int i) { int q = start + i; return q >= nst ? q - nst : q; };
+  // a stage matters if its last row can see the first key of the work-group
+  auto visible = [&](int i) {
+    return !CAUSAL || a.q0 + (int64_t)(st_of(i) + 1) * (64 * NQ) - 1 >= key0;
   };
-  auto store_tile = [&](int buf) {
+  auto advance = [&](int i) { ++i; while (i < nst && !visible(i)) ++i; return i; };
+
+  // Direct global->LDS copy of one stage: wave w moves 16-byte pieces (w*2+j)*64 + lane of
+  // every tile; the piece at LDS position p = 8*row + pc holds logical chunk pc ^ rot(row).
+  int g_off[2], l_off[2];
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const int off = tile_off(ld_row + it * 32, ld_ch);
-      *reinterpret_cast<u32x4 *>(Qs[buf] + off) = qr[it];
-      *reinterpret_cast<u32x4 *>(dOs[buf] + off) = gr[it];
+  for (int j = 0; j < 2; ++j) {
+    const int p = (wave * 2 + j) * 64 + lane;
+    const int row = p >> 3, cc = (p & 7) ^ swz_rot(row);
+    g_off[j] = row * 64 + cc * 8;
+    l_off[j] = (wave * 2 + j) * 1024;
+  }
+  auto load_stage = [&](int i, int buf) {
+    const int st = st_of(i);
+#pragma unroll
+    for (int u = 0; u < NQ; ++u) {
+      int qt = st * NQ + u;
+      if (qt >= nqt) qt = nqt - 1;  // past the last tile: refetch it (never used)
+      const int64_t r0 = (int64_t)qt * 64;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        lds_dma16(Qh + r0 * 64 + g_off[j], Qs[buf][u] + l_off[j]);
+        lds_dma16(dOh + r0 * 64 + g_off[j], dOs[buf][u] + l_off[j]);
+      }
+      if (tid < 64) lse_s[buf][u][tid] = -LSEh[r0 + tid] * kLog2e;
+      else if (tid < 128) d_s[buf][u][tid - 64] = -Dh[r0 + tid - 64];
     }
-    if (tid < 64) lse_s[buf][tid] = lr;
-    else if (tid < 128) d_s[buf][tid - 64] = dr;
   };
 
   int i = visible(0) ? 0 : advance(0);
   int buf = 0;
-  if (i < nqt) {
-    load_tile(i);
-    store_tile(0);
-  }
+  if (i < nst) load_stage(i, 0);
+  wait_vmem();
   __syncthreads();
-  while (i < nqt) {
+  while (i < nst) {
     const int inext = advance(i);
-    if (inext < nqt) load_tile(inext);
-    const int64_t qf = a.q0 + (int64_t)qt_of(i) * 64;  // global index of the tile's first row
+    if (inext < nst) load_stage(inext, buf ^ 1);
 
-    if (!CAUSAL || qf + 63 >= wkey0) {
-      const bool domask = CAUSAL && qf < wkey0 + KW - 1;
-      bf16x8 pf[4], sf[4];  // [kk]: P and dS as B operands, k = query
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        // accumulators start from -LSE log2e and -D of their rows (same for all lanes of a half)
-        f32x16 s, dp;
+    for (int u = 0; u < NQ; ++u) {
+      const int qt = st_of(i) * NQ + u;
+      const int64_t qf = a.q0 + (int64_t)qt * 64;  // global index of the tile's first row
+      if (qt < nqt && (!CAUSAL || qf + 63 >= wkey0)) {
+        const bool domask = CAUSAL && qf < wkey0 + KW - 1;
+        bf16x8 pf[4], sf[4];  // [kk]: P and dS as B operands, k = query
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&lse_s[buf][qb * 32 + g * 8 + half * 4]);
-          const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&d_s[buf][qb * 32 + g * 8 + half * 4]);
+        for (int qb = 0; qb < 2; ++qb) {
+          // accumulators start from -LSE log2e and -D of their rows (same for all lanes of a half)
+          f32x16 s, dp;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) { s[g * 4 + e] = l4[e]; dp[g * 4 + e] = d4[e]; }
-        }
+          for (int g = 0; g < 4; ++g) {
+            const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&lse_s[buf][u][qb * 32 + g * 8 + half * 4]);
+            const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&d_s[buf][u][qb * 32 + g * 8 + half * 4]);
 #pragma unroll
-        for (int dk = 0; dk < 4; ++dk) {
-          const bf16x8 qa = tl.read_rows(Qs[buf], qb * 32, dk);
-          const bf16x8 ga = tl.read_rows(dOs[buf], qb * 32, dk);
-          s = mfma_32x32x16(qa, kreg[dk], s);
-          dp = mfma_32x32x16(ga, vreg[dk], dp);
-        }
-        if (domask) {
+            for (int e = 0; e < 4; ++e) { s[g * 4 + e] = l4[e]; dp[g * 4 + e] = d4[e]; }
+          }
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int64_t qg = qf + qb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-            if (wkey0 + col > qg) s[v] = -INFINITY;
+          for (int dk = 0; dk < 4; ++dk) {
+            const bf16x8 qa = tl.read_rows(Qs[buf][u], qb * 32, dk);
+            const bf16x8 ga = tl.read_rows(dOs[buf][u], qb * 32, dk);
+            s = mfma_32x32x16(qa, kreg[dk], s);
+            dp = mfma_32x32x16(ga, vreg[dk], dp);
+          }
+          if (domask) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int64_t qg = qf + qb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+              if (wkey0 + col > qg) s[v] = -INFINITY;
+            }
+          }
+#pragma unroll
+          for (int w2 = 0; w2 < 2; ++w2) {
+            u32x4 w, x;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float p0 = __builtin_amdgcn_exp2f(s[w2 * 8 + 2 * e]);
+              const float p1 = __builtin_amdgcn_exp2f(s[w2 * 8 + 2 * e + 1]);
+              w[e] = pack_bf16(p0, p1);
+              x[e] = pack_bf16(p0 * dp[w2 * 8 + 2 * e], p1 * dp[w2 * 8 + 2 * e + 1]);
+            }
+            pf[qb * 2 + w2] = __builtin_bit_cast(bf16x8, w);
+            sf[qb * 2 + w2] = __builtin_bit_cast(bf16x8, x);
           }
         }
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          u32x4 w, x;
+        for (int db = 0; db < 2; ++db)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float p0 = __builtin_amdgcn_exp2f(s[u * 8 + 2 * e]);
-            const float p1 = __builtin_amdgcn_exp2f(s[u * 8 + 2 * e + 1]);
-            w[e] = pack_bf16(p0, p1);
-            x[e] = pack_bf16(p0 * dp[u * 8 + 2 * e], p1 * dp[u * 8 + 2 * e + 1]);
+          for (int kk = 0; kk < 4; ++kk) {
+            const bf16x8 ga = tl.read_cols(dOs[buf][u], kk * 16, db);
+            const bf16x8 qa = tl.read_cols(Qs[buf][u], kk * 16, db);
+            dv[db] = mfma_32x32x16(ga, pf[kk], dv[db]);
+            dk_[db] = mfma_32x32x16(qa, sf[kk], dk_[db]);
           }
-          pf[qb * 2 + u] = __builtin_bit_cast(bf16x8, w);
-          sf[qb * 2 + u] = __builtin_bit_cast(bf16x8, x);
-        }
       }
-#pragma unroll
-      for (int db = 0; db < 2; ++db)
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          const bf16x8 ga = tl.read_cols(dOs[buf], kk * 16, db);
-          const bf16x8 qa = tl.read_cols(Qs[buf], kk * 16, db);
-          dv[db] = mfma_32x32x16(ga, pf[kk], dv[db]);
-          dk_[db] = mfma_32x32x16(qa, sf[kk], dk_[db]);
-        }
     }
 
-    if (inext < nqt) store_tile(buf ^ 1);
+    wait_vmem();
     __syncthreads();
     buf ^= 1;
     i = inext;
@@ -432,9 +442,9 @@ hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Qs, const v
   a.tiles_per_head = (int)((d.L + 127) / 128);
   dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head));
   if (d.causal)
-    hipLaunchKernelGGL((fused_bwd_dkdv_kernel<true>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((fused_bwd_dkdv_kernel<2, true>), grid, dim3(256), 0, st, a);
   else
-    hipLaunchKernelGGL((fused_bwd_dkdv_kernel<false>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((fused_bwd_dkdv_kernel<2, false>), grid, dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
