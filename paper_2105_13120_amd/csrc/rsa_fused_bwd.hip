@@ -123,16 +123,7 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
   };
   auto advance = [&](int i) { ++i; while (i < nst && !visible(i)) ++i; return i; };
 
-  // Direct global->LDS copy of one stage: wave w moves 16-byte pieces (w*2+j)*64 + lane of
-  // every tile; the piece at LDS position p = 8*row + pc holds logical chunk pc ^ rot(row).
-  int g_off[2], l_off[2];
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int p = (wave * 2 + j) * 64 + lane;
-    const int row = p >> 3, cc = (p & 7) ^ swz_rot(row);
-    g_off[j] = row * 64 + cc * 8;
-    l_off[j] = (wave * 2 + j) * 1024;
-  }
+  const TileDMA dma(wave, lane);
   auto load_stage = [&](int i, int buf) {
     const int st = st_of(i);
 #pragma unroll
@@ -140,11 +131,8 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
       int qt = st * NQ + u;
       if (qt >= nqt) qt = nqt - 1;  // past the last tile: refetch it (never used)
       const int64_t r0 = (int64_t)qt * 64;
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        lds_dma16(Qh + r0 * 64 + g_off[j], Qs[buf][u] + l_off[j]);
-        lds_dma16(dOh + r0 * 64 + g_off[j], dOs[buf][u] + l_off[j]);
-      }
+      dma.load(Qh + r0 * 64, Qs[buf][u]);
+      dma.load(dOh + r0 * 64, dOs[buf][u]);
       if (tid < 64) lse_s[buf][u][tid] = -LSEh[r0 + tid] * kLog2e;
       else if (tid < 128) d_s[buf][u][tid - 64] = -Dh[r0 + tid - 64];
     }
@@ -247,10 +235,12 @@ template <int R, bool CAUSAL>
 __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdArgs a) {
   constexpr int QB = R / 32;
   constexpr int BM = 4 * R;
-  __shared__ __attribute__((aligned(16))) unsigned char Ks[2][kTileBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char Vs[2][kTileBytes];
+  constexpr int NK = 2;  // key tiles per stage (one barrier per stage)
+  __shared__ __attribute__((aligned(16))) unsigned char Ks[2][NK][kTileBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Vs[2][NK][kTileBytes];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
   const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x);
   const int64_t head = wg / a.tiles_per_head;
@@ -258,7 +248,7 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   const int64_t q_first = a.q0 + row0;
   const int64_t q_last = a.q0 + (row0 + BM < a.Lq ? row0 + BM : a.Lq) - 1;
   const int n = (int)(q_first / a.c);
-  const int tpc = (int)(a.c / kTileKeys);
+  const int tpc = (int)(a.c / kTileKeys);  // tiles per chunk
 
   const uint16_t *Qh = a.Q + head * a.Lq * 64;
   const uint16_t *dOh = a.dO + head * a.Lq * 64;
@@ -290,7 +280,6 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   const int64_t wq_last = a.q0 + (row0 + wave * R + R - 1 < a.Lq ? row0 + wave * R + R - 1 : a.Lq - 1);
 
   const TileLanes tl(lane);
-  const int ld_row = tid >> 3, ld_ch = tid & 7;
 
   f32x16 dq[2][QB];
 #pragma unroll
@@ -300,50 +289,50 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
 #pragma unroll
       for (int v = 0; v < 16; ++v) dq[db][qb][v] = 0.f;
 
-  auto k0_of = [&](int t, int kt) -> int64_t {
+  // The ring walk: ring step t visits chunk (n - t) mod N.  Tiles are taken NK at a time;
+  // a stage never straddles chunks when tiles-per-chunk is even, otherwise NK falls to 1.
+  const int nk = (tpc % NK == 0) ? NK : 1;
+  const int spc = tpc / nk;  // stages per chunk
+  auto k0_of = [&](int t, int ks) -> int64_t {
     int j = n - t;
     if (j < 0) j += a.N;
-    return (int64_t)j * a.c + (int64_t)kt * kTileKeys;
+    return (int64_t)j * a.c + (int64_t)ks * nk * kTileKeys;
   };
-  auto advance = [&](int &t, int &kt) -> bool {
-    ++kt;
+  auto advance = [&](int &t, int &ks) -> bool {
+    ++ks;
     for (;;) {
-      if (kt >= tpc) { ++t; kt = 0; }
+      if (ks >= spc) { ++t; ks = 0; }
       if (t >= a.N) return false;
-      if (!CAUSAL || k0_of(t, kt) <= q_last) return true;
-      kt = tpc;
+      if (!CAUSAL || k0_of(t, ks) <= q_last) return true;
+      ks = spc;
     }
   };
-  u32x4 kr[2], vr[2];
-  auto load_tile = [&](int64_t k0) {
+  const TileDMA dma(wave, lane);
+  auto load_stage = [&](int64_t k0, int buf) {
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const int64_t off = (k0 + ld_row + it * 32) * 64 + ld_ch * 8;
-      kr[it] = *reinterpret_cast<const u32x4 *>(Kh + off);
-      vr[it] = *reinterpret_cast<const u32x4 *>(Vh + off);
-    }
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const int off = tile_off(ld_row + it * 32, ld_ch);
-      *reinterpret_cast<u32x4 *>(Ks[buf] + off) = kr[it];
-      *reinterpret_cast<u32x4 *>(Vs[buf] + off) = vr[it];
+    for (int u = 0; u < NK; ++u) {
+      if (u < nk) {
+        dma.load(Kh + (k0 + u * kTileKeys) * 64, Ks[buf][u]);
+        dma.load(Vh + (k0 + u * kTileKeys) * 64, Vs[buf][u]);
+      }
     }
   };
 
   int t = 0, kt = 0, buf = 0;
-  load_tile(k0_of(0, 0));
-  store_tile(0);
+  load_stage(k0_of(0, 0), 0);
+  wait_vmem();
   __syncthreads();
   bool have = true;
   while (have) {
-    const int64_t k0 = k0_of(t, kt);
+    const int64_t ks0 = k0_of(t, kt);
     int t2 = t, kt2 = kt;
     const bool have_next = advance(t2, kt2);
-    if (have_next) load_tile(k0_of(t2, kt2));
+    if (have_next) load_stage(k0_of(t2, kt2), buf ^ 1);
 
-    if (!CAUSAL || k0 <= wq_last) {
+#pragma unroll
+    for (int u = 0; u < NK; ++u) {
+    const int64_t k0 = ks0 + u * kTileKeys;
+    if (u < nk && (!CAUSAL || k0 <= wq_last)) {
       const bool domask = CAUSAL && k0 + kTileKeys - 1 > wq_first;
       bf16x8 sf[QB][4];
 #pragma unroll
@@ -351,8 +340,8 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
         f32x16 s[QB], dp[QB];
 #pragma unroll
         for (int dk = 0; dk < 4; ++dk) {
-          const bf16x8 ka = tl.read_rows(Ks[buf], kb * 32, dk);
-          const bf16x8 va = tl.read_rows(Vs[buf], kb * 32, dk);
+          const bf16x8 ka = tl.read_rows(Ks[buf][u], kb * 32, dk);
+          const bf16x8 va = tl.read_rows(Vs[buf][u], kb * 32, dk);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) {
             s[qb] = mfma_32x32x16(ka, qreg[qb][dk], dk == 0 ? negl[qb] : s[qb]);
@@ -383,13 +372,15 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
       for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-          const bf16x8 ka = tl.read_cols(Ks[buf], kk * 16, db);
+          const bf16x8 ka = tl.read_cols(Ks[buf][u], kk * 16, db);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) dq[db][qb] = mfma_32x32x16(ka, sf[qb][kk], dq[db][qb]);
         }
     }
 
-    if (have_next) store_tile(buf ^ 1);
+    }
+
+    wait_vmem();
     __syncthreads();
     buf ^= 1; t = t2; kt = kt2; have = have_next;
   }

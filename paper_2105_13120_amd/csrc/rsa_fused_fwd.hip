@@ -6,6 +6,9 @@
 // strip S^n of Table 2 never reaches device memory.  The result is Eq. 1 /
 // Eq. 3 exactly, up to summation order.
 //
+// K/V tiles reach LDS by direct global->LDS loads, two tiles per stage, double-buffered,
+// one work-group barrier per stage.
+//
 // Data flow per 64-key tile and wave (R query rows):
 //   S^T = K Q^T    A operand: K tile rows from LDS, B operand: Q^T in registers
 //   softmax update on S^T: lane l owns query column l%32, so the row max and
@@ -30,10 +33,12 @@ template <int R, bool CAUSAL>
 __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
   constexpr int QB = R / 32;
   constexpr int BM = 4 * R;
-  __shared__ __attribute__((aligned(16))) unsigned char Ks[2][kTileBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char Vs[2][kTileBytes];
+  constexpr int NK = 2;  // key tiles per stage (one barrier per stage)
+  __shared__ __attribute__((aligned(16))) unsigned char Ks[2][NK][kTileBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Vs[2][NK][kTileBytes];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
   const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x);
   const int64_t head = wg / a.tiles_per_head;
@@ -63,7 +68,6 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
   const int64_t wq_last = a.q0 + (row0 + wave * R + R - 1 < a.Lq ? row0 + wave * R + R - 1 : a.Lq - 1);
 
   const TileLanes tl(lane);
-  const int ld_row = tid >> 3, ld_ch = tid & 7;  // this thread's 16-byte pieces of a tile
 
   f32x16 o[2][QB];
   float m[QB], mc[QB], l[QB];
@@ -76,59 +80,58 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
       for (int v = 0; v < 16; ++v) o[db][qb][v] = 0.f;
   }
 
-  auto k0_of = [&](int t, int kt) -> int64_t {
+  // The ring walk: ring step t visits chunk (n - t) mod N.  Tiles are taken NK at a time;
+  // a stage never straddles chunks when tiles-per-chunk is even, otherwise NK falls to 1.
+  const int nk = (tpc % NK == 0) ? NK : 1;
+  const int spc = tpc / nk;  // stages per chunk
+  auto k0_of = [&](int t, int ks) -> int64_t {
     int j = n - t;
     if (j < 0) j += a.N;
-    return (int64_t)j * a.c + (int64_t)kt * kTileKeys;
+    return (int64_t)j * a.c + (int64_t)ks * nk * kTileKeys;
   };
-  // next tile of the ring walk that holds a visible key for some row of this work-group
-  auto advance = [&](int &t, int &kt) -> bool {
-    ++kt;
+  // next stage of the ring walk that holds a visible key for some row of this work-group
+  auto advance = [&](int &t, int &ks) -> bool {
+    ++ks;
     for (;;) {
-      if (kt >= tpc) { ++t; kt = 0; }
+      if (ks >= spc) { ++t; ks = 0; }
       if (t >= a.N) return false;
-      if (!CAUSAL || k0_of(t, kt) <= q_last) return true;
-      kt = tpc;  // later tiles of this chunk start even further right
+      if (!CAUSAL || k0_of(t, ks) <= q_last) return true;
+      ks = spc;  // later stages of this chunk start even further right
     }
   };
-
-  u32x4 kr[2], vr[2];
-  auto load_tile = [&](int64_t k0) {
+  const TileDMA dma(wave, lane);
+  auto load_stage = [&](int64_t k0, int buf) {
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const int64_t off = (k0 + ld_row + it * 32) * 64 + ld_ch * 8;
-      kr[it] = *reinterpret_cast<const u32x4 *>(Kh + off);
-      vr[it] = *reinterpret_cast<const u32x4 *>(Vh + off);
-    }
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const int off = tile_off(ld_row + it * 32, ld_ch);
-      *reinterpret_cast<u32x4 *>(Ks[buf] + off) = kr[it];
-      *reinterpret_cast<u32x4 *>(Vs[buf] + off) = vr[it];
+    for (int u = 0; u < NK; ++u) {
+      if (u < nk) {
+        dma.load(Kh + (k0 + u * kTileKeys) * 64, Ks[buf][u]);
+        dma.load(Vh + (k0 + u * kTileKeys) * 64, Vs[buf][u]);
+      }
     }
   };
 
   int t = 0, kt = 0, buf = 0;
-  load_tile(k0_of(0, 0));
-  store_tile(0);
+  load_stage(k0_of(0, 0), 0);
+  wait_vmem();
   __syncthreads();
   bool have = true;
   while (have) {
-    const int64_t k0 = k0_of(t, kt);
+    const int64_t ks0 = k0_of(t, kt);
     int t2 = t, kt2 = kt;
     const bool have_next = advance(t2, kt2);
-    if (have_next) load_tile(k0_of(t2, kt2));
+    if (have_next) load_stage(k0_of(t2, kt2), buf ^ 1);
 
-    if (!CAUSAL || k0 <= wq_last) {
+#pragma unroll
+    for (int u = 0; u < NK; ++u) {
+    const int64_t k0 = ks0 + u * kTileKeys;
+    if (u < nk && (!CAUSAL || k0 <= wq_last)) {
       // ---- S^T = K Q^T
       f32x16 s[2][QB];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
         bf16x8 ka[4];
 #pragma unroll
-        for (int dk = 0; dk < 4; ++dk) ka[dk] = tl.read_rows(Ks[buf], kb * 32, dk);
+        for (int dk = 0; dk < 4; ++dk) ka[dk] = tl.read_rows(Ks[buf][u], kb * 32, dk);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
@@ -205,13 +208,15 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
       for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-          const bf16x8 va = tl.read_cols(Vs[buf], kk * 16, db);
+          const bf16x8 va = tl.read_cols(Vs[buf][u], kk * 16, db);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) o[db][qb] = mfma_32x32x16(va, pf[qb][kk], o[db][qb]);
         }
     }
 
-    if (have_next) store_tile(buf ^ 1);
+    }
+
+    wait_vmem();
     __syncthreads();
     buf ^= 1; t = t2; kt = kt2; have = have_next;
   }

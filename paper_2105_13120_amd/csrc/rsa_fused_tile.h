@@ -63,4 +63,26 @@ struct TileLanes {
   }
 };
 
+// Direct global->LDS copy of one 64 x 64 bf16 tile by a 4-wave work-group: wave w moves
+// the 16-byte pieces (2 w + j) * 64 + lane, j = 0, 1; the piece at LDS position
+// p = 8 row + pc holds logical chunk pc ^ rot(row) of that row, so the tile lands in the
+// swizzled layout above.  `g` points at element [0][0] of the tile in global memory
+// (rows 64 elements apart).  Completion: wait_vmem(), then a barrier.
+struct TileDMA {
+  int g_off[2], l_off[2];
+  __device__ __forceinline__ TileDMA(int wave, int lane) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int p = (wave * 2 + j) * 64 + lane;
+      const int row = p >> 3, cc = (p & 7) ^ swz_rot(row);
+      g_off[j] = row * 64 + cc * 8;
+      l_off[j] = (wave * 2 + j) * 1024;
+    }
+  }
+  __device__ __forceinline__ void load(const uint16_t *g, unsigned char *tile) const {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) lds_dma16(g + g_off[j], tile + l_off[j]);
+  }
+};
+
 }  // namespace rsa
