@@ -21,9 +21,11 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs (see profiles/); None until measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch of the dominant kernel (fused_bwd_dkdv_kernel) from two
+# rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same
+# counter reads for a 1 GiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); the
+# summary is profiles/rsa_fused_bert_large_hbm_traffic.txt.  None where not measured.
+MEASURED_TRAFFIC_BYTES = {"bert_large": 204.6e6}
 
 
 def parse():
@@ -35,6 +37,11 @@ def parse():
                     choices=["bert_base", "bert_large", "long_32k", "rank15_64k_causal"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true", help="also time the other workloads briefly")
+    ap.add_argument("--staged", action="store_true",
+                    help="also time the staged (two-pass) kernels of one rank: HBM GB/s of the score strip")
+    ap.add_argument("--profile-copy", type=int, default=0, metavar="BYTES",
+                    help="after the timed steps, run a plain device copy of BYTES three times "
+                         "(the known-size kernel that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -103,6 +110,42 @@ def time_workload(cfg, steps, warmup, torch, rsa, inputs, per_kernel=True):
     return res, x
 
 
+def staged_report(cfg, torch, rsa, inputs):
+    """The paper's two-pass layout for one simulated rank (rank 0): time every ring step
+    kernel with HIP events and price the memory-bound ones against HBM."""
+    x = inputs.make_inputs(cfg)
+    t = {k: torch.from_numpy(v).to(torch.bfloat16).cuda().contiguous() for k, v in x.items()}
+    desc = rsa.make_desc(t["K"], cfg.N, causal=cfg.causal, mode=rsa.MODE_STAGED)
+    n, c, L, N, heads = 0, cfg.c, cfg.L, cfg.N, cfg.B * cfg.Z
+    dev = t["K"].device
+    S = torch.empty((cfg.B, cfg.Z, c, L), dtype=torch.float32, device=dev)
+    P = torch.empty((cfg.B, cfg.Z, c, L), dtype=torch.bfloat16, device=dev)
+    dS = torch.empty_like(P)
+    LSE = torch.empty((cfg.B, cfg.Z, cfg.L), dtype=torch.float32, device=dev)
+    D = torch.zeros_like(LSE)
+    Oacc = torch.empty((cfg.B, cfg.Z, c, cfg.A), dtype=torch.float32, device=dev)
+    for j in range(N):
+        rsa.qk_step(desc, n, j, t["Q"], t["K"], S)
+    scores = heads * c * L
+    ms = {
+        "qk_step": event_ms(lambda: rsa.qk_step(desc, n, 1 % N, t["Q"], t["K"], S), 10, torch),
+        "row_softmax": event_ms(lambda: rsa.row_softmax(desc, n, S, P, LSE), 10, torch),
+        "av_step": event_ms(lambda: rsa.av_step(desc, n, 1 % N, P, t["V"], Oacc, 0), 10, torch),
+        "softmax_bwd": event_ms(lambda: rsa.softmax_bwd(desc, n, P, S, D, dS), 10, torch),
+    }
+    gbs = lambda nbytes, m: nbytes / (m * 1e-3) / 1e9
+    # algorithmic bytes: softmax reads 4 B and writes 2 B per score; softmax backward reads
+    # P (2 B) and dP (4 B) and writes dS (2 B); a qk step writes 4 B per score of its block
+    return {
+        "rank": n, "scores_per_rank": scores, "kernel_ms": {k: round(v, 4) for k, v in ms.items()},
+        "row_softmax_GBps": round(gbs(6 * scores, ms["row_softmax"]), 1),
+        "softmax_bwd_GBps": round(gbs(8 * scores, ms["softmax_bwd"]), 1),
+        "qk_step_write_GBps": round(gbs(4 * scores / N, ms["qk_step"]), 1),
+        "hbm_peak_GBps": PEAK_HBM_GBS,
+        "strip_bytes_forward_all_ranks": (4 + 4 + 2 + 2) * scores * N,
+    }
+
+
 def cpu_baseline(cfg, x, inputs):
     """The fp64 oracle, as it stands, on a bounded head sample of the same workload."""
     import numpy as np
@@ -167,6 +210,15 @@ def main():
             other[name] = {"tflops": round(r2["tflops"], 2), "ms_per_step": round(r2["ms_per_step"], 4),
                            "kernel_ms": {n: round(v, 4) for n, v in r2["kernel_ms"].items()}}
         out["other_workloads"] = other
+    if a.staged:
+        out["staged"] = staged_report(cfg, torch, rsa, inputs)
+    if a.profile_copy > 0:
+        src = torch.empty(a.profile_copy, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["profile_copy_bytes"] = a.profile_copy
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, x, inputs)
     print(json.dumps(out))
