@@ -104,3 +104,69 @@ def test_staged_and_fused_agree():
     b = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED)
     for k in ("O", "dQ", "dK", "dV"):
         check(k, download(a[k]), download(b[k]), "bf16")
+
+
+def test_fused_path_is_deterministic():
+    """No atomics anywhere: two runs on the same inputs give the same bits."""
+    cfg = cfg_of(2, 2, 768, 3, causal=True, seed=23)
+    x = inputs.make_inputs(cfg)
+    a = gpu_forward_backward(cfg, x)
+    b = gpu_forward_backward(cfg, x)
+    for k in ("O", "LSE", "dQ", "dK", "dV"):
+        assert torch.equal(a[k], b[k]), k
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_chunk_of_64_rows_and_single_rank_of_many(causal):
+    """Smallest chunk (c = 64, N = 16) for the whole ring, and one middle rank of it."""
+    for rb, re in ((0, -1), (7, 8)):
+        cfg = cfg_of(1, 2, 1024, 16, causal=causal, rb=rb, re=re, seed=29)
+        x = inputs.make_inputs(cfg)
+        out = gpu_forward_backward(cfg, x)
+        compare_heads(cfg, x, out, [0, 1])
+
+
+def test_outputs_do_not_depend_on_buffer_contents():
+    """dQ, dK, dV, O are overwritten, not accumulated into (buffers pre-filled with NaN)."""
+    cfg = cfg_of(1, 2, 384, 3, seed=31)
+    x = inputs.make_inputs(cfg)
+    Q, K, V, dO = (upload(x[k], "bf16") for k in ("Q", "K", "V", "dO"))
+    desc = rsa.make_desc(K, cfg.N)
+    nan = lambda t: torch.full_like(t, float("nan"))
+    O, LSE = rsa.forward(desc, Q, K, V, O=nan(Q), LSE=torch.full(Q.shape[:3], float("nan"), device="cuda"))
+    ws = torch.full((rsa.workspace_bytes(desc, True),), 0xFF, dtype=torch.uint8, device="cuda")
+    dQ, dK, dV = rsa.backward(desc, dO, Q, K, V, O, LSE, dQ=nan(Q), dK=nan(K), dV=nan(V), ws=ws)
+    torch.cuda.synchronize()
+    compare_heads(cfg, x, dict(O=O, LSE=LSE, dQ=dQ, dK=dK, dV=dV), [0, 1])
+
+
+def test_backward_parts_equal_the_whole():
+    """rsa_backward = rsa_bwd_preprocess + rsa_bwd_dkdv + rsa_bwd_dq, bit for bit."""
+    cfg = cfg_of(1, 3, 512, 4, causal=True, seed=37)
+    x = inputs.make_inputs(cfg)
+    Q, K, V, dO = (upload(x[k], "bf16") for k in ("Q", "K", "V", "dO"))
+    desc = rsa.make_desc(K, cfg.N, causal=True)
+    O, LSE = rsa.forward(desc, Q, K, V)
+    dQ, dK, dV = rsa.backward(desc, dO, Q, K, V, O, LSE)
+    ws = torch.empty(rsa.workspace_bytes(desc, True), dtype=torch.uint8, device="cuda")
+    dQ2, dK2, dV2 = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    rsa.bwd_preprocess(desc, dO, O, Q, ws)
+    rsa.bwd_dkdv(desc, dO, K, V, LSE, ws, dK2, dV2)
+    rsa.bwd_dq(desc, dO, Q, K, V, LSE, ws, dQ2)
+    torch.cuda.synchronize()
+    assert torch.equal(dQ, dQ2) and torch.equal(dK, dK2) and torch.equal(dV, dV2)
+
+
+def test_error_codes_on_the_device_path():
+    cfg = cfg_of(1, 1, 128, 2, seed=41)
+    x = inputs.make_inputs(cfg)
+    Q, K, V = (upload(x[k], "bf16") for k in ("Q", "K", "V"))
+    desc = rsa.make_desc(K, 3)                      # 128 % 3 != 0
+    with pytest.raises(rsa.RSAError) as e:
+        rsa.forward(desc, Q, K, V)
+    assert e.value.status == -2
+    desc = rsa.make_desc(K, 2)
+    O, LSE = rsa.forward(desc, Q, K, V)
+    with pytest.raises(rsa.RSAError) as e:          # backward workspace too small
+        rsa.backward(desc, Q, Q, K, V, O, LSE, ws=torch.empty(64, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == -4
