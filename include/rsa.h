@@ -141,22 +141,22 @@ int rsa_store(const rsa_desc *d, const float *src, void *dst, size_t count,
  * The kernels of the fused backward on their own (bf16, fused mode), for
  * profiling and tests; rsa_backward = these three in this order, on one
  * workspace `ws` of rsa_workspace_bytes(d, 1) bytes.
- *  rsa_bwd_preprocess: fills ws with D_i = sum_a dO_ia O_ia (fp32) and with Qs,
- *    a bf16 copy of Q multiplied by s * log2(e), the operand from which both
- *    other kernels recompute P = exp2(Qs K^T - LSE log2 e) tile by tile.
+ *  rsa_bwd_preprocess: fills ws with the row terms -D_i = -sum_a dO_ia O_ia and
+ *    -LSE_i log2(e) (fp32) and with Qs, a bf16 copy of Q multiplied by
+ *    s * log2(e), the operand from which both other kernels recompute
+ *    P = exp2(Qs K^T - LSE log2 e) tile by tile.  The other two read ws only.
  *  rsa_bwd_dkdv: for every key chunk, the walk over the query rows of all
  *    simulated ranks -- dV = sum_n P^T dO, dK = s sum_n dS^T Q (the sums the
  *    ring all-reduces, section 3.2.2).  Also forms dP = dO V^T for its tiles.
  *  rsa_bwd_dq: for every rank, the K ring pass dQ^n = s sum_j dS^n_j K^j.
  */
 int rsa_bwd_preprocess(const rsa_desc *d, const void *dO, const void *O,
-                       const void *Q, void *ws, size_t ws_bytes, void *stream);
+                       const void *Q, const float *LSE, void *ws,
+                       size_t ws_bytes, void *stream);
 int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *K, const void *V,
-                 const float *LSE, const void *ws, void *dK, void *dV,
-                 void *stream);
+                 const void *ws, void *dK, void *dV, void *stream);
 int rsa_bwd_dq(const rsa_desc *d, const void *dO, const void *Q, const void *K,
-               const void *V, const float *LSE, const void *ws, void *dQ,
-               void *stream);
+               const void *V, const void *ws, void *dQ, void *stream);
 
 #ifdef __cplusplus
 }

@@ -59,17 +59,20 @@ StagedWs staged_layout(const Dims &d, int dtype, int pass) {
 
 size_t workspace_bytes(const Dims &d, int dtype, unsigned flags, int pass) {
   if (flags == RSA_MODE_STAGED) return staged_layout(d, dtype, pass).total;
-  if (pass == 1) {  // D (fp32 per row), then Qs (pre-scaled bf16 copy of Q)
+  if (pass == 1) {  // -D and -LSE log2e (fp32 per row), then Qs (pre-scaled bf16 copy of Q)
     const size_t rows = (size_t)d.B * d.Z * d.Lq;
-    return align256(rows * 4) + align256(rows * d.A * 2);
+    return 2 * align256(rows * 4) + align256(rows * d.A * 2);
   }
   return 0;
 }
 
-// Fused backward workspace: D at the start, Qs after it.
-inline float *fused_D(void *ws) { return static_cast<float *>(ws); }
+// Fused backward workspace: -D at the start, -LSE log2e next, Qs after them.
+inline float *fused_nD(void *ws) { return static_cast<float *>(ws); }
+inline float *fused_nL(const Dims &d, void *ws) {
+  return reinterpret_cast<float *>(static_cast<char *>(ws) + align256((size_t)d.B * d.Z * d.Lq * 4));
+}
 inline void *fused_Qs(const Dims &d, void *ws) {
-  return static_cast<char *>(ws) + align256((size_t)d.B * d.Z * d.Lq * 4);
+  return static_cast<char *>(ws) + 2 * align256((size_t)d.B * d.Z * d.Lq * 4);
 }
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? RSA_OK : RSA_ERR_HIP; }
@@ -218,8 +221,8 @@ int rsa_backward(const rsa_desc *d, const void *dO, const void *Q, const void *K
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (d->flags == RSA_MODE_STAGED)
     return staged_backward(dm, d->dtype, dO, Q, K, V, O, dQ, dK, dV, static_cast<char *>(ws), st);
-  return hip_status(rsa::fused_backward(dm, dO, Q, K, V, O, LSE, dQ, dK, dV, fused_D(ws),
-                                        fused_Qs(dm, ws), st));
+  return hip_status(rsa::fused_backward(dm, dO, Q, K, V, O, LSE, dQ, dK, dV, fused_nD(ws),
+                                        fused_nL(dm, ws), fused_Qs(dm, ws), st));
 }
 
 // ------------------------------------------------------------ step level ----
@@ -298,27 +301,30 @@ int rsa_store(const rsa_desc *d, const float *src, void *dst, size_t count, void
   return hip_status(rsa::store_rows(d->dtype, src, dst, 1, 1, (int64_t)count, 0, 0, st));
 }
 
-int rsa_bwd_preprocess(const rsa_desc *d, const void *dO, const void *O, const void *Q, void *ws,
-                       size_t ws_bytes, void *stream) {
-  RSA_STEP_PROLOGUE(dO && O && Q, dO, O, Q, ws);
+int rsa_bwd_preprocess(const rsa_desc *d, const void *dO, const void *O, const void *Q,
+                       const float *LSE, void *ws, size_t ws_bytes, void *stream) {
+  RSA_STEP_PROLOGUE(dO && O && Q && LSE, dO, O, Q, LSE, ws);
   if (d->dtype != RSA_BF16 || d->flags != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
   if (!ws || ws_bytes < workspace_bytes(dm, d->dtype, d->flags, 1)) return RSA_ERR_WORKSPACE;
-  return hip_status(rsa::fused_bwd_preprocess(dm, dO, O, Q, fused_D(ws), fused_Qs(dm, ws), st));
+  return hip_status(rsa::fused_bwd_preprocess(dm, dO, O, Q, LSE, fused_nD(ws), fused_nL(dm, ws),
+                                              fused_Qs(dm, ws), st));
 }
 
-int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *K, const void *V, const float *LSE,
-                 const void *ws, void *dK, void *dV, void *stream) {
-  RSA_STEP_PROLOGUE(dO && K && V && LSE && ws && dK && dV, dO, K, V, LSE, ws, dK, dV);
+int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *K, const void *V, const void *ws,
+                 void *dK, void *dV, void *stream) {
+  RSA_STEP_PROLOGUE(dO && K && V && ws && dK && dV, dO, K, V, ws, dK, dV);
   if (d->dtype != RSA_BF16 || d->flags != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
   void *w = const_cast<void *>(ws);
-  return hip_status(rsa::fused_bwd_dkdv(dm, dO, fused_Qs(dm, w), K, V, LSE, fused_D(w), dK, dV, st));
+  return hip_status(rsa::fused_bwd_dkdv(dm, dO, fused_Qs(dm, w), K, V, fused_nL(dm, w), fused_nD(w),
+                                        dK, dV, st));
 }
 
 int rsa_bwd_dq(const rsa_desc *d, const void *dO, const void *Q, const void *K, const void *V,
-               const float *LSE, const void *ws, void *dQ, void *stream) {
-  RSA_STEP_PROLOGUE(dO && Q && K && V && LSE && ws && dQ, dO, Q, K, V, LSE, ws, dQ);
+               const void *ws, void *dQ, void *stream) {
+  RSA_STEP_PROLOGUE(dO && Q && K && V && ws && dQ, dO, Q, K, V, ws, dQ);
   if (d->dtype != RSA_BF16 || d->flags != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
-  return hip_status(rsa::fused_bwd_dq(dm, dO, Q, K, V, LSE, fused_D(const_cast<void *>(ws)), dQ, st));
+  void *w = const_cast<void *>(ws);
+  return hip_status(rsa::fused_bwd_dq(dm, dO, Q, K, V, fused_nL(dm, w), fused_nD(w), dQ, st));
 }
 
 }  // extern "C"

@@ -72,6 +72,12 @@ __device__ __forceinline__ void lds_dma16(const void *gsrc, void *lds_base) {
   typedef __attribute__((address_space(3))) void *lptr_t;
   __builtin_amdgcn_global_load_lds((gptr_t)gsrc, (lptr_t)lds_base, 16, 0, 0);
 }
+// Same, 4 bytes per lane: lane l's dword lands at lds_base + 4 l.
+__device__ __forceinline__ void lds_dma4(const void *gsrc, void *lds_base) {
+  typedef __attribute__((address_space(1))) const void *gptr_t;
+  typedef __attribute__((address_space(3))) void *lptr_t;
+  __builtin_amdgcn_global_load_lds((gptr_t)gsrc, (lptr_t)lds_base, 4, 0, 0);
+}
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0)
 
 // Exchange between the two lanes l and l^32 (the two halves of a 32x32

@@ -2,7 +2,7 @@
 // with the ring structure of section 3.2.2, without the score strip in memory.
 // P is recomputed from Q, K and the forward's LSE: P = exp(s QK^T - LSE).
 //
-//   preprocess: D = rowsum(dO o O) and Qs = bf16(Q * s * log2 e).
+//   preprocess: the row terms -D = -rowsum(dO o O) and -LSE log2e, and Qs = bf16(Q * s * log2 e).
 //   dkdv kernel: a work-group owns 4*32 keys and walks the query tiles of every
 //     simulated rank, starting with the rank that holds those keys (ring
 //     order); the sum over ranks that the ring would all-reduce is its loop.
@@ -20,7 +20,7 @@ namespace rsa {
 
 struct BwdArgs {
   const uint16_t *Q, *Qs, *K, *V, *dO;  // Qs = bf16(Q * scale * log2 e)
-  const float *LSE, *D;
+  const float *nL, *nD;                 // -LSE log2e and -D per query row
   uint16_t *dQ, *dK, *dV;
   int64_t L, c, Lq, q0;
   int N, tiles_per_head;
@@ -28,10 +28,12 @@ struct BwdArgs {
 };
 
 // ------------------------------------------------------------- preprocess ---
-// D_i = sum_a dO_ia O_ia and Qs = bf16(Q * scale * log2 e): 8 lanes x 8 elements per row.
+// nD_i = -sum_a dO_ia O_ia, nL_i = -LSE_i log2e and Qs = bf16(Q * scale * log2 e):
+// 8 lanes x 8 elements per row.
 __global__ void __launch_bounds__(256) bwd_preprocess_kernel(const uint16_t *dO, const uint16_t *O,
-                                                             const uint16_t *Q, float *D,
-                                                             uint16_t *Qs, int64_t rows, float cl2) {
+                                                             const uint16_t *Q, const float *LSE,
+                                                             float *nD, float *nL, uint16_t *Qs,
+                                                             int64_t rows, float cl2) {
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t row = gid >> 3;
   const int sub = (int)(gid & 7);
@@ -51,7 +53,10 @@ __global__ void __launch_bounds__(256) bwd_preprocess_kernel(const uint16_t *dO,
   acc += __shfl_xor(acc, 1);
   acc += __shfl_xor(acc, 2);
   acc += __shfl_xor(acc, 4);
-  if (row < rows && sub == 0) D[row] = acc;
+  if (row < rows && sub == 0) {
+    nD[row] = -acc;
+    nL[row] = -LSE[row] * kLog2e;
+  }
 }
 
 // ------------------------------------------------------------------ dK, dV ---
@@ -67,10 +72,13 @@ template <int NQ, bool CAUSAL>
 __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
   constexpr int KW = 32;      // keys per wave
   constexpr int BK = 4 * KW;  // keys per work-group
-  __shared__ __attribute__((aligned(16))) unsigned char Qs[2][NQ][kTileBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char dOs[2][NQ][kTileBytes];
-  __shared__ __attribute__((aligned(16))) float lse_s[2][NQ][64];
-  __shared__ __attribute__((aligned(16))) float d_s[2][NQ][64];
+  // The two stage buffers are separate objects, each addressed by name, so that the
+  // compiler knows a direct load into one cannot alias the LDS reads of the other.
+  struct Stage {
+    unsigned char Qs[NQ][kTileBytes], dOs[NQ][kTileBytes];
+    float lse[NQ][64], d[NQ][64];
+  };
+  __shared__ __attribute__((aligned(16))) Stage stage0, stage1;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -84,8 +92,8 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
   const uint16_t *dOh = a.dO + head * a.Lq * 64;
   const uint16_t *Kh = a.K + head * a.L * 64;
   const uint16_t *Vh = a.V + head * a.L * 64;
-  const float *LSEh = a.LSE + head * a.Lq;
-  const float *Dh = a.D + head * a.Lq;
+  const float *nLh = a.nL + head * a.Lq;
+  const float *nDh = a.nD + head * a.Lq;
 
   // K and V rows of this wave as B operands: lane (col, half) holds row
   // key = wkey0 + col, elements dk*16 + half*8 .. +8.
@@ -124,28 +132,31 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
   auto advance = [&](int i) { ++i; while (i < nst && !visible(i)) ++i; return i; };
 
   const TileDMA dma(wave, lane);
-  auto load_stage = [&](int i, int buf) {
+  auto load_stage = [&](int i, Stage &sn) __attribute__((always_inline)) {
     const int st = st_of(i);
 #pragma unroll
     for (int u = 0; u < NQ; ++u) {
       int qt = st * NQ + u;
       if (qt >= nqt) qt = nqt - 1;  // past the last tile: refetch it (never used)
       const int64_t r0 = (int64_t)qt * 64;
-      dma.load(Qh + r0 * 64, Qs[buf][u]);
-      dma.load(dOh + r0 * 64, dOs[buf][u]);
-      if (tid < 64) lse_s[buf][u][tid] = -LSEh[r0 + tid] * kLog2e;
-      else if (tid < 128) d_s[buf][u][tid - 64] = -Dh[r0 + tid - 64];
+      dma.load(Qh + r0 * 64, sn.Qs[u]);
+      dma.load(dOh + r0 * 64, sn.dOs[u]);
+      // the 64 row terms of the tile, one dword per lane: waves 0/1 fetch -LSE log2e, 2/3 fetch -D
+      if ((wave & 1) == (u & 1)) {
+        if (wave < 2) lds_dma4(nLh + r0 + lane, sn.lse[u]);
+        else lds_dma4(nDh + r0 + lane, sn.d[u]);
+      }
     }
   };
 
   int i = visible(0) ? 0 : advance(0);
-  int buf = 0;
-  if (i < nst) load_stage(i, 0);
+  if (i < nst) load_stage(i, stage0);
   wait_vmem();
   __syncthreads();
-  while (i < nst) {
+  // one stage: start the loads of the next stage into sn, compute on sc
+  auto stage = [&](Stage &sc, Stage &sn) __attribute__((always_inline)) {
     const int inext = advance(i);
-    if (inext < nst) load_stage(inext, buf ^ 1);
+    if (inext < nst) load_stage(inext, sn);
 
 #pragma unroll
     for (int u = 0; u < NQ; ++u) {
@@ -160,15 +171,15 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
           f32x16 s, dp;
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
-            const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&lse_s[buf][u][qb * 32 + g * 8 + half * 4]);
-            const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&d_s[buf][u][qb * 32 + g * 8 + half * 4]);
+            const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&sc.lse[u][qb * 32 + g * 8 + half * 4]);
+            const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&sc.d[u][qb * 32 + g * 8 + half * 4]);
 #pragma unroll
             for (int e = 0; e < 4; ++e) { s[g * 4 + e] = l4[e]; dp[g * 4 + e] = d4[e]; }
           }
 #pragma unroll
           for (int dk = 0; dk < 4; ++dk) {
-            const bf16x8 qa = tl.read_rows(Qs[buf][u], qb * 32, dk);
-            const bf16x8 ga = tl.read_rows(dOs[buf][u], qb * 32, dk);
+            const bf16x8 qa = tl.read_rows(sc.Qs[u], qb * 32, dk);
+            const bf16x8 ga = tl.read_rows(sc.dOs[u], qb * 32, dk);
             s = mfma_32x32x16(qa, kreg[dk], s);
             dp = mfma_32x32x16(ga, vreg[dk], dp);
           }
@@ -197,8 +208,8 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
         for (int db = 0; db < 2; ++db)
 #pragma unroll
           for (int kk = 0; kk < 4; ++kk) {
-            const bf16x8 ga = tl.read_cols(dOs[buf][u], kk * 16, db);
-            const bf16x8 qa = tl.read_cols(Qs[buf][u], kk * 16, db);
+            const bf16x8 ga = tl.read_cols(sc.dOs[u], kk * 16, db);
+            const bf16x8 qa = tl.read_cols(sc.Qs[u], kk * 16, db);
             dv[db] = mfma_32x32x16(ga, pf[kk], dv[db]);
             dk_[db] = mfma_32x32x16(qa, sf[kk], dk_[db]);
           }
@@ -207,8 +218,12 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
 
     wait_vmem();
     __syncthreads();
-    buf ^= 1;
     i = inext;
+  };
+  while (i < nst) {
+    stage(stage0, stage1);
+    if (i >= nst) break;
+    stage(stage1, stage0);
   }
 
   uint16_t *dKh = a.dK + head * a.L * 64;
@@ -236,8 +251,9 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   constexpr int QB = R / 32;
   constexpr int BM = 4 * R;
   constexpr int NK = 2;  // key tiles per stage (one barrier per stage)
-  __shared__ __attribute__((aligned(16))) unsigned char Ks[2][NK][kTileBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char Vs[2][NK][kTileBytes];
+  // two named stage buffers: see the dK/dV kernel
+  __shared__ __attribute__((aligned(16))) unsigned char Ks0[NK][kTileBytes], Ks1[NK][kTileBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Vs0[NK][kTileBytes], Vs1[NK][kTileBytes];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -271,8 +287,8 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
           *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * 64 + dk * 16 + half * 8), a.cl2);
       greg[qb][dk] = *reinterpret_cast<const bf16x8 *>(dOh + qrow[qb] * 64 + dk * 16 + half * 8);
     }
-    const float l2 = -a.LSE[head * a.Lq + qrow[qb]] * kLog2e;
-    const float dd = -a.D[head * a.Lq + qrow[qb]];
+    const float l2 = a.nL[head * a.Lq + qrow[qb]];
+    const float dd = a.nD[head * a.Lq + qrow[qb]];
 #pragma unroll
     for (int v = 0; v < 16; ++v) { negl[qb][v] = l2; negd[qb][v] = dd; }
   }
@@ -308,26 +324,27 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
     }
   };
   const TileDMA dma(wave, lane);
-  auto load_stage = [&](int64_t k0, int buf) {
+  auto load_stage = [&](int64_t k0, auto &Kn, auto &Vn) __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < NK; ++u) {
       if (u < nk) {
-        dma.load(Kh + (k0 + u * kTileKeys) * 64, Ks[buf][u]);
-        dma.load(Vh + (k0 + u * kTileKeys) * 64, Vs[buf][u]);
+        dma.load(Kh + (k0 + u * kTileKeys) * 64, Kn[u]);
+        dma.load(Vh + (k0 + u * kTileKeys) * 64, Vn[u]);
       }
     }
   };
 
-  int t = 0, kt = 0, buf = 0;
-  load_stage(k0_of(0, 0), 0);
+  int t = 0, kt = 0;
+  load_stage(k0_of(0, 0), Ks0, Vs0);
   wait_vmem();
   __syncthreads();
   bool have = true;
-  while (have) {
+  // one stage: start the loads of the next stage into (Kn, Vn), compute on (Kc, Vc)
+  auto stage = [&](auto &Kc, auto &Vc, auto &Kn, auto &Vn) __attribute__((always_inline)) {
     const int64_t ks0 = k0_of(t, kt);
     int t2 = t, kt2 = kt;
     const bool have_next = advance(t2, kt2);
-    if (have_next) load_stage(k0_of(t2, kt2), buf ^ 1);
+    if (have_next) load_stage(k0_of(t2, kt2), Kn, Vn);
 
 #pragma unroll
     for (int u = 0; u < NK; ++u) {
@@ -340,8 +357,8 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
         f32x16 s[QB], dp[QB];
 #pragma unroll
         for (int dk = 0; dk < 4; ++dk) {
-          const bf16x8 ka = tl.read_rows(Ks[buf][u], kb * 32, dk);
-          const bf16x8 va = tl.read_rows(Vs[buf][u], kb * 32, dk);
+          const bf16x8 ka = tl.read_rows(Kc[u], kb * 32, dk);
+          const bf16x8 va = tl.read_rows(Vc[u], kb * 32, dk);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) {
             s[qb] = mfma_32x32x16(ka, qreg[qb][dk], dk == 0 ? negl[qb] : s[qb]);
@@ -372,7 +389,7 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
       for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-          const bf16x8 ka = tl.read_cols(Ks[buf][u], kk * 16, db);
+          const bf16x8 ka = tl.read_cols(Kc[u], kk * 16, db);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) dq[db][qb] = mfma_32x32x16(ka, sf[qb][kk], dq[db][qb]);
         }
@@ -382,7 +399,12 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
 
     wait_vmem();
     __syncthreads();
-    buf ^= 1; t = t2; kt = kt2; have = have_next;
+    t = t2; kt = kt2; have = have_next;
+  };
+  while (have) {
+    stage(Ks0, Vs0, Ks1, Vs1);
+    if (!have) break;
+    stage(Ks1, Vs1, Ks0, Vs0);
   }
 
   uint16_t *dQh = a.dQ + head * a.Lq * 64;
@@ -403,12 +425,12 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
 }
 
 static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const void *Qs,
-                             const void *K, const void *V, const float *LSE, const float *D,
+                             const void *K, const void *V, const float *nL, const float *nD,
                              void *dQ, void *dK, void *dV) {
   BwdArgs a;
   a.Q = (const uint16_t *)Q; a.Qs = (const uint16_t *)Qs;
   a.K = (const uint16_t *)K; a.V = (const uint16_t *)V;
-  a.dO = (const uint16_t *)dO; a.LSE = LSE; a.D = D;
+  a.dO = (const uint16_t *)dO; a.nL = nL; a.nD = nD;
   a.dQ = (uint16_t *)dQ; a.dK = (uint16_t *)dK; a.dV = (uint16_t *)dV;
   a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.q0 = (int64_t)d.rank_begin * d.c;
   a.N = d.N; a.cl2 = d.scale * kLog2e; a.scale = d.scale;
@@ -417,19 +439,19 @@ static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const
 }
 
 hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, const void *Q,
-                                float *D, void *Qs, hipStream_t st) {
+                                const float *LSE, float *nD, float *nL, void *Qs, hipStream_t st) {
   const int64_t rows = (int64_t)d.B * d.Z * d.Lq;
   dim3 grid((unsigned)((rows * 8 + 255) / 256));
   hipLaunchKernelGGL(bwd_preprocess_kernel, grid, dim3(256), 0, st, (const uint16_t *)dO,
-                     (const uint16_t *)O, (const uint16_t *)Q, D, (uint16_t *)Qs, rows,
+                     (const uint16_t *)O, (const uint16_t *)Q, LSE, nD, nL, (uint16_t *)Qs, rows,
                      d.scale * kLog2e);
   return hipGetLastError();
 }
 
 hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Qs, const void *K,
-                          const void *V, const float *LSE, const float *D, void *dK, void *dV,
+                          const void *V, const float *nL, const float *nD, void *dK, void *dV,
                           hipStream_t st) {
-  BwdArgs a = make_bwd_args(d, dO, nullptr, Qs, K, V, LSE, D, nullptr, dK, dV);
+  BwdArgs a = make_bwd_args(d, dO, nullptr, Qs, K, V, nL, nD, nullptr, dK, dV);
   a.tiles_per_head = (int)((d.L + 127) / 128);
   dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head));
   if (d.causal)
@@ -440,8 +462,8 @@ hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Qs, const v
 }
 
 hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void *K, const void *V,
-                        const float *LSE, const float *D, void *dQ, hipStream_t st) {
-  BwdArgs a = make_bwd_args(d, dO, Q, nullptr, K, V, LSE, D, dQ, nullptr, nullptr);
+                        const float *nL, const float *nD, void *dQ, hipStream_t st) {
+  BwdArgs a = make_bwd_args(d, dO, Q, nullptr, K, V, nL, nD, dQ, nullptr, nullptr);
   a.tiles_per_head = (int)((d.Lq + 127) / 128);
   dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head));
   if (d.causal)
@@ -453,12 +475,12 @@ hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void
 
 hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const void *K,
                           const void *V, const void *O, const float *LSE, void *dQ, void *dK,
-                          void *dV, float *D, void *Qs, hipStream_t st) {
-  hipError_t e = fused_bwd_preprocess(d, dO, O, Q, D, Qs, st);
+                          void *dV, float *nD, float *nL, void *Qs, hipStream_t st) {
+  hipError_t e = fused_bwd_preprocess(d, dO, O, Q, LSE, nD, nL, Qs, st);
   if (e != hipSuccess) return e;
-  e = fused_bwd_dkdv(d, dO, Qs, K, V, LSE, D, dK, dV, st);
+  e = fused_bwd_dkdv(d, dO, Qs, K, V, nL, nD, dK, dV, st);
   if (e != hipSuccess) return e;
-  return fused_bwd_dq(d, dO, Q, K, V, LSE, D, dQ, st);
+  return fused_bwd_dq(d, dO, Q, K, V, nL, nD, dQ, st);
 }
 
 }  // namespace rsa

@@ -34,8 +34,11 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
   constexpr int QB = R / 32;
   constexpr int BM = 4 * R;
   constexpr int NK = 2;  // key tiles per stage (one barrier per stage)
-  __shared__ __attribute__((aligned(16))) unsigned char Ks[2][NK][kTileBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char Vs[2][NK][kTileBytes];
+  // The two stage buffers are separate objects, each addressed by name: the compiler then
+  // knows that a direct load into one buffer cannot alias the LDS reads of the other and
+  // does not wait for the load before them.
+  __shared__ __attribute__((aligned(16))) unsigned char Ks0[NK][kTileBytes], Ks1[NK][kTileBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Vs0[NK][kTileBytes], Vs1[NK][kTileBytes];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -100,26 +103,27 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
     }
   };
   const TileDMA dma(wave, lane);
-  auto load_stage = [&](int64_t k0, int buf) {
+  auto load_stage = [&](int64_t k0, auto &Kn, auto &Vn) __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < NK; ++u) {
       if (u < nk) {
-        dma.load(Kh + (k0 + u * kTileKeys) * 64, Ks[buf][u]);
-        dma.load(Vh + (k0 + u * kTileKeys) * 64, Vs[buf][u]);
+        dma.load(Kh + (k0 + u * kTileKeys) * 64, Kn[u]);
+        dma.load(Vh + (k0 + u * kTileKeys) * 64, Vn[u]);
       }
     }
   };
 
-  int t = 0, kt = 0, buf = 0;
-  load_stage(k0_of(0, 0), 0);
+  int t = 0, kt = 0;
+  load_stage(k0_of(0, 0), Ks0, Vs0);
   wait_vmem();
   __syncthreads();
   bool have = true;
-  while (have) {
+  // one stage: start the loads of the next stage into (Kn, Vn), compute on (Kc, Vc)
+  auto stage = [&](auto &Kc, auto &Vc, auto &Kn, auto &Vn) __attribute__((always_inline)) {
     const int64_t ks0 = k0_of(t, kt);
     int t2 = t, kt2 = kt;
     const bool have_next = advance(t2, kt2);
-    if (have_next) load_stage(k0_of(t2, kt2), buf ^ 1);
+    if (have_next) load_stage(k0_of(t2, kt2), Kn, Vn);
 
 #pragma unroll
     for (int u = 0; u < NK; ++u) {
@@ -131,7 +135,7 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
       for (int kb = 0; kb < 2; ++kb) {
         bf16x8 ka[4];
 #pragma unroll
-        for (int dk = 0; dk < 4; ++dk) ka[dk] = tl.read_rows(Ks[buf][u], kb * 32, dk);
+        for (int dk = 0; dk < 4; ++dk) ka[dk] = tl.read_rows(Kc[u], kb * 32, dk);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
@@ -208,7 +212,7 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
       for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-          const bf16x8 va = tl.read_cols(Vs[buf][u], kk * 16, db);
+          const bf16x8 va = tl.read_cols(Vc[u], kk * 16, db);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) o[db][qb] = mfma_32x32x16(va, pf[qb][kk], o[db][qb]);
         }
@@ -218,7 +222,12 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
 
     wait_vmem();
     __syncthreads();
-    buf ^= 1; t = t2; kt = kt2; have = have_next;
+    t = t2; kt = kt2; have = have_next;
+  };
+  while (have) {
+    stage(Ks0, Vs0, Ks1, Vs1);
+    if (!have) break;
+    stage(Ks1, Vs1, Ks0, Vs0);
   }
 
   // ---- epilogue: O = O^T / l, LSE = s m + ln l

@@ -33,16 +33,16 @@ hipError_t store_rows(int dtype, const float *src, void *dst, int64_t batches,
 // --- fused (online-softmax) path, bf16, A = 64 ---
 hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void *V, void *O,
                          float *LSE, hipStream_t st);
-// D = rowsum(dO o O) (B,Z,Lq) fp32 and Qs = bf16(Q * scale * log2 e) (B,Z,Lq,64)
+// nD = -rowsum(dO o O) and nL = -LSE log2e, (B,Z,Lq) fp32; Qs = bf16(Q * scale * log2 e) (B,Z,Lq,64)
 hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, const void *Q,
-                                float *D, void *Qs, hipStream_t st);
+                                const float *LSE, float *nD, float *nL, void *Qs, hipStream_t st);
 hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Qs, const void *K,
-                          const void *V, const float *LSE, const float *D, void *dK, void *dV,
+                          const void *V, const float *nL, const float *nD, void *dK, void *dV,
                           hipStream_t st);
 hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void *K, const void *V,
-                        const float *LSE, const float *D, void *dQ, hipStream_t st);
+                        const float *nL, const float *nD, void *dQ, hipStream_t st);
 hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const void *K,
                           const void *V, const void *O, const float *LSE, void *dQ, void *dK,
-                          void *dV, float *D, void *Qs, hipStream_t st);
+                          void *dV, float *nD, float *nL, void *Qs, hipStream_t st);
 
 }  // namespace rsa

@@ -71,7 +71,7 @@ def test_workspace_sizes_follow_table2():
     strip = 2 * 3 * 128 * 512
     assert rsa.workspace_bytes(d, False) >= strip * 4 + strip * 2
     assert rsa.workspace_bytes(desc(), False) == 0            # fused forward: no strip
-    assert rsa.workspace_bytes(desc(), True) == 1 * 2 * 256 * 4 + 1 * 2 * 256 * 64 * 2   # D and Qs
+    assert rsa.workspace_bytes(desc(), True) == 2 * (1 * 2 * 256 * 4) + 1 * 2 * 256 * 64 * 2   # row terms and Qs
     assert rsa.workspace_bytes(desc(N=3), True) == 0          # invalid descriptor
     for s in range(-5, 1):
         assert rsa.strerror(s)

@@ -150,9 +150,9 @@ def test_backward_parts_equal_the_whole():
     dQ, dK, dV = rsa.backward(desc, dO, Q, K, V, O, LSE)
     ws = torch.empty(rsa.workspace_bytes(desc, True), dtype=torch.uint8, device="cuda")
     dQ2, dK2, dV2 = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
-    rsa.bwd_preprocess(desc, dO, O, Q, ws)
-    rsa.bwd_dkdv(desc, dO, K, V, LSE, ws, dK2, dV2)
-    rsa.bwd_dq(desc, dO, Q, K, V, LSE, ws, dQ2)
+    rsa.bwd_preprocess(desc, dO, O, Q, LSE, ws)
+    rsa.bwd_dkdv(desc, dO, K, V, ws, dK2, dV2)
+    rsa.bwd_dq(desc, dO, Q, K, V, ws, dQ2)
     torch.cuda.synchronize()
     assert torch.equal(dQ, dQ2) and torch.equal(dK, dK2) and torch.equal(dV, dV2)
 
