@@ -31,8 +31,11 @@ MEASURED_TRAFFIC_BYTES = {"bert_large": 204.6e6}
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    # The chip needs on the order of 100 ms of back-to-back launches before its clocks settle:
+    # kernel times measured over 20 launches are about 10 % longer than over 1000.  The
+    # defaults (set in main) give about 0.2 s of warm-up and 1.5 s of timed steps.
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="bert_large",
                     choices=["bert_base", "bert_large", "long_32k", "rank15_64k_causal"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -96,7 +99,9 @@ def time_workload(cfg, steps, warmup, torch, rsa, inputs, per_kernel=True):
     res = {"ms_per_step": ms, "tflops": cfg.flops() / (ms * 1e-3) / 1e12,
            "tokens_per_s": cfg.B * cfg.Lq / (ms * 1e-3)}
     if per_kernel:
-        it = max(3, min(steps, 20))
+        it = max(3, min(steps, 400))
+        for _ in range(min(warmup, 50)):   # keep the clocks up between the two timed regions
+            step()
         k = {
             "fwd": event_ms(fwd, it, torch),
             "bwd_preprocess": event_ms(lambda: rsa.bwd_preprocess(desc, t["dO"], b["O"], t["Q"], b["LSE"],
@@ -180,6 +185,12 @@ def main():
         return 2
     rsa.lib()   # fails loudly if the HIP library is not built
     cfg = inputs.CONFIGS[a.workload]
+    # default step count: about as many flops as 2000 steps of bert_large
+    scale = inputs.CONFIGS["bert_large"].flops() / cfg.flops()
+    if a.steps is None:
+        a.steps = int(min(5000, max(20, round(2000 * scale))))
+    if a.warmup is None:
+        a.warmup = int(min(1000, max(5, round(300 * scale))))
     res, x = time_workload(cfg, a.steps, a.warmup, torch, rsa, inputs)
     k = res["kernel_ms"]
     # dominant kernel: dK/dV.  Algorithmic flops per launch: the dV, dK and dP
@@ -207,7 +218,9 @@ def main():
             if name == cfg.name:
                 continue
             c2 = inputs.CONFIGS[name]
-            r2, _ = time_workload(c2, 5, 2, torch, rsa, inputs)
+            s2 = inputs.CONFIGS["bert_large"].flops() / c2.flops()
+            r2, _ = time_workload(c2, int(min(2000, max(10, round(500 * s2)))),
+                                  int(min(300, max(3, round(100 * s2)))), torch, rsa, inputs)
             other[name] = {"tflops": round(r2["tflops"], 2), "ms_per_step": round(r2["ms_per_step"], 4),
                            "kernel_ms": {n: round(v, 4) for n, v in r2["kernel_ms"].items()}}
         out["other_workloads"] = other

@@ -184,11 +184,12 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
             dp = mfma_32x32x16(ga, vreg[dk], dp);
           }
           if (domask) {
+            // first visible row of the lane's key, relative to the block of 32 rows (32-bit compare)
+            const int64_t d64 = wkey0 + col - qf - qb * 32 - half * 4;
+            const int dfirst = d64 < -64 ? -64 : (int)d64;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int64_t qg = qf + qb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-              if (wkey0 + col > qg) s[v] = -INFINITY;
-            }
+            for (int v = 0; v < 16; ++v)
+              if ((v >> 2) * 8 + (v & 3) < dfirst) s[v] = -INFINITY;
           }
 #pragma unroll
           for (int w2 = 0; w2 < 2; ++w2) {
@@ -367,14 +368,13 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
         }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-          const int64_t qg = a.q0 + qrow[qb];
+          // last visible key of the lane's row, relative to the block of 32 keys (32-bit compare)
+          const int64_t d64 = a.q0 + qrow[qb] - k0 - kb * 32 - half * 4;
+          const int dlast = d64 > 64 ? 64 : (int)d64;
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             float x = s[qb][v];
-            if (domask) {
-              const int64_t kg = k0 + kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-              if (kg > qg) x = -INFINITY;
-            }
+            if (domask && (v >> 2) * 8 + (v & 3) > dlast) x = -INFINITY;
             dp[qb][v] *= __builtin_amdgcn_exp2f(x);
           }
 #pragma unroll

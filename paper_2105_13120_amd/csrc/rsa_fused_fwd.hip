@@ -147,14 +147,14 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
       if (CAUSAL && k0 + kTileKeys - 1 > wq_first) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-          const int64_t qg = a.q0 + qrow[qb];
+          // last visible key of the lane's row, relative to the tile (clamped: 32-bit compare)
+          const int64_t d64 = a.q0 + qrow[qb] - k0 - half * 4;
+          const int dlast = d64 > 64 ? 64 : (int)d64;
 #pragma unroll
           for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int64_t kg = k0 + kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-              if (kg > qg) s[kb][qb][v] = -INFINITY;
-            }
+            for (int v = 0; v < 16; ++v)
+              if (kb * 32 + (v >> 2) * 8 + (v & 3) > dlast) s[kb][qb][v] = -INFINITY;
         }
       }
       // ---- running max; the accumulators are rescaled only when some row's max
