@@ -158,62 +158,107 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
     const int inext = advance(i);
     if (inext < nst) load_stage(inext, sn);
 
+    // The 32 MFMAs of a tile go in four groups of eight -- S', dP' of rows 0..31 (G0) and of
+    // rows 32..63 (G1), then dV, dK over rows 0..31 (H0) and 32..63 (H1) -- and the vector work
+    // of each half (V0, V1) sits beside the next group: G0 | G1 + V0 | H0 + V1 | H1.  MFMA and
+    // vector instructions of one wave overlap only when they alternate in its instruction
+    // stream, and an LDS read costs its full latency unless issued a phase early, so the
+    // phases are fenced, every read after the tile's first is issued one phase before its
+    // use, and the compiler interleaves inside a phase.
+    bf16x8 qa[2][4], ga[2][4];
+    f32x16 sacc[2], dpacc[2];
+    const int qt0 = st_of(i) * NQ;
+    auto active = [&](int u) {
+      const int qt = qt0 + u;
+      return qt < nqt && (!CAUSAL || a.q0 + (int64_t)qt * 64 + 63 >= wkey0);
+    };
+    auto fetch = [&](int u, int qb) __attribute__((always_inline)) {
+      // accumulators start from -LSE log2e and -D of their rows (same for all lanes of a half)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&sc.lse[u][qb * 32 + g * 8 + half * 4]);
+        const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&sc.d[u][qb * 32 + g * 8 + half * 4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { sacc[qb][g * 4 + e] = l4[e]; dpacc[qb][g * 4 + e] = d4[e]; }
+      }
+#pragma unroll
+      for (int dk = 0; dk < 4; ++dk) {
+        qa[qb][dk] = tl.read_rows(sc.Qs[u], qb * 32, dk);
+        ga[qb][dk] = tl.read_rows(sc.dOs[u], qb * 32, dk);
+      }
+    };
 #pragma unroll
     for (int u = 0; u < NQ; ++u) {
-      const int qt = st_of(i) * NQ + u;
-      const int64_t qf = a.q0 + (int64_t)qt * 64;  // global index of the tile's first row
-      if (qt < nqt && (!CAUSAL || qf + 63 >= wkey0)) {
+      if (active(u)) {
+        const int64_t qf = a.q0 + (int64_t)(qt0 + u) * 64;  // global index of the tile's first row
         const bool domask = CAUSAL && qf < wkey0 + KW - 1;
         bf16x8 pf[4], sf[4];  // [kk]: P and dS as B operands, k = query
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-          // accumulators start from -LSE log2e and -D of their rows (same for all lanes of a half)
-          f32x16 s, dp;
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&sc.lse[u][qb * 32 + g * 8 + half * 4]);
-            const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&sc.d[u][qb * 32 + g * 8 + half * 4]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { s[g * 4 + e] = l4[e]; dp[g * 4 + e] = d4[e]; }
-          }
+        auto g12 = [&](int qb) __attribute__((always_inline)) {
 #pragma unroll
           for (int dk = 0; dk < 4; ++dk) {
-            const bf16x8 qa = tl.read_rows(sc.Qs[u], qb * 32, dk);
-            const bf16x8 ga = tl.read_rows(sc.dOs[u], qb * 32, dk);
-            s = mfma_32x32x16(qa, kreg[dk], s);
-            dp = mfma_32x32x16(ga, vreg[dk], dp);
+            sacc[qb] = mfma_32x32x16(qa[qb][dk], kreg[dk], sacc[qb]);
+            dpacc[qb] = mfma_32x32x16(ga[qb][dk], vreg[dk], dpacc[qb]);
           }
+        };
+        auto softmax_bwd = [&](int qb) __attribute__((always_inline)) {
+          f32x16 &sv = sacc[qb];
+          const f32x16 &dp = dpacc[qb];
           if (domask) {
             // first visible row of the lane's key, relative to the block of 32 rows (32-bit compare)
             const int64_t d64 = wkey0 + col - qf - qb * 32 - half * 4;
             const int dfirst = d64 < -64 ? -64 : (int)d64;
 #pragma unroll
             for (int v = 0; v < 16; ++v)
-              if ((v >> 2) * 8 + (v & 3) < dfirst) s[v] = -INFINITY;
+              if ((v >> 2) * 8 + (v & 3) < dfirst) sv[v] = -INFINITY;
           }
 #pragma unroll
           for (int w2 = 0; w2 < 2; ++w2) {
             u32x4 w, x;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const float p0 = __builtin_amdgcn_exp2f(s[w2 * 8 + 2 * e]);
-              const float p1 = __builtin_amdgcn_exp2f(s[w2 * 8 + 2 * e + 1]);
+              const float p0 = __builtin_amdgcn_exp2f(sv[w2 * 8 + 2 * e]);
+              const float p1 = __builtin_amdgcn_exp2f(sv[w2 * 8 + 2 * e + 1]);
               w[e] = pack_bf16(p0, p1);
               x[e] = pack_bf16(p0 * dp[w2 * 8 + 2 * e], p1 * dp[w2 * 8 + 2 * e + 1]);
             }
             pf[qb * 2 + w2] = __builtin_bit_cast(bf16x8, w);
             sf[qb * 2 + w2] = __builtin_bit_cast(bf16x8, x);
           }
-        }
+        };
+        bf16x8 gt[2][2][2], qt2[2][2][2];  // [qb][kk & 1][db]: dO^T and Qs^T fragments
+        auto fetch_t = [&](int qb) __attribute__((always_inline)) {
 #pragma unroll
-        for (int db = 0; db < 2; ++db)
+          for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-          for (int kk = 0; kk < 4; ++kk) {
-            const bf16x8 ga = tl.read_cols(sc.dOs[u], kk * 16, db);
-            const bf16x8 qa = tl.read_cols(sc.Qs[u], kk * 16, db);
-            dv[db] = mfma_32x32x16(ga, pf[kk], dv[db]);
-            dk_[db] = mfma_32x32x16(qa, sf[kk], dk_[db]);
-          }
+            for (int db = 0; db < 2; ++db) {
+              gt[qb][k2][db] = tl.read_cols(sc.dOs[u], (qb * 2 + k2) * 16, db);
+              qt2[qb][k2][db] = tl.read_cols(sc.Qs[u], (qb * 2 + k2) * 16, db);
+            }
+        };
+        auto g34 = [&](int qb) __attribute__((always_inline)) {
+#pragma unroll
+          for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+            for (int db = 0; db < 2; ++db) {
+              dv[db] = mfma_32x32x16(gt[qb][k2][db], pf[qb * 2 + k2], dv[db]);
+              dk_[db] = mfma_32x32x16(qt2[qb][k2][db], sf[qb * 2 + k2], dk_[db]);
+            }
+        };
+        fetch(u, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(u, 1);
+        g12(0);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch_t(0);
+        g12(1);
+        softmax_bwd(0);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch_t(1);
+        g34(0);
+        softmax_bwd(1);
+        __builtin_amdgcn_sched_barrier(0);
+        g34(1);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
 
