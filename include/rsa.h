@@ -48,9 +48,17 @@ typedef enum {
 
 typedef enum { RSA_F32 = 0, RSA_BF16 = 1 } rsa_dtype;
 
-/* flags */
+/* flags: one mode, optionally or-ed with an ownership bit */
 #define RSA_MODE_FUSED 0u  /* online-softmax kernels, no score strip in HBM   */
 #define RSA_MODE_STAGED 1u /* the paper's two-pass layout: strip S^n in HBM   */
+/* Zig-zag chunk ownership (fused mode only; an extension for the causal mask, which
+ * the paper leaves open in section 3.1): the sequence is cut into 2N half-chunks of
+ * h = c/2 rows and rank n owns half-chunks n and 2N-1-n, so that every rank sees the
+ * same number of keys under the causal mask.  The c local rows of rank n in
+ * Q, O, dO, dQ, LSE are then tokens [n h, (n+1) h) followed by tokens
+ * [(2N-1-n) h, (2N-n) h); K, V, dK, dV stay in token order.  Ring step t of rank n
+ * visits the two half-chunks of rank (n - t) mod N.  Needs h divisible by 64. */
+#define RSA_OWN_ZIGZAG 2u
 
 typedef struct {
   int32_t B, Z, A;   /* batch, heads, head size                              */
@@ -61,7 +69,7 @@ typedef struct {
                      /* query i iff j <= i in global token index (extension) */
   int32_t dtype;     /* rsa_dtype of Q, K, V, O, dO, dQ, dK, dV              */
   float scale;       /* 1/sqrt(d_k) of Eq. 1; 0 selects 1/sqrt(A)            */
-  uint32_t flags;    /* RSA_MODE_FUSED or RSA_MODE_STAGED                    */
+  uint32_t flags;    /* RSA_MODE_FUSED or RSA_MODE_STAGED [| RSA_OWN_ZIGZAG] */
 } rsa_desc;
 
 int rsa_version(void);

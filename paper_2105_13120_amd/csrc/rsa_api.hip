@@ -15,15 +15,19 @@ int validate(const rsa_desc *d, Dims *out) {
   if (d->rank_begin < 0 || d->rank_end > d->N || d->rank_begin >= d->rank_end) return RSA_ERR_SHAPE;
   if (d->A != 64) return RSA_ERR_UNSUPPORTED;
   if (d->dtype != RSA_F32 && d->dtype != RSA_BF16) return RSA_ERR_UNSUPPORTED;
-  if (d->flags != RSA_MODE_FUSED && d->flags != RSA_MODE_STAGED) return RSA_ERR_UNSUPPORTED;
-  if (d->flags == RSA_MODE_FUSED && d->dtype != RSA_BF16) return RSA_ERR_UNSUPPORTED;
+  if (d->flags & ~(RSA_MODE_STAGED | RSA_OWN_ZIGZAG)) return RSA_ERR_UNSUPPORTED;
+  const int mode = (int)(d->flags & RSA_MODE_STAGED);
+  const int zigzag = (d->flags & RSA_OWN_ZIGZAG) ? 1 : 0;
+  if (mode == RSA_MODE_FUSED && d->dtype != RSA_BF16) return RSA_ERR_UNSUPPORTED;
   const int64_t c = d->L / d->N;
   if (c % 64 != 0) return RSA_ERR_UNSUPPORTED;
+  if (zigzag && (mode == RSA_MODE_STAGED || c % 128 != 0)) return RSA_ERR_UNSUPPORTED;
   if (!(d->scale >= 0.0f) || !std::isfinite(d->scale)) return RSA_ERR_SHAPE;
   if ((int64_t)d->B * d->Z > 65535) return RSA_ERR_UNSUPPORTED;  // heads ride on gridDim.z
   out->B = d->B; out->Z = d->Z; out->A = d->A; out->N = d->N;
   out->rank_begin = d->rank_begin; out->rank_end = d->rank_end;
   out->causal = d->causal ? 1 : 0;
+  out->mode = mode; out->zigzag = zigzag;
   out->L = d->L; out->c = c; out->Lq = (int64_t)(d->rank_end - d->rank_begin) * c;
   out->scale = d->scale > 0.0f ? d->scale : 1.0f / std::sqrt((float)d->A);
   return RSA_OK;
@@ -57,8 +61,8 @@ StagedWs staged_layout(const Dims &d, int dtype, int pass) {
   return w;
 }
 
-size_t workspace_bytes(const Dims &d, int dtype, unsigned flags, int pass) {
-  if (flags == RSA_MODE_STAGED) return staged_layout(d, dtype, pass).total;
+size_t workspace_bytes(const Dims &d, int dtype, int pass) {
+  if (d.mode == RSA_MODE_STAGED) return staged_layout(d, dtype, pass).total;
   if (pass == 1) {  // -D and -LSE log2e (fp32 per row), then Qs (pre-scaled bf16 copy of Q)
     const size_t rows = (size_t)d.B * d.Z * d.Lq;
     return 2 * align256(rows * 4) + align256(rows * d.A * 2);
@@ -187,7 +191,7 @@ const char *rsa_strerror(int status) {
 size_t rsa_workspace_bytes(const rsa_desc *d, int pass) {
   Dims dm;
   if (validate(d, &dm) != RSA_OK || (pass != 0 && pass != 1)) return 0;
-  return workspace_bytes(dm, d->dtype, d->flags, pass);
+  return workspace_bytes(dm, d->dtype, pass);
 }
 
 int rsa_forward(const rsa_desc *d, const void *Q, const void *K, const void *V, void *O, float *LSE,
@@ -198,10 +202,10 @@ int rsa_forward(const rsa_desc *d, const void *Q, const void *K, const void *V, 
   if (!Q || !K || !V || !O || !LSE) return RSA_ERR_NULL;
   if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(LSE) || misaligned(ws))
     return RSA_ERR_UNSUPPORTED;
-  const size_t need = workspace_bytes(dm, d->dtype, d->flags, 0);
+  const size_t need = workspace_bytes(dm, d->dtype, 0);
   if (need > 0 && (!ws || ws_bytes < need)) return RSA_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (d->flags == RSA_MODE_STAGED)
+  if (dm.mode == RSA_MODE_STAGED)
     return staged_forward(dm, d->dtype, Q, K, V, O, LSE, static_cast<char *>(ws), st);
   return hip_status(rsa::fused_forward(dm, Q, K, V, O, LSE, st));
 }
@@ -216,10 +220,10 @@ int rsa_backward(const rsa_desc *d, const void *dO, const void *Q, const void *K
   if (misaligned(dO) || misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) ||
       misaligned(LSE) || misaligned(dQ) || misaligned(dK) || misaligned(dV) || misaligned(ws))
     return RSA_ERR_UNSUPPORTED;
-  const size_t need = workspace_bytes(dm, d->dtype, d->flags, 1);
+  const size_t need = workspace_bytes(dm, d->dtype, 1);
   if (!ws || ws_bytes < need) return RSA_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (d->flags == RSA_MODE_STAGED)
+  if (dm.mode == RSA_MODE_STAGED)
     return staged_backward(dm, d->dtype, dO, Q, K, V, O, dQ, dK, dV, static_cast<char *>(ws), st);
   return hip_status(rsa::fused_backward(dm, dO, Q, K, V, O, LSE, dQ, dK, dV, fused_nD(ws),
                                         fused_nL(dm, ws), fused_Qs(dm, ws), st));
@@ -304,8 +308,8 @@ int rsa_store(const rsa_desc *d, const float *src, void *dst, size_t count, void
 int rsa_bwd_preprocess(const rsa_desc *d, const void *dO, const void *O, const void *Q,
                        const float *LSE, void *ws, size_t ws_bytes, void *stream) {
   RSA_STEP_PROLOGUE(dO && O && Q && LSE, dO, O, Q, LSE, ws);
-  if (d->dtype != RSA_BF16 || d->flags != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
-  if (!ws || ws_bytes < workspace_bytes(dm, d->dtype, d->flags, 1)) return RSA_ERR_WORKSPACE;
+  if (d->dtype != RSA_BF16 || dm.mode != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < workspace_bytes(dm, d->dtype, 1)) return RSA_ERR_WORKSPACE;
   return hip_status(rsa::fused_bwd_preprocess(dm, dO, O, Q, LSE, fused_nD(ws), fused_nL(dm, ws),
                                               fused_Qs(dm, ws), st));
 }
@@ -313,7 +317,7 @@ int rsa_bwd_preprocess(const rsa_desc *d, const void *dO, const void *O, const v
 int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *K, const void *V, const void *ws,
                  void *dK, void *dV, void *stream) {
   RSA_STEP_PROLOGUE(dO && K && V && ws && dK && dV, dO, K, V, ws, dK, dV);
-  if (d->dtype != RSA_BF16 || d->flags != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
+  if (d->dtype != RSA_BF16 || dm.mode != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
   void *w = const_cast<void *>(ws);
   return hip_status(rsa::fused_bwd_dkdv(dm, dO, fused_Qs(dm, w), K, V, fused_nL(dm, w), fused_nD(w),
                                         dK, dV, st));
@@ -322,7 +326,7 @@ int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *K, const void *V
 int rsa_bwd_dq(const rsa_desc *d, const void *dO, const void *Q, const void *K, const void *V,
                const void *ws, void *dQ, void *stream) {
   RSA_STEP_PROLOGUE(dO && Q && K && V && ws && dQ, dO, Q, K, V, ws, dQ);
-  if (d->dtype != RSA_BF16 || d->flags != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
+  if (d->dtype != RSA_BF16 || dm.mode != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
   void *w = const_cast<void *>(ws);
   return hip_status(rsa::fused_bwd_dq(dm, dO, Q, K, V, fused_nL(dm, w), fused_nD(w), dQ, st));
 }

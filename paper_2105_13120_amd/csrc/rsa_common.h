@@ -128,8 +128,43 @@ __device__ __forceinline__ uint32_t xcd_remap(uint32_t id, uint32_t n) {
 // Derived sizes of a validated descriptor, shared by host code and kernels.
 struct Dims {
   int B, Z, A, N, rank_begin, rank_end, causal;
+  int mode;    // RSA_MODE_FUSED or RSA_MODE_STAGED
+  int zigzag;  // 1: rank n owns half-chunks n and 2N-1-n (RSA_OWN_ZIGZAG)
   int64_t L, c, Lq;
   float scale;
 };
+
+// Which global token a local query row is.  Contiguous ownership (the paper, section 3.1):
+// rank n owns rows [n c, (n+1) c).  Zig-zag ownership: the sequence is cut into 2N
+// half-chunks of h = c/2 rows and rank n owns half-chunks n and 2N-1-n, stored in that
+// order, so that under the causal mask every rank sees the same number of keys.
+// h is a multiple of 64: the 64 rows of a tile are consecutive tokens in both layouts.
+struct RowMap {
+  int64_t q0, c, h;
+  int rb, last_half;  // first simulated rank; 2N - 1
+  int zigzag;
+  __host__ __device__ int64_t operator()(int64_t r) const {
+    if (!zigzag) return q0 + r;
+    const int64_t rho = rb + r / c, w = r % c;
+    return w < h ? rho * h + w : (last_half - rho) * h + (w - h);
+  }
+  // first key of the rows [w, ...) of the chunk (pair of half-chunks) that rank j owns
+  __host__ __device__ int64_t key_of(int j, int64_t w) const {
+    if (!zigzag) return (int64_t)j * c + w;
+    return w < h ? (int64_t)j * h + w : (int64_t)(last_half - j) * h + (w - h);
+  }
+  // rank that owns global token g
+  __host__ __device__ int owner(int64_t g) const {
+    if (!zigzag) return (int)(g / c);
+    const int hc = (int)(g / h);
+    return hc <= last_half / 2 ? hc : last_half - hc;
+  }
+};
+inline RowMap make_row_map(const Dims &d) {
+  RowMap m;
+  m.q0 = (int64_t)d.rank_begin * d.c; m.c = d.c; m.h = d.c / 2;
+  m.rb = d.rank_begin; m.last_half = 2 * d.N - 1; m.zigzag = d.zigzag;
+  return m;
+}
 
 }  // namespace rsa

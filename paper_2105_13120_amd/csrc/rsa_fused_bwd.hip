@@ -22,7 +22,8 @@ struct BwdArgs {
   const uint16_t *Q, *Qs, *K, *V, *dO;  // Qs = bf16(Q * scale * log2 e)
   const float *nL, *nD;                 // -LSE log2e and -D per query row
   uint16_t *dQ, *dK, *dV;
-  int64_t L, c, Lq, q0;
+  int64_t L, c, Lq;
+  RowMap map;  // local query row -> global token index
   int N, tiles_per_head;
   float cl2, scale;
 };
@@ -121,13 +122,19 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
   const int nst = (nqt + NQ - 1) / NQ;
   int start = 0;
   {
-    const int64_t r = (key0 / a.c) * a.c - a.q0;  // local row of that rank's first query
+    const int64_t r = (int64_t)(a.map.owner(key0) - a.map.rb) * a.c;  // local row of that rank's first query
     if (r >= 0 && r < a.Lq) start = (int)(r / (64 * NQ));
   }
   auto st_of = [&](int i) { int q = start + i; return q >= nst ? q - nst : q; };
-  // a stage matters if its last row can see the first key of the work-group
+  // a stage matters if some row of it can see the first key of the work-group
   auto visible = [&](int i) {
-    return !CAUSAL || a.q0 + (int64_t)(st_of(i) + 1) * (64 * NQ) - 1 >= key0;
+    if (!CAUSAL) return true;
+    const int qt = st_of(i) * NQ;
+    bool v = false;
+#pragma unroll
+    for (int u = 0; u < NQ; ++u)
+      v = v || (qt + u < nqt && a.map((int64_t)(qt + u) * 64) + 63 >= key0);
+    return v;
   };
   auto advance = [&](int i) { ++i; while (i < nst && !visible(i)) ++i; return i; };
 
@@ -170,7 +177,7 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
     const int qt0 = st_of(i) * NQ;
     auto active = [&](int u) {
       const int qt = qt0 + u;
-      return qt < nqt && (!CAUSAL || a.q0 + (int64_t)qt * 64 + 63 >= wkey0);
+      return qt < nqt && (!CAUSAL || a.map((int64_t)qt * 64) + 63 >= wkey0);
     };
     auto fetch = [&](int u, int qb) __attribute__((always_inline)) {
       // accumulators start from -LSE log2e and -D of their rows (same for all lanes of a half)
@@ -190,7 +197,7 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
 #pragma unroll
     for (int u = 0; u < NQ; ++u) {
       if (active(u)) {
-        const int64_t qf = a.q0 + (int64_t)(qt0 + u) * 64;  // global index of the tile's first row
+        const int64_t qf = a.map((int64_t)(qt0 + u) * 64);  // token of the tile's first row
         const bool domask = CAUSAL && qf < wkey0 + KW - 1;
         bf16x8 pf[4], sf[4];  // [kk]: P and dS as B operands, k = query
         auto g12 = [&](int qb) __attribute__((always_inline)) {
@@ -306,11 +313,21 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   const int col = lane & 31, half = lane >> 5;
   const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x);
   const int64_t head = wg / a.tiles_per_head;
-  const int64_t row0 = (wg % a.tiles_per_head) * BM;
-  const int64_t q_first = a.q0 + row0;
-  const int64_t q_last = a.q0 + (row0 + BM < a.Lq ? row0 + BM : a.Lq) - 1;
-  const int n = (int)(q_first / a.c);
-  const int tpc = (int)(a.c / kTileKeys);  // tiles per chunk
+  // under the causal mask later rows see more keys: the long work-groups of a head start first
+  const int64_t row0 =
+      (CAUSAL ? a.tiles_per_head - 1 - wg % a.tiles_per_head : wg % a.tiles_per_head) * BM;
+  const int n = a.map.rb + (int)(row0 / a.c);  // rank that owns the first row
+  // last token any row of the work-group may look at (its 64-row tiles are runs of tokens)
+  int64_t q_last = 0;
+#pragma unroll
+  for (int i = 0; i < BM / 64; ++i)
+    if (row0 + i * 64 < a.Lq) {
+      const int64_t e = a.map(row0 + i * 64) + 63;
+      q_last = e > q_last ? e : q_last;
+    }
+  // tiles per run of consecutive tokens of a chunk: the chunk, or its half under zig-zag ownership
+  const int tpc = (int)(a.c / kTileKeys);
+  const int tpr = a.map.zigzag ? tpc / 2 : tpc;
 
   const uint16_t *Qh = a.Q + head * a.Lq * 64;
   const uint16_t *dOh = a.dO + head * a.Lq * 64;
@@ -322,11 +339,14 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   // over an accumulator, are what S'^T and dP'^T start from.
   bf16x8 qreg[QB][4], greg[QB][4];
   int64_t qrow[QB];
+  int64_t qtok[QB];  // global token index of the lane's row
   f32x16 negl[QB], negd[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const int64_t r = row0 + wave * R + qb * 32 + col;
     qrow[qb] = r < a.Lq ? r : a.Lq - 1;
+    const int64_t blk = row0 + wave * R + qb * 32;  // the block of 32 rows is whole or absent
+    qtok[qb] = a.map(blk < a.Lq ? blk : a.Lq - 32) + col;
 #pragma unroll
     for (int dk = 0; dk < 4; ++dk) {
       qreg[qb][dk] = scale_bf16x8(
@@ -338,8 +358,10 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
 #pragma unroll
     for (int v = 0; v < 16; ++v) { negl[qb][v] = l2; negd[qb][v] = dd; }
   }
-  const int64_t wq_first = a.q0 + (row0 + wave * R < a.Lq ? row0 + wave * R : a.Lq - 1);
-  const int64_t wq_last = a.q0 + (row0 + wave * R + R - 1 < a.Lq ? row0 + wave * R + R - 1 : a.Lq - 1);
+  // first and last token of this wave's rows (R <= 64 rows inside one tile: a run of tokens)
+  const int64_t wrow = row0 + wave * R < a.Lq ? row0 + wave * R : a.Lq - R;
+  const int64_t wq_first = a.map(wrow);
+  const int64_t wq_last = wq_first + R - 1;
 
   const TileLanes tl(lane);
 
@@ -353,12 +375,12 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
 
   // The ring walk: ring step t visits chunk (n - t) mod N.  Tiles are taken NK at a time;
   // a stage never straddles chunks when tiles-per-chunk is even, otherwise NK falls to 1.
-  const int nk = (tpc % NK == 0) ? NK : 1;
+  const int nk = (tpr % NK == 0) ? NK : 1;
   const int spc = tpc / nk;  // stages per chunk
   auto k0_of = [&](int t, int ks) -> int64_t {
     int j = n - t;
     if (j < 0) j += a.N;
-    return (int64_t)j * a.c + (int64_t)ks * nk * kTileKeys;
+    return a.map.key_of(j, (int64_t)ks * nk * kTileKeys);
   };
   auto advance = [&](int &t, int &ks) -> bool {
     ++ks;
@@ -414,7 +436,7 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
           // last visible key of the lane's row, relative to the block of 32 keys (32-bit compare)
-          const int64_t d64 = a.q0 + qrow[qb] - k0 - kb * 32 - half * 4;
+          const int64_t d64 = qtok[qb] - k0 - kb * 32 - half * 4;
           const int dlast = d64 > 64 ? 64 : (int)d64;
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
@@ -477,7 +499,7 @@ static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const
   a.K = (const uint16_t *)K; a.V = (const uint16_t *)V;
   a.dO = (const uint16_t *)dO; a.nL = nL; a.nD = nD;
   a.dQ = (uint16_t *)dQ; a.dK = (uint16_t *)dK; a.dV = (uint16_t *)dV;
-  a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.q0 = (int64_t)d.rank_begin * d.c;
+  a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.map = make_row_map(d);
   a.N = d.N; a.cl2 = d.scale * kLog2e; a.scale = d.scale;
   a.tiles_per_head = 0;
   return a;

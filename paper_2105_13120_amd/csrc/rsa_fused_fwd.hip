@@ -24,7 +24,8 @@ struct FwdArgs {
   const uint16_t *Q, *K, *V;
   uint16_t *O;
   float *LSE;
-  int64_t L, c, Lq, q0;  // q0: global token index of Q row 0
+  int64_t L, c, Lq;
+  RowMap map;            // local query row -> global token index
   int N, tiles_per_head;
   float cl2;             // scale * log2(e)
 };
@@ -45,12 +46,21 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
   const int col = lane & 31, half = lane >> 5;
   const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x);
   const int64_t head = wg / a.tiles_per_head;
-  const int64_t qt = wg % a.tiles_per_head;
+  // under the causal mask later rows see more keys: the long work-groups of a head start first
+  const int64_t qt = CAUSAL ? a.tiles_per_head - 1 - wg % a.tiles_per_head : wg % a.tiles_per_head;
   const int64_t row0 = qt * BM;  // first local row of this work-group
-  const int64_t q_first = a.q0 + row0;
-  const int64_t q_last = a.q0 + (row0 + BM < a.Lq ? row0 + BM : a.Lq) - 1;
-  const int n = (int)(q_first / a.c);  // rank that owns the first row
+  const int n = a.map.rb + (int)(row0 / a.c);  // rank that owns the first row
+  // last token any row of the work-group may look at (its 64-row tiles are runs of tokens)
+  int64_t q_last = 0;
+#pragma unroll
+  for (int i = 0; i < BM / 64; ++i)
+    if (row0 + i * 64 < a.Lq) {
+      const int64_t e = a.map(row0 + i * 64) + 63;
+      q_last = e > q_last ? e : q_last;
+    }
+  // tiles per run of consecutive tokens of a chunk: the chunk, or its half under zig-zag ownership
   const int tpc = (int)(a.c / kTileKeys);
+  const int tpr = a.map.zigzag ? tpc / 2 : tpc;
 
   const uint16_t *Qh = a.Q + head * a.Lq * 64;
   const uint16_t *Kh = a.K + head * a.L * 64;
@@ -59,16 +69,21 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
   // Q^T operand: lane (col, half) holds Q[row][dk*16 + half*8 .. +8]
   bf16x8 qreg[QB][4];
   int64_t qrow[QB];  // local row (clamped to the last row for a ragged tail)
+  int64_t qtok[QB];  // its global token index
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     int64_t r = row0 + wave * R + qb * 32 + col;
     qrow[qb] = r < a.Lq ? r : a.Lq - 1;
+    const int64_t blk = row0 + wave * R + qb * 32;  // the block of 32 rows is whole or absent
+    qtok[qb] = a.map(blk < a.Lq ? blk : a.Lq - 32) + col;
 #pragma unroll
     for (int dk = 0; dk < 4; ++dk)
       qreg[qb][dk] = *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * 64 + dk * 16 + half * 8);
   }
-  const int64_t wq_first = a.q0 + (row0 + wave * R < a.Lq ? row0 + wave * R : a.Lq - 1);
-  const int64_t wq_last = a.q0 + (row0 + wave * R + R - 1 < a.Lq ? row0 + wave * R + R - 1 : a.Lq - 1);
+  // first and last token of this wave's rows (R <= 64 rows inside one tile: a run of tokens)
+  const int64_t wrow = row0 + wave * R < a.Lq ? row0 + wave * R : a.Lq - R;
+  const int64_t wq_first = a.map(wrow);
+  const int64_t wq_last = wq_first + R - 1;
 
   const TileLanes tl(lane);
 
@@ -85,12 +100,12 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
 
   // The ring walk: ring step t visits chunk (n - t) mod N.  Tiles are taken NK at a time;
   // a stage never straddles chunks when tiles-per-chunk is even, otherwise NK falls to 1.
-  const int nk = (tpc % NK == 0) ? NK : 1;
+  const int nk = (tpr % NK == 0) ? NK : 1;
   const int spc = tpc / nk;  // stages per chunk
   auto k0_of = [&](int t, int ks) -> int64_t {
     int j = n - t;
     if (j < 0) j += a.N;
-    return (int64_t)j * a.c + (int64_t)ks * nk * kTileKeys;
+    return a.map.key_of(j, (int64_t)ks * nk * kTileKeys);
   };
   // next stage of the ring walk that holds a visible key for some row of this work-group
   auto advance = [&](int &t, int &ks) -> bool {
@@ -148,7 +163,7 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
           // last visible key of the lane's row, relative to the tile (clamped: 32-bit compare)
-          const int64_t d64 = a.q0 + qrow[qb] - k0 - half * 4;
+          const int64_t d64 = qtok[qb] - k0 - half * 4;
           const int dlast = d64 > 64 ? 64 : (int)d64;
 #pragma unroll
           for (int kb = 0; kb < 2; ++kb)
@@ -266,7 +281,7 @@ hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void
   FwdArgs a;
   a.Q = (const uint16_t *)Q; a.K = (const uint16_t *)K; a.V = (const uint16_t *)V;
   a.O = (uint16_t *)O; a.LSE = LSE;
-  a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.q0 = (int64_t)d.rank_begin * d.c;
+  a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.map = make_row_map(d);
   a.N = d.N;
   a.cl2 = d.scale * kLog2e;
   const int64_t heads = (int64_t)d.B * d.Z;

@@ -30,6 +30,7 @@ class RSAConfig:
     qkv_scale: float = 1.0
     backward: bool = True
     seed: int = 0
+    zigzag: bool = False  # rank n owns half-chunks n and 2N-1-n instead of chunk n
 
     @property
     def c(self):
@@ -49,13 +50,25 @@ class RSAConfig:
         b, e = self.ranks
         return (e - b) * self.c
 
+    def segments(self):
+        """The local query rows as runs of consecutive tokens: a list of
+        (local_row, first_token, length), in local order."""
+        b, e = self.ranks
+        if not self.zigzag:
+            return [(0, b * self.c, (e - b) * self.c)]
+        h = self.c // 2
+        out = []
+        for n in range(b, e):
+            out.append(((n - b) * self.c, n * h, h))
+            out.append(((n - b) * self.c + h, (2 * self.N - 1 - n) * h, h))
+        return out
+
     def visible_pairs(self):
         """Number of (query, key) pairs per head that are not masked."""
         if not self.causal:
             return self.Lq * self.L
-        q0, lq = self.q0, self.Lq
         # row i (global) sees i + 1 keys
-        return lq * q0 + lq * (lq + 1) // 2
+        return sum(n * t0 + n * (n + 1) // 2 for _, t0, n in self.segments())
 
     def flops(self, backward=None):
         """Algorithmic flops: 4 per pair per head-dim forward, 8 backward."""

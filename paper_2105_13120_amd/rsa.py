@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_PKG, "librsa_hip.so")
 
 RSA_F32, RSA_BF16 = 0, 1
 MODE_FUSED, MODE_STAGED = 0, 1
+OWN_ZIGZAG = 2   # flag bit: rank n owns half-chunks n and 2N-1-n
 
 EXPORTS = (
     "rsa_version", "rsa_strerror", "rsa_workspace_bytes", "rsa_forward", "rsa_backward",
@@ -104,11 +105,13 @@ def _dtype_code(t):
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
-def make_desc(K, N, causal=False, rank_begin=0, rank_end=None, mode=MODE_FUSED, scale=0.0):
-    """Descriptor for K of shape (B, Z, L, A)."""
+def make_desc(K, N, causal=False, rank_begin=0, rank_end=None, mode=MODE_FUSED, scale=0.0,
+              zigzag=False):
+    """Descriptor for K of shape (B, Z, L, A).  zigzag: rank n owns half-chunks n and 2N-1-n."""
     B, Z, L, A = K.shape
     return RSADesc(B, Z, A, L, N, rank_begin, N if rank_end is None else rank_end,
-                   int(bool(causal)), _dtype_code(K), float(scale), int(mode))
+                   int(bool(causal)), _dtype_code(K), float(scale),
+                   int(mode) | (OWN_ZIGZAG if zigzag else 0))
 
 
 def workspace_bytes(desc, backward):

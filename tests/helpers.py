@@ -80,7 +80,8 @@ def gpu_forward_backward(cfg, x, mode=rsa.MODE_FUSED, backward=True):
     """Run the HIP path on cfg's inputs x (dict of numpy float32)."""
     Q, K, V = (upload(x[k], cfg.dtype) for k in ("Q", "K", "V"))
     rb, re = cfg.ranks
-    desc = rsa.make_desc(K, cfg.N, causal=cfg.causal, rank_begin=rb, rank_end=re, mode=mode)
+    desc = rsa.make_desc(K, cfg.N, causal=cfg.causal, rank_begin=rb, rank_end=re, mode=mode,
+                         zigzag=cfg.zigzag)
     O, LSE = rsa.forward(desc, Q, K, V)
     out = {"O": O, "LSE": LSE}
     if backward:
@@ -91,10 +92,31 @@ def gpu_forward_backward(cfg, x, mode=rsa.MODE_FUSED, backward=True):
     return out
 
 
+def oracle_on_segments(cfg, Qh, Kh, Vh, dOh=None):
+    """The oracle on cfg's local query rows: one call per run of consecutive tokens
+    (one run unless the ownership is zig-zag); O, LSE, dQ are put back in local row
+    order and the partial dK, dV of the runs are added."""
+    O = np.empty_like(Qh)
+    LSE = np.empty(Qh.shape[:3])
+    dQ = np.empty_like(Qh) if dOh is not None else None
+    dK = dV = None
+    for r0, t0, n in cfg.segments():
+        Qs = np.ascontiguousarray(Qh[:, :, r0:r0 + n])
+        O[:, :, r0:r0 + n], LSE[:, :, r0:r0 + n] = oracle.forward(Qs, Kh, Vh, q0=t0, causal=cfg.causal)
+        if dOh is not None:
+            g = oracle.backward(Qs, Kh, Vh, np.ascontiguousarray(dOh[:, :, r0:r0 + n]), q0=t0,
+                                causal=cfg.causal)
+            dQ[:, :, r0:r0 + n] = g[0]
+            dK = g[1] if dK is None else dK + g[1]
+            dV = g[2] if dV is None else dV + g[2]
+    return O, LSE, dQ, dK, dV
+
+
 def compare_heads(cfg, x, out, heads, backward=True):
     """Full comparison with the oracle on the listed flat head indices."""
     Qh, Kh, Vh = (heads_view(x[k], heads) for k in ("Q", "K", "V"))
-    O_ref, LSE_ref = oracle.forward(Qh, Kh, Vh, q0=cfg.q0, causal=cfg.causal)
+    dOh = heads_view(x["dO"], heads) if backward else None
+    O_ref, LSE_ref, dQ_ref, dK_ref, dV_ref = oracle_on_segments(cfg, Qh, Kh, Vh, dOh)
     errs = {}
     errs["O"] = check("O", heads_view(download(out["O"]), heads), O_ref, cfg.dtype)
     lse = download(out["LSE"]).reshape(-1, cfg.Lq)[heads][None]
@@ -102,8 +124,6 @@ def compare_heads(cfg, x, out, heads, backward=True):
     assert err <= LSE_ATOL, f"LSE: max abs err {err:.3e}"
     errs["LSE"] = err
     if backward:
-        dOh = heads_view(x["dO"], heads)
-        dQ_ref, dK_ref, dV_ref = oracle.backward(Qh, Kh, Vh, dOh, q0=cfg.q0, causal=cfg.causal)
         for name, ref in (("dQ", dQ_ref), ("dK", dK_ref), ("dV", dV_ref)):
             errs[name] = check(name, heads_view(download(out[name]), heads), ref, cfg.dtype)
     return errs

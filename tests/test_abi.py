@@ -49,6 +49,9 @@ def test_validation_happens_before_any_launch():
     assert fwd_status(desc(dtype=7)) == -3
     assert fwd_status(desc(dtype=rsa.RSA_F32)) == -3         # fused mode is bf16 only
     assert fwd_status(desc(flags=9)) == -3
+    assert fwd_status(desc(flags=rsa.MODE_STAGED | rsa.OWN_ZIGZAG)) == -3   # zig-zag: fused mode only
+    assert fwd_status(desc(L=256, N=4, flags=rsa.OWN_ZIGZAG)) == -3          # half-chunk of 32 rows
+    assert rsa.workspace_bytes(desc(L=512, N=4, flags=rsa.OWN_ZIGZAG), True) > 0
     assert fwd_status(desc(), ptr=0) == -1
     assert fwd_status(desc(), ptr=0x1008) == -3              # misaligned
     staged = desc(flags=rsa.MODE_STAGED)

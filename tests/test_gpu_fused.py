@@ -11,9 +11,9 @@ from paper_2105_13120_amd import inputs, rsa
 pytestmark = pytest.mark.gpu
 
 
-def cfg_of(B, Z, L, N, causal=False, rb=0, re=-1, seed=7, scale=1.0):
+def cfg_of(B, Z, L, N, causal=False, rb=0, re=-1, seed=7, scale=1.0, zigzag=False):
     return inputs.RSAConfig("t", B=B, Z=Z, L=L, A=64, N=N, dtype="bf16", causal=causal,
-                            rank_begin=rb, rank_end=re, seed=seed, qkv_scale=scale)
+                            rank_begin=rb, rank_end=re, seed=seed, qkv_scale=scale, zigzag=zigzag)
 
 
 # sizes that span several 64-key tiles, several work-groups and ragged tails
@@ -40,6 +40,42 @@ def test_fused_rank_subrange_gives_partial_sums(causal, rb, re):
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x)
     compare_heads(cfg, x, out, [0, 1])
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("B,Z,L,N,rb,re", [
+    (1, 2, 512, 4, 0, -1),      # whole ring, half-chunks of 64 rows
+    (1, 2, 1024, 4, 0, -1),     # half-chunks of 128 rows: two tiles per stage
+    (2, 2, 768, 3, 0, -1),      # odd ring size
+    (1, 2, 1536, 3, 1, 2),      # one rank's share (work-group straddles its two half-chunks)
+    (1, 1, 2048, 4, 3, 4),      # last rank: half-chunks 3 and 4 are neighbours
+    (1, 2, 1280, 5, 1, 4),      # three ranks of five
+    (1, 1, 4096, 2, 0, 1),      # half-chunks of 1024 rows: whole work-groups inside one half
+])
+def test_zigzag_ownership(B, Z, L, N, rb, re, causal):
+    """Rank n holds tokens of half-chunks n and 2N-1-n; the oracle is called once per run of
+    consecutive tokens and the runs' partial dK, dV are added."""
+    cfg = cfg_of(B, Z, L, N, causal, rb=rb, re=re, seed=13, zigzag=True)
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x)
+    compare_heads(cfg, x, out, list(range(B * Z)))
+
+
+def test_zigzag_whole_ring_is_a_row_permutation_of_the_contiguous_ring():
+    """Ownership only decides which rank holds a row: over the whole ring the outputs are
+    those of the contiguous layout, rows permuted (different summation order: tolerance)."""
+    cfg = cfg_of(1, 2, 1024, 4, True, seed=17)
+    zz = cfg_of(1, 2, 1024, 4, True, seed=17, zigzag=True)
+    x = inputs.make_inputs(cfg)
+    perm = np.concatenate([np.arange(t0, t0 + n) for _, t0, n in zz.segments()])
+    xz = dict(x, Q=np.ascontiguousarray(x["Q"][:, :, perm]), dO=np.ascontiguousarray(x["dO"][:, :, perm]))
+    a = {k: download(v) for k, v in gpu_forward_backward(cfg, x).items()}
+    b = {k: download(v) for k, v in gpu_forward_backward(zz, xz).items()}
+    check("O", b["O"], a["O"][:, :, perm], "bf16")
+    check("dQ", b["dQ"], a["dQ"][:, :, perm], "bf16")
+    check("dK", b["dK"], a["dK"], "bf16")
+    check("dV", b["dV"], a["dV"], "bf16")
+    assert np.abs(b["LSE"] - a["LSE"][:, :, perm]).max() <= LSE_ATOL
 
 
 def test_result_is_independent_of_the_ring_size():

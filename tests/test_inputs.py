@@ -46,3 +46,30 @@ def test_inputs_are_deterministic_and_rounded():
     h = inputs.make_inputs(small, heads=2)
     np.testing.assert_array_equal(h["K"][0, 1], x["K"][0, 1])
     assert h["Q"].shape == (1, 2, 32, 64)
+
+
+def test_zigzag_segments_cover_every_token_once_and_balance_the_causal_work():
+    """Rank n owns half-chunks n and 2N-1-n: the ranks' rows partition the sequence
+    and every rank sees the same number of keys under the causal mask."""
+    N, L = 8, 4096
+    seen = np.zeros(L, dtype=int)
+    work = []
+    for n in range(N):
+        cfg = inputs.RSAConfig("z", B=1, Z=1, L=L, A=64, N=N, dtype="bf16", causal=True,
+                               rank_begin=n, rank_end=n + 1, zigzag=True)
+        segs = cfg.segments()
+        assert [s[0] for s in segs] == [0, cfg.c // 2] and sum(s[2] for s in segs) == cfg.Lq
+        for _, t0, m in segs:
+            seen[t0:t0 + m] += 1
+        # brute force count of visible pairs
+        toks = np.concatenate([np.arange(t0, t0 + m) for _, t0, m in segs])
+        assert cfg.visible_pairs() == int((toks + 1).sum())
+        work.append(cfg.visible_pairs())
+    assert (seen == 1).all()
+    assert max(work) == min(work)
+    whole = inputs.RSAConfig("z", B=1, Z=1, L=L, A=64, N=N, dtype="bf16", causal=True, zigzag=True)
+    assert whole.visible_pairs() == L * (L + 1) // 2 == sum(work)
+    # contiguous ownership: the last rank has (2N - 1) times the work of the first
+    first = inputs.RSAConfig("c", B=1, Z=1, L=L, A=64, N=N, dtype="bf16", causal=True, rank_begin=0, rank_end=1)
+    last = inputs.RSAConfig("c", B=1, Z=1, L=L, A=64, N=N, dtype="bf16", causal=True, rank_begin=N - 1, rank_end=N)
+    assert last.visible_pairs() > 14 * first.visible_pairs()
