@@ -37,7 +37,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="bert_large",
-                    choices=["bert_base", "bert_large", "long_32k", "rank15_64k_causal"])
+                    choices=["bert_base", "bert_large", "long_32k", "rank15_64k_causal",
+                             "causal_ring_32k", "zigzag_rank0_64k_causal"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true", help="also time the other workloads briefly")
     ap.add_argument("--staged", action="store_true",
@@ -65,7 +66,7 @@ def setup(cfg, torch, rsa, inputs):
     dt = torch.bfloat16
     t = {k: torch.from_numpy(v).to(dt).cuda().contiguous() for k, v in x.items()}
     rb, re = cfg.ranks
-    desc = rsa.make_desc(t["K"], cfg.N, causal=cfg.causal, rank_begin=rb, rank_end=re)
+    desc = rsa.make_desc(t["K"], cfg.N, causal=cfg.causal, rank_begin=rb, rank_end=re, zigzag=cfg.zigzag)
     buf = dict(
         O=torch.empty_like(t["Q"]), LSE=torch.empty(t["Q"].shape[:3], dtype=torch.float32, device="cuda"),
         dQ=torch.empty_like(t["Q"]), dK=torch.empty_like(t["K"]), dV=torch.empty_like(t["V"]),
@@ -162,10 +163,13 @@ def cpu_baseline(cfg, x, inputs):
     sel = lambda a: np.ascontiguousarray(
         a.reshape(heads_total, a.shape[2], a.shape[3])[:heads][None].astype(np.float64))
     Q, K, V, dO = (sel(x[k]) for k in ("Q", "K", "V", "dO"))
-    t0 = time.perf_counter()
-    oracle.forward(Q, K, V, q0=cfg.q0, causal=cfg.causal)
-    oracle.backward(Q, K, V, dO, q0=cfg.q0, causal=cfg.causal)
-    dt = time.perf_counter() - t0
+    dt = 0.0
+    for r0, tok0, n in cfg.segments():   # one oracle call per run of consecutive tokens
+        Qs, dOs = (np.ascontiguousarray(a[:, :, r0:r0 + n]) for a in (Q, dO))
+        t0 = time.perf_counter()
+        oracle.forward(Qs, K, V, q0=tok0, causal=cfg.causal)
+        oracle.backward(Qs, K, V, dOs, q0=tok0, causal=cfg.causal)
+        dt += time.perf_counter() - t0
     flops = 12.0 * heads * cfg.A * cfg.visible_pairs()
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
             "sample": f"first {heads} of {heads_total} (batch, head) pairs of {cfg.name}, fwd+bwd, "
@@ -203,7 +207,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": cfg.name, "B": cfg.B, "Z": cfg.Z, "L": cfg.L, "A": cfg.A, "N": cfg.N,
-                   "chunk": cfg.c, "causal": cfg.causal, "ranks": list(cfg.ranks), "mode": "fused"},
+                   "chunk": cfg.c, "causal": cfg.causal, "ranks": list(cfg.ranks), "mode": "fused",
+                   "ownership": "zigzag" if cfg.zigzag else "contiguous"},
         "frac_of_bf16_peak": round(res["tflops"] / PEAK_BF16_TFLOPS, 4),
         "tokens_per_s": round(res["tokens_per_s"], 1),
         "kernel_ms": {n: round(v, 4) for n, v in k.items()},
@@ -214,7 +219,8 @@ def main():
     }
     if a.all:
         other = {}
-        for name in ("bert_base", "bert_large", "long_32k", "rank15_64k_causal"):
+        for name in ("bert_base", "bert_large", "long_32k", "rank15_64k_causal", "causal_ring_32k",
+                     "zigzag_rank0_64k_causal"):
             if name == cfg.name:
                 continue
             c2 = inputs.CONFIGS[name]

@@ -87,6 +87,13 @@ CONFIGS = {
     "rank15_64k_causal": RSAConfig("rank15_64k_causal", B=1, Z=12, L=65536, A=64,
                                    N=16, dtype="bf16", causal=True,
                                    rank_begin=15, rank_end=16),
+    # The causal extension over the whole ring, and one rank's share of the 64K ring when
+    # ownership is zig-zag (every rank then has the same share; rank 0 stands for all).
+    "causal_ring_32k": RSAConfig("causal_ring_32k", B=1, Z=16, L=32768, A=64, N=16,
+                                 dtype="bf16", causal=True, qkv_scale=0.5),
+    "zigzag_rank0_64k_causal": RSAConfig("zigzag_rank0_64k_causal", B=1, Z=12, L=65536, A=64,
+                                         N=16, dtype="bf16", causal=True,
+                                         rank_begin=0, rank_end=1, zigzag=True),
 }
 
 

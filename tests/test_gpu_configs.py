@@ -33,15 +33,25 @@ def sampled_check(cfg, x, out, head, row_blocks, cols):
     O = O.reshape(-1, cfg.Lq, 64)[head]
     dQ = dQ.reshape(-1, cfg.Lq, 64)[head]
     LSE = LSE.reshape(-1, cfg.Lq)[head]
-    # the RMS that normalises the error is that of the whole head, from the full backward below
-    dQ_ref, dK_ref, dV_ref = oracle.backward(Qh, Kh, Vh, dOh, q0=cfg.q0, causal=cfg.causal, cols=cols)
+    # the RMS that normalises the error is that of the whole head, from the full backward below;
+    # one oracle call per run of consecutive tokens (one run unless ownership is zig-zag)
+    dQ_ref = np.empty_like(Qh)
+    dK_ref = dV_ref = None
+    for s0, t0, n in cfg.segments():
+        g = oracle.backward(np.ascontiguousarray(Qh[:, :, s0:s0 + n]), Kh, Vh,
+                            np.ascontiguousarray(dOh[:, :, s0:s0 + n]), q0=t0, causal=cfg.causal, cols=cols)
+        dQ_ref[:, :, s0:s0 + n] = g[0]
+        dK_ref = g[1] if dK_ref is None else dK_ref + g[1]
+        dV_ref = g[2] if dV_ref is None else dV_ref + g[2]
     check("dQ", dQ[None, None], dQ_ref, cfg.dtype)
     dK = download(out["dK"]).reshape(-1, cfg.L, 64)[head][cols]
     dV = download(out["dV"]).reshape(-1, cfg.L, 64)[head][cols]
     check("dK", dK[None, None], dK_ref, cfg.dtype)
     check("dV", dV[None, None], dV_ref, cfg.dtype)
     for r0, nr in row_blocks:
-        O_ref, LSE_ref = oracle.forward(Qh[:, :, r0:r0 + nr], Kh, Vh, q0=cfg.q0 + r0, causal=cfg.causal)
+        s0, t0, n = next(s for s in cfg.segments() if s[0] <= r0 and r0 + nr <= s[0] + s[2])
+        O_ref, LSE_ref = oracle.forward(np.ascontiguousarray(Qh[:, :, r0:r0 + nr]), Kh, Vh,
+                                        q0=t0 + r0 - s0, causal=cfg.causal)
         check("O", O[None, None, r0:r0 + nr], O_ref, cfg.dtype)
         assert np.abs(LSE[r0:r0 + nr] - LSE_ref[0, 0]).max() <= LSE_ATOL
 
@@ -63,3 +73,24 @@ def test_rank15_of_64k_causal_sampled():
     cols = np.concatenate([[0, 4095, 4096, 61439, 61440, 61503, 65535],
                            rng.integers(0, cfg.L, 150), rng.integers(61440, cfg.L, 100)])
     sampled_check(cfg, x, out, head=11, row_blocks=[(0, 64), (2000, 100), (4096 - 64, 64)], cols=cols)
+
+
+def test_causal_ring_32k_sampled():
+    """All 16 ranks under the causal mask (contiguous ownership)."""
+    cfg = inputs.CONFIGS["causal_ring_32k"]
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x)
+    rng = np.random.Generator(np.random.PCG64(3))
+    cols = np.concatenate([[0, 63, 64, 2047, 2048, 32767], rng.integers(0, cfg.L, 250)])
+    sampled_check(cfg, x, out, head=9, row_blocks=[(0, 64), (2016, 64), (20000, 64), (32768 - 96, 96)], cols=cols)
+
+
+def test_zigzag_rank0_of_64k_causal_sampled():
+    """One rank's share of the 64K causal ring under zig-zag ownership: tokens 0..2047 and 63488..65535."""
+    cfg = inputs.CONFIGS["zigzag_rank0_64k_causal"]
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x)
+    rng = np.random.Generator(np.random.PCG64(4))
+    cols = np.concatenate([[0, 1, 2047, 2048, 63487, 63488, 65535],
+                           rng.integers(0, 2048, 100), rng.integers(0, cfg.L, 100), rng.integers(63488, cfg.L, 50)])
+    sampled_check(cfg, x, out, head=7, row_blocks=[(0, 64), (1990, 58), (2048, 64), (4096 - 64, 64)], cols=cols)
