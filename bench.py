@@ -40,7 +40,8 @@ def parse():
                     choices=["bert_base", "bert_large", "long_32k", "rank15_64k_causal",
                              "causal_ring_32k", "zigzag_rank0_64k_causal"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--all", action="store_true", help="also time the other workloads briefly")
+    ap.add_argument("--all", action="store_true", help="(default) also time the other workloads briefly")
+    ap.add_argument("--only", action="store_true", help="time the chosen workload only")
     ap.add_argument("--staged", action="store_true",
                     help="also time the staged (two-pass) kernels of one rank: HBM GB/s of the score strip")
     ap.add_argument("--profile-copy", type=int, default=0, metavar="BYTES",
@@ -217,7 +218,7 @@ def main():
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name)},
     }
-    if a.all:
+    if not a.only:
         other = {}
         for name in ("bert_base", "bert_large", "long_32k", "rank15_64k_causal", "causal_ring_32k",
                      "zigzag_rank0_64k_causal"):
