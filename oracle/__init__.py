@@ -9,3 +9,4 @@ from .rsa_oracle import (  # noqa: F401
     backward,
     threads,
 )
+from . import proj_oracle as proj  # noqa: F401  (the linear maps of Table 2 around RSA)
