@@ -166,6 +166,34 @@ int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *K, const void *V
 int rsa_bwd_dq(const rsa_desc *d, const void *dO, const void *Q, const void *K,
                const void *V, const void *ws, void *dQ, void *stream);
 
+/*
+ * The two linear maps around RSA on the simulated ranks' rows (Table 2, sequence
+ * parallelism rows "Q/K/V" and "Linear"), bf16 with fp32 accumulation, fused mode
+ * descriptors only.  H is the hidden size (a multiple of 64).  X, Y and their
+ * gradients are (B, Lq, H); Q, K, V, O and their gradients are (B, Z, Lq, A), the
+ * layout RSA reads and writes, so nothing is transposed in memory.  Wqkv is (H, 3 Z A)
+ * row-major with columns [Q | K | V], each block head-major; Wo is (Z A, H).  The
+ * paper prints no bias.  Weight gradients are fp32 and cover the rows of this call
+ * (the sum over ranks is the all-reduce of the replicated weights); they are
+ * overwritten.  ws: at least rsa_proj_workspace_bytes(d, H) bytes (partial sums of
+ * the weight gradients over row blocks, added in a fixed order).
+ */
+size_t rsa_proj_workspace_bytes(const rsa_desc *d, int32_t H);
+/* Q, K, V = heads of X Wqkv. */
+int rsa_qkv_proj(const rsa_desc *d, int32_t H, const void *X, const void *Wqkv,
+                 void *Q, void *K, void *V, void *stream);
+/* Y = merge_heads(O) Wo. */
+int rsa_out_proj(const rsa_desc *d, int32_t H, const void *O, const void *Wo,
+                 void *Y, void *stream);
+/* dO = heads of dY Wo^T; dWo = merge_heads(O)^T dY. */
+int rsa_out_proj_bwd(const rsa_desc *d, int32_t H, const void *dY, const void *O,
+                     const void *Wo, void *dO, float *dWo, void *ws,
+                     size_t ws_bytes, void *stream);
+/* dX = [dQ | dK | dV] Wqkv^T; dWqkv = X^T [dQ | dK | dV]. */
+int rsa_qkv_proj_bwd(const rsa_desc *d, int32_t H, const void *dQ, const void *dK,
+                     const void *dV, const void *X, const void *Wqkv, void *dX,
+                     float *dWqkv, void *ws, size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -331,4 +331,65 @@ int rsa_bwd_dq(const rsa_desc *d, const void *dO, const void *Q, const void *K, 
   return hip_status(rsa::fused_bwd_dq(dm, dO, Q, K, V, fused_nL(dm, w), fused_nD(w), dQ, st));
 }
 
+// ----------------------------------------------- projections around RSA ----
+namespace {
+int proj_check(const rsa_desc *d, int32_t H, Dims *dm) {
+  int rc = validate(d, dm);
+  if (rc != RSA_OK) return rc;
+  if (dm->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16) return RSA_ERR_UNSUPPORTED;
+  if (H < 64) return RSA_ERR_SHAPE;
+  if (H % 64 != 0) return RSA_ERR_UNSUPPORTED;
+  return RSA_OK;
+}
+size_t proj_ws(const Dims &dm, int64_t H) {
+  const int64_t M = (int64_t)dm.B * dm.Lq, ZA = (int64_t)dm.Z * dm.A;
+  const int s1 = rsa::proj_wgrad_splits(ZA, H, M), s2 = rsa::proj_wgrad_splits(H, 3 * ZA, M);
+  const size_t a = s1 > 1 ? (size_t)s1 * ZA * H * 4 : 0, b = s2 > 1 ? (size_t)s2 * H * 3 * ZA * 4 : 0;
+  return align256(a > b ? a : b);
+}
+}  // namespace
+
+size_t rsa_proj_workspace_bytes(const rsa_desc *d, int32_t H) {
+  Dims dm;
+  if (proj_check(d, H, &dm) != RSA_OK) return 0;
+  return proj_ws(dm, H);
+}
+
+#define RSA_PROJ_PROLOGUE(ptr_ok, ...)                            \
+  Dims dm;                                                        \
+  int rc = proj_check(d, H, &dm);                                 \
+  if (rc != RSA_OK) return rc;                                    \
+  if (!(ptr_ok)) return RSA_ERR_NULL;                             \
+  { const void *ps_[] = {__VA_ARGS__};                            \
+    for (const void *p_ : ps_) if (misaligned(p_)) return RSA_ERR_UNSUPPORTED; } \
+  hipStream_t st = static_cast<hipStream_t>(stream)
+
+int rsa_qkv_proj(const rsa_desc *d, int32_t H, const void *X, const void *Wqkv, void *Q, void *K,
+                 void *V, void *stream) {
+  RSA_PROJ_PROLOGUE(X && Wqkv && Q && K && V, X, Wqkv, Q, K, V);
+  return hip_status(rsa::proj_qkv(dm, H, X, Wqkv, Q, K, V, st));
+}
+
+int rsa_out_proj(const rsa_desc *d, int32_t H, const void *O, const void *Wo, void *Y, void *stream) {
+  RSA_PROJ_PROLOGUE(O && Wo && Y, O, Wo, Y);
+  return hip_status(rsa::proj_out(dm, H, O, Wo, Y, st));
+}
+
+int rsa_out_proj_bwd(const rsa_desc *d, int32_t H, const void *dY, const void *O, const void *Wo,
+                     void *dO, float *dWo, void *ws, size_t ws_bytes, void *stream) {
+  RSA_PROJ_PROLOGUE(dY && O && Wo && dO && dWo, dY, O, Wo, dO, dWo, ws);
+  const size_t need = proj_ws(dm, H);
+  if (need > 0 && (!ws || ws_bytes < need)) return RSA_ERR_WORKSPACE;
+  return hip_status(rsa::proj_out_bwd(dm, H, dY, O, Wo, dO, dWo, static_cast<float *>(ws), st));
+}
+
+int rsa_qkv_proj_bwd(const rsa_desc *d, int32_t H, const void *dQ, const void *dK, const void *dV,
+                     const void *X, const void *Wqkv, void *dX, float *dWqkv, void *ws,
+                     size_t ws_bytes, void *stream) {
+  RSA_PROJ_PROLOGUE(dQ && dK && dV && X && Wqkv && dX && dWqkv, dQ, dK, dV, X, Wqkv, dX, dWqkv, ws);
+  const size_t need = proj_ws(dm, H);
+  if (need > 0 && (!ws || ws_bytes < need)) return RSA_ERR_WORKSPACE;
+  return hip_status(rsa::proj_qkv_bwd(dm, H, dQ, dK, dV, X, Wqkv, dX, dWqkv, static_cast<float *>(ws), st));
+}
+
 }  // extern "C"

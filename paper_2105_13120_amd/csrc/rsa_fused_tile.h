@@ -50,6 +50,18 @@ struct TileLanes {
     return *reinterpret_cast<const bf16x8 *>(tile + row_base * 128 + rows_off[dk]);
   }
 
+  // The same operand with the k index of slice dk taken in the order read_cols delivers it
+  // (element e <-> column dk*16 + (e>>2)*8 + half*4 + (e&3)): two 8-byte reads.  For an MFMA
+  // whose other operand comes from read_cols.
+  __device__ __forceinline__ bf16x8 read_rows_perm(const unsigned char *tile, int row_base, int dk,
+                                                   int lane) const {
+    const int row = row_base + (lane & 31), half = lane >> 5;
+    const u32x2 lo = *reinterpret_cast<const u32x2 *>(tile + tile_off(row, dk * 2) + half * 8);
+    const u32x2 hi = *reinterpret_cast<const u32x2 *>(tile + tile_off(row, dk * 2 + 1) + half * 8);
+    const u32x4 w = {lo[0], lo[1], hi[0], hi[1]};
+    return __builtin_bit_cast(bf16x8, w);
+  }
+
   // Operand whose MFMA row index runs over the head dimension and whose k
   // index runs over 16 tile rows: lane (col, half) gets, for e = 0..7,
   //   tile[row_base + (e>>2)*8 + half*4 + (e&3)][db*32 + col],
@@ -67,14 +79,17 @@ struct TileLanes {
 // the 16-byte pieces (2 w + j) * 64 + lane, j = 0, 1; the piece at LDS position
 // p = 8 row + pc holds logical chunk pc ^ rot(row) of that row, so the tile lands in the
 // swizzled layout above.  `g` points at element [0][0] of the tile in global memory
-// (rows 64 elements apart).  Completion: wait_vmem(), then a barrier.
+// (rows 64 elements apart, or `ld` elements apart in the second form of load).
+// Completion: wait_vmem(), then a barrier.
 struct TileDMA {
-  int g_off[2], l_off[2];
+  int g_off[2], l_off[2], g_row[2], g_col[2];
   __device__ __forceinline__ TileDMA(int wave, int lane) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int p = (wave * 2 + j) * 64 + lane;
       const int row = p >> 3, cc = (p & 7) ^ swz_rot(row);
+      g_row[j] = row;
+      g_col[j] = cc * 8;
       g_off[j] = row * 64 + cc * 8;
       l_off[j] = (wave * 2 + j) * 1024;
     }
@@ -82,6 +97,10 @@ struct TileDMA {
   __device__ __forceinline__ void load(const uint16_t *g, unsigned char *tile) const {
 #pragma unroll
     for (int j = 0; j < 2; ++j) lds_dma16(g + g_off[j], tile + l_off[j]);
+  }
+  __device__ __forceinline__ void load(const uint16_t *g, unsigned char *tile, int64_t ld) const {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) lds_dma16(g + g_row[j] * ld + g_col[j], tile + l_off[j]);
   }
 };
 

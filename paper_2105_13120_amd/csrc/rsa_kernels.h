@@ -45,4 +45,17 @@ hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const vo
                           const void *V, const void *O, const float *LSE, void *dQ, void *dK,
                           void *dV, float *nD, float *nL, void *Qs, hipStream_t st);
 
+// --- the linear maps around RSA (Table 2, rows Q/K/V and Linear), bf16, A = 64 ---
+// X, dX, Y, dY: (B, Lq, H); W: (H, 3*Z*64), columns [Q | K | V] head-major; Wo: (Z*64, H);
+// Q, K, V, O and their gradients: (B, Z, Lq, 64); dW, dWo: fp32; part: k-split partial sums.
+int proj_wgrad_splits(int64_t Mout, int64_t Nout, int64_t K);
+hipError_t proj_qkv(const Dims &d, int64_t H, const void *X, const void *W, void *Q, void *K, void *V,
+                    hipStream_t st);
+hipError_t proj_out(const Dims &d, int64_t H, const void *O, const void *Wo, void *Y, hipStream_t st);
+hipError_t proj_out_bwd(const Dims &d, int64_t H, const void *dY, const void *O, const void *Wo,
+                        void *dO, float *dWo, float *part, hipStream_t st);
+hipError_t proj_qkv_bwd(const Dims &d, int64_t H, const void *dQ, const void *dK, const void *dV,
+                        const void *X, const void *W, void *dX, float *dW, float *part,
+                        hipStream_t st);
+
 }  // namespace rsa

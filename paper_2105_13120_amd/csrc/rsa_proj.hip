@@ -1,0 +1,274 @@
+// The two linear maps around Ring Self-Attention on a rank's rows (paper Table 2, sequence
+// parallelism rows "Q/K/V" and "Linear") and their derivatives, bf16 with fp32 accumulation:
+//   Q/K/V:  (B, rows, H) x (H, AZ) -> (B, Z, rows, A), written head-split as RSA reads it
+//   Linear: (B, Z, rows, A) x (AZ, H) -> (B, rows, H), read head-split as RSA writes it
+// One MFMA GEMM kernel serves all six products.  An operand is a "view": a matrix cut into
+// 64 x 64 tiles that are either blocks of a plain row-major matrix or the (64 rows, one head)
+// blocks of up to three (B, Z, rows, 64) tensors, so no tensor is ever re-laid out in memory.
+//
+// Work-group: 128 x 128 outputs, 4 waves of 64 x 64 (2 x 2 MFMA blocks of 32 x 32), k in slabs
+// of 64 through the swizzled LDS tiles of the attention kernels (direct global->LDS loads,
+// two named stage buffers, one barrier per slab).  The product is formed transposed
+// (accumulator rows = n, columns = m): a lane then owns one output row m and four consecutive
+// n per register group, which is an 8- or 16-byte store.
+#include "rsa_fused_tile.h"
+#include "rsa_kernels.h"
+
+namespace rsa {
+
+// A bf16 matrix [R][C] served as 64 x 64 tiles.
+struct MatView {
+  const uint16_t *p[3];  // plain: p[0]; head-split: tensor cb / Z holds column tile cb
+  int64_t ld;            // plain: row stride in elements
+  int64_t rows;          // head-split: rows per (b, z) block (a multiple of 64)
+  int Z;                 // head-split: heads = column tiles per tensor
+  int split;             // 0: plain row-major; 1: (B, Z, rows, 64) tensors, row index = b * rows + r
+  __device__ __forceinline__ const uint16_t *tile(int64_t rb, int64_t cb, int64_t &ldt) const {
+    if (!split) {
+      ldt = ld;
+      return p[0] + rb * 64 * ld + cb * 64;
+    }
+    const int which = (int)(cb / Z), z = (int)(cb % Z);
+    const int64_t m0 = rb * 64, b = m0 / rows, r0 = m0 % rows;
+    ldt = 64;
+    return p[which] + ((b * Z + z) * rows + r0) * 64;
+  }
+};
+
+struct GemmArgs {
+  MatView A, B;       // m-side and n-side operands
+  int64_t M, N, K;    // multiples of 64
+  int64_t kslabs;     // slabs of 64 k per split (split s takes slabs [s * kslabs, ...))
+  void *out[3];       // plain: out[0] (+ split * M * out_ld elements for a k split); head-split: 3 tensors
+  int64_t out_ld, out_rows;
+  int out_Z, out_split;
+  int ntiles;         // 128-wide column tiles
+};
+
+// A_KROWS / B_KROWS: the operand's tiles hold k along their rows (the view is [K][M] or [K][N])
+// instead of along their columns ([M][K], [N][K]).
+template <bool A_KROWS, bool B_KROWS, bool OUT_F32>
+__global__ void __launch_bounds__(256, 2) proj_gemm_kernel(GemmArgs g) {
+  struct Stage { unsigned char a[2][kTileBytes], b[2][kTileBytes]; };
+  __shared__ __attribute__((aligned(16))) Stage stage0, stage1;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int col = lane & 31, half = lane >> 5;
+  const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x);
+  const int64_t m0 = (int64_t)(wg / g.ntiles) * 128, n0 = (int64_t)(wg % g.ntiles) * 128;
+  const int64_t mt_last = g.M / 64 - 1, nt_last = g.N / 64 - 1;
+  const int64_t ks_begin = (int64_t)blockIdx.y * g.kslabs;
+  int64_t ks_end = ks_begin + g.kslabs;
+  if (ks_end > g.K / 64) ks_end = g.K / 64;
+
+  const TileLanes tl(lane);
+  const TileDMA dma(wave, lane);
+  auto load_stage = [&](int64_t ks, Stage &s) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      int64_t mt = m0 / 64 + t, nt = n0 / 64 + t, ld;
+      if (mt > mt_last) mt = mt_last;  // ragged edge: refetch the last tile (never stored)
+      if (nt > nt_last) nt = nt_last;
+      const uint16_t *pa = A_KROWS ? g.A.tile(ks, mt, ld) : g.A.tile(mt, ks, ld);
+      dma.load(pa, s.a[t], ld);
+      const uint16_t *pb = B_KROWS ? g.B.tile(ks, nt, ld) : g.B.tile(nt, ks, ld);
+      dma.load(pb, s.b[t], ld);
+    }
+  };
+
+  f32x16 acc[2][2];  // [nb][mb]: rows n, columns m
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.f;
+
+  int64_t ks = ks_begin;
+  if (ks < ks_end) load_stage(ks, stage0);
+  wait_vmem();
+  __syncthreads();
+  auto stage = [&](Stage &sc, Stage &sn) __attribute__((always_inline)) {
+    if (ks + 1 < ks_end) load_stage(ks + 1, sn);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 af[2], bf[2];
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+        af[mb] = A_KROWS ? tl.read_cols(sc.a[wm], kk * 16, mb)
+                         : (B_KROWS ? tl.read_rows_perm(sc.a[wm], mb * 32, kk, lane)
+                                    : tl.read_rows(sc.a[wm], mb * 32, kk));
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+        bf[nb] = B_KROWS ? tl.read_cols(sc.b[wn], kk * 16, nb)
+                         : (A_KROWS ? tl.read_rows_perm(sc.b[wn], nb * 32, kk, lane)
+                                    : tl.read_rows(sc.b[wn], nb * 32, kk));
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) acc[nb][mb] = mfma_32x32x16(bf[nb], af[mb], acc[nb][mb]);
+    }
+    wait_vmem();
+    __syncthreads();
+    ++ks;
+  };
+  while (ks < ks_end) {
+    stage(stage0, stage1);
+    if (ks >= ks_end) break;
+    stage(stage1, stage0);
+  }
+
+  // lane (col, half) holds, for output row m, the columns n = nb*32 + grp*8 + half*4 .. +4
+#pragma unroll
+  for (int mb = 0; mb < 2; ++mb) {
+    const int64_t m = m0 + wm * 64 + mb * 32 + col;
+    if (m >= g.M) continue;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int grp = 0; grp < 4; ++grp) {
+        const int64_t n = n0 + wn * 64 + nb * 32 + grp * 8 + half * 4;
+        if (n >= g.N) continue;
+        int64_t off;
+        int which = 0;
+        if (!g.out_split) {
+          off = ((int64_t)blockIdx.y * g.M + m) * g.out_ld + n;
+        } else {
+          const int64_t hb = n / 64;
+          which = (int)(hb / g.out_Z);
+          const int64_t z = hb % g.out_Z, b = m / g.out_rows, r = m % g.out_rows;
+          off = ((b * g.out_Z + z) * g.out_rows + r) * 64 + (n & 63);
+        }
+        const f32x16 &c = acc[nb][mb];
+        if (OUT_F32) {
+          const f32x4 w = {c[grp * 4 + 0], c[grp * 4 + 1], c[grp * 4 + 2], c[grp * 4 + 3]};
+          *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out[which]) + off) = w;
+        } else {
+          const u32x2 w = {pack_bf16(c[grp * 4 + 0], c[grp * 4 + 1]), pack_bf16(c[grp * 4 + 2], c[grp * 4 + 3])};
+          *reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(g.out[which]) + off) = w;
+        }
+      }
+  }
+}
+
+// out[i] = sum over s of part[s][i], s in fixed order: the deterministic end of a k split
+__global__ void __launch_bounds__(256) ksplit_reduce_kernel(const float *part, float *out, int64_t n4,
+                                                            int splits) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n4) return;
+  f32x4 s = reinterpret_cast<const f32x4 *>(part)[i];
+  for (int k = 1; k < splits; ++k) s += reinterpret_cast<const f32x4 *>(part)[(int64_t)k * n4 + i];
+  reinterpret_cast<f32x4 *>(out)[i] = s;
+}
+
+static MatView plain(const void *p, int64_t ld) {
+  MatView v{};
+  v.p[0] = static_cast<const uint16_t *>(p); v.ld = ld; v.split = 0; v.rows = 64; v.Z = 1;
+  return v;
+}
+static MatView heads(const void *p0, const void *p1, const void *p2, int64_t rows, int Z) {
+  MatView v{};
+  v.p[0] = static_cast<const uint16_t *>(p0); v.p[1] = static_cast<const uint16_t *>(p1);
+  v.p[2] = static_cast<const uint16_t *>(p2); v.ld = 64; v.rows = rows; v.Z = Z; v.split = 1;
+  return v;
+}
+
+template <bool A_KROWS, bool B_KROWS, bool OUT_F32>
+static hipError_t launch_gemm(GemmArgs &g, int splits, hipStream_t st) {
+  g.ntiles = (int)((g.N + 127) / 128);
+  const int64_t mtiles = (g.M + 127) / 128;
+  g.kslabs = (g.K / 64 + splits - 1) / splits;
+  dim3 grid((unsigned)(mtiles * g.ntiles), (unsigned)splits);
+  hipLaunchKernelGGL((proj_gemm_kernel<A_KROWS, B_KROWS, OUT_F32>), grid, dim3(256), 0, st, g);
+  return hipGetLastError();
+}
+
+// k splits of a weight-gradient product: enough work-groups to fill the chip twice
+int proj_wgrad_splits(int64_t Mout, int64_t Nout, int64_t K) {
+  const int64_t tiles = ((Mout + 127) / 128) * ((Nout + 127) / 128);
+  int64_t s = (1024 + tiles - 1) / tiles;
+  const int64_t slabs = K / 64;
+  if (s > slabs / 4) s = slabs / 4;
+  if (s < 1) s = 1;
+  if (s > 64) s = 64;
+  return (int)s;
+}
+
+hipError_t proj_qkv(const Dims &d, int64_t H, const void *X, const void *W, void *Q, void *K, void *V,
+                    hipStream_t st) {
+  GemmArgs g{};
+  g.M = (int64_t)d.B * d.Lq; g.N = 3LL * d.Z * 64; g.K = H;
+  g.A = plain(X, H);          // [M][K]
+  g.B = plain(W, g.N);        // [K][N]
+  g.out[0] = Q; g.out[1] = K; g.out[2] = V;
+  g.out_split = 1; g.out_rows = d.Lq; g.out_Z = d.Z;
+  return launch_gemm<false, true, false>(g, 1, st);
+}
+
+hipError_t proj_out(const Dims &d, int64_t H, const void *O, const void *Wo, void *Y, hipStream_t st) {
+  GemmArgs g{};
+  g.M = (int64_t)d.B * d.Lq; g.N = H; g.K = (int64_t)d.Z * 64;
+  g.A = heads(O, nullptr, nullptr, d.Lq, d.Z);  // [M][K], column tile = head
+  g.B = plain(Wo, H);                           // [K][N]
+  g.out[0] = Y; g.out_split = 0; g.out_ld = H;
+  return launch_gemm<false, true, false>(g, 1, st);
+}
+
+hipError_t proj_out_bwd(const Dims &d, int64_t H, const void *dY, const void *O, const void *Wo,
+                        void *dO, float *dWo, float *part, hipStream_t st) {
+  const int64_t M = (int64_t)d.B * d.Lq, ZA = (int64_t)d.Z * 64;
+  {  // dO = dY Wo^T, head-split
+    GemmArgs g{};
+    g.M = M; g.N = ZA; g.K = H;
+    g.A = plain(dY, H);   // [M][K]
+    g.B = plain(Wo, H);   // [N][K]
+    g.out[0] = dO; g.out_split = 1; g.out_rows = d.Lq; g.out_Z = d.Z;
+    hipError_t e = launch_gemm<false, false, false>(g, 1, st);
+    if (e != hipSuccess) return e;
+  }
+  // dWo = O^T dY: contraction over the rows
+  GemmArgs g{};
+  g.M = ZA; g.N = H; g.K = M;
+  g.A = heads(O, nullptr, nullptr, d.Lq, d.Z);  // [K][M]
+  g.B = plain(dY, H);                           // [K][N]
+  const int splits = proj_wgrad_splits(ZA, H, M);
+  g.out[0] = splits > 1 ? part : dWo; g.out_split = 0; g.out_ld = H;
+  hipError_t e = launch_gemm<true, true, true>(g, splits, st);
+  if (e != hipSuccess || splits == 1) return e;
+  const int64_t n4 = ZA * H / 4;
+  hipLaunchKernelGGL(ksplit_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, part, dWo,
+                     n4, splits);
+  return hipGetLastError();
+}
+
+hipError_t proj_qkv_bwd(const Dims &d, int64_t H, const void *dQ, const void *dK, const void *dV,
+                        const void *X, const void *W, void *dX, float *dW, float *part,
+                        hipStream_t st) {
+  const int64_t M = (int64_t)d.B * d.Lq, N3 = 3LL * d.Z * 64;
+  {  // dX = [dQ | dK | dV] W^T
+    GemmArgs g{};
+    g.M = M; g.N = H; g.K = N3;
+    g.A = heads(dQ, dK, dV, d.Lq, d.Z);  // [M][K]
+    g.B = plain(W, N3);                  // [N][K]
+    g.out[0] = dX; g.out_split = 0; g.out_ld = H;
+    hipError_t e = launch_gemm<false, false, false>(g, 1, st);
+    if (e != hipSuccess) return e;
+  }
+  // dW = X^T [dQ | dK | dV]
+  GemmArgs g{};
+  g.M = H; g.N = N3; g.K = M;
+  g.A = plain(X, H);                   // [K][M]
+  g.B = heads(dQ, dK, dV, d.Lq, d.Z);  // [K][N]
+  const int splits = proj_wgrad_splits(H, N3, M);
+  g.out[0] = splits > 1 ? part : dW; g.out_split = 0; g.out_ld = N3;
+  hipError_t e = launch_gemm<true, true, true>(g, splits, st);
+  if (e != hipSuccess || splits == 1) return e;
+  const int64_t n4 = H * N3 / 4;
+  hipLaunchKernelGGL(ksplit_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, part, dW,
+                     n4, splits);
+  return hipGetLastError();
+}
+
+}  // namespace rsa

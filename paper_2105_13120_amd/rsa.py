@@ -21,6 +21,7 @@ EXPORTS = (
     "rsa_qk_step", "rsa_row_softmax", "rsa_av_step", "rsa_bwd_rowdot", "rsa_dv_step",
     "rsa_dp_step", "rsa_softmax_bwd", "rsa_dq_step", "rsa_dk_step", "rsa_store",
     "rsa_bwd_preprocess", "rsa_bwd_dkdv", "rsa_bwd_dq",
+    "rsa_proj_workspace_bytes", "rsa_qkv_proj", "rsa_out_proj", "rsa_out_proj_bwd", "rsa_qkv_proj_bwd",
 )
 
 
@@ -74,8 +75,14 @@ def lib():
         L.rsa_bwd_preprocess.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
         L.rsa_bwd_dkdv.argtypes = [dp] + [vp] * 7
         L.rsa_bwd_dq.argtypes = [dp] + [vp] * 7
+        L.rsa_proj_workspace_bytes.argtypes = [dp, i]
+        L.rsa_qkv_proj.argtypes = [dp, i] + [vp] * 6
+        L.rsa_out_proj.argtypes = [dp, i] + [vp] * 4
+        L.rsa_out_proj_bwd.argtypes = [dp, i] + [vp] * 6 + [sz, vp]
+        L.rsa_qkv_proj_bwd.argtypes = [dp, i] + [vp] * 8 + [sz, vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = i
+        L.rsa_proj_workspace_bytes.restype = sz
         _lib = L
     return _lib
 
@@ -212,3 +219,55 @@ def bwd_dkdv(desc, dO, K, V, ws, dK, dV):
 def bwd_dq(desc, dO, Q, K, V, ws, dQ):
     _check(lib().rsa_bwd_dq(ctypes.byref(desc), _p(dO), _p(Q), _p(K), _p(V), _p(ws), _p(dQ),
                             _stream()))
+
+
+# ---- the linear maps around RSA (Table 2, rows Q/K/V and Linear) ----
+def proj_workspace_bytes(desc, H):
+    return int(lib().rsa_proj_workspace_bytes(ctypes.byref(desc), int(H)))
+
+
+def _proj_ws(desc, H, device):
+    return torch.empty(max(proj_workspace_bytes(desc, H), 16), dtype=torch.uint8, device=device)
+
+
+def _head_shape(desc, X):
+    rows = (desc.rank_end - desc.rank_begin) * (desc.L // desc.N)
+    return (desc.B, desc.Z, rows, desc.A)
+
+
+def qkv_proj(desc, X, Wqkv, Q=None, K=None, V=None):
+    """X (B, Lq, H), Wqkv (H, 3*Z*A) -> Q, K, V (B, Z, Lq, A)."""
+    H = X.shape[-1]
+    Q, K, V = (torch.empty(_head_shape(desc, X), dtype=X.dtype, device=X.device) if t is None else t
+               for t in (Q, K, V))
+    _check(lib().rsa_qkv_proj(ctypes.byref(desc), H, _p(X), _p(Wqkv), _p(Q), _p(K), _p(V), _stream()))
+    return Q, K, V
+
+
+def out_proj(desc, O, Wo, Y=None):
+    """O (B, Z, Lq, A), Wo (Z*A, H) -> Y (B, Lq, H)."""
+    H = Wo.shape[-1]
+    if Y is None:
+        Y = torch.empty((O.shape[0], O.shape[2], H), dtype=O.dtype, device=O.device)
+    _check(lib().rsa_out_proj(ctypes.byref(desc), H, _p(O), _p(Wo), _p(Y), _stream()))
+    return Y
+
+
+def out_proj_bwd(desc, dY, O, Wo, dO=None, dWo=None, ws=None):
+    H = Wo.shape[-1]
+    dO = torch.empty_like(O) if dO is None else dO
+    dWo = torch.empty(Wo.shape, dtype=torch.float32, device=Wo.device) if dWo is None else dWo
+    ws = _proj_ws(desc, H, O.device) if ws is None else ws
+    _check(lib().rsa_out_proj_bwd(ctypes.byref(desc), H, _p(dY), _p(O), _p(Wo), _p(dO), _p(dWo), _p(ws),
+                                  ws.numel(), _stream()))
+    return dO, dWo
+
+
+def qkv_proj_bwd(desc, dQ, dK, dV, X, Wqkv, dX=None, dW=None, ws=None):
+    H = X.shape[-1]
+    dX = torch.empty_like(X) if dX is None else dX
+    dW = torch.empty(Wqkv.shape, dtype=torch.float32, device=X.device) if dW is None else dW
+    ws = _proj_ws(desc, H, X.device) if ws is None else ws
+    _check(lib().rsa_qkv_proj_bwd(ctypes.byref(desc), H, _p(dQ), _p(dK), _p(dV), _p(X), _p(Wqkv), _p(dX),
+                                  _p(dW), _p(ws), ws.numel(), _stream()))
+    return dX, dW

@@ -1,0 +1,105 @@
+"""GPU parity of the linear maps around RSA (Table 2, rows Q/K/V and Linear) with the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import check, download, upload
+from paper_2105_13120_amd import inputs, rsa
+
+pytestmark = pytest.mark.gpu
+
+
+def draw(shape, seed, scale=1.0):
+    x = np.random.Generator(np.random.PCG64(seed)).standard_normal(shape) * scale
+    return inputs.round_to_bf16(x)
+
+
+def check_f32(name, got, ref):
+    """fp32 weight gradients: the bf16 products are exact in fp32, so the only error is the fp32
+    accumulation over up to K/16 MFMA steps (K <= 16384 rows here): at most about 1000 roundings
+    of 2^-24 relative to a partial sum of the size of the result, 6e-5 of its RMS if they all
+    pointed the same way.  Bound: 2e-4 of the RMS, on the maximum error."""
+    assert got.shape == ref.shape
+    rms = float(np.sqrt(np.mean(np.square(ref))))
+    err = float(np.abs(got - ref).max())
+    assert err <= 2e-4 * rms, f"{name}: max abs err {err:.3e} vs rms {rms:.3e}"
+
+
+# (B, Z, L, N, rank range, H): several 128-tiles, ragged 64-edges in M, N and K, one rank's share
+CASES = [
+    (1, 1, 64, 1, (0, 1), 64),
+    (2, 2, 128, 2, (0, 2), 192),
+    (1, 3, 320, 5, (0, 5), 320),
+    (2, 4, 512, 4, (1, 3), 256),
+    (1, 16, 2048, 8, (0, 8), 1024),
+]
+
+
+@pytest.mark.parametrize("B,Z,L,N,ranks,H", CASES)
+def test_projections_forward_and_backward(B, Z, L, N, ranks, H):
+    A = 64
+    rows = (ranks[1] - ranks[0]) * (L // N)
+    X = draw((B, rows, H), 1)
+    W = draw((H, 3 * Z * A), 2, H ** -0.5)
+    Wo = draw((Z * A, H), 3, (Z * A) ** -0.5)
+    O = draw((B, Z, rows, A), 4)
+    dY = draw((B, rows, H), 5)
+    dQ, dK, dV = (draw((B, Z, rows, A), s) for s in (6, 7, 8))
+    t = {k: upload(v, "bf16") for k, v in dict(X=X, W=W, Wo=Wo, O=O, dY=dY, dQ=dQ, dK=dK, dV=dV).items()}
+    Kfull = torch.empty((B, Z, L, A), dtype=torch.bfloat16, device="cuda")
+    desc = rsa.make_desc(Kfull, N, rank_begin=ranks[0], rank_end=ranks[1])
+
+    Q, K, V = rsa.qkv_proj(desc, t["X"], t["W"])
+    Y = rsa.out_proj(desc, t["O"], t["Wo"])
+    gO, gWo = rsa.out_proj_bwd(desc, t["dY"], t["O"], t["Wo"])
+    gX, gW = rsa.qkv_proj_bwd(desc, t["dQ"], t["dK"], t["dV"], t["X"], t["W"])
+    torch.cuda.synchronize()
+
+    P = oracle.proj
+    for name, got, ref in zip("QKV", (Q, K, V), P.qkv_proj(X, W, Z, A)):
+        check(name, download(got), ref, "bf16")
+    check("Y", download(Y), P.out_proj(O, Wo), "bf16")
+    rO, rWo = P.out_proj_bwd(dY, O, Wo)
+    check("dO", download(gO), rO, "bf16")
+    check_f32("dWo", download(gWo), rWo)
+    rX, rW = P.qkv_proj_bwd(dQ, dK, dV, X, W)
+    check("dX", download(gX), rX, "bf16")
+    check_f32("dWqkv", download(gW), rW)
+
+
+def test_projection_outputs_feed_rsa_without_relayout():
+    """X -> Q/K/V projection -> RSA -> Linear, against the oracle chain on the rounded intermediates."""
+    B, Z, L, N, H, A = 1, 4, 512, 4, 256, 64
+    X = draw((B, L, H), 11)
+    W = draw((H, 3 * Z * A), 12, H ** -0.5)
+    Wo = draw((Z * A, H), 13, (Z * A) ** -0.5)
+    tX, tW, tWo = (upload(v, "bf16") for v in (X, W, Wo))
+    Kfull = torch.empty((B, Z, L, A), dtype=torch.bfloat16, device="cuda")
+    desc = rsa.make_desc(Kfull, N)
+    Q, K, V = rsa.qkv_proj(desc, tX, tW)
+    O, LSE = rsa.forward(desc, Q, K, V)
+    Y = rsa.out_proj(desc, O, tWo)
+    torch.cuda.synchronize()
+    # the oracle continues from the GPU's rounded Q, K, V (each stage is checked on its own inputs)
+    O_ref, _ = oracle.forward(download(Q), download(K), download(V))
+    check("O", download(O), O_ref, "bf16")
+    check("Y", download(Y), oracle.proj.out_proj(download(O), Wo), "bf16")
+
+
+def test_projection_error_codes():
+    Kfull = torch.empty((1, 2, 128, 64), dtype=torch.bfloat16, device="cuda")
+    desc = rsa.make_desc(Kfull, 2)
+    X = torch.zeros((1, 128, 100), dtype=torch.bfloat16, device="cuda")   # H = 100: not a multiple of 64
+    W = torch.zeros((100, 384), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(rsa.RSAError) as e:
+        rsa.qkv_proj(desc, X, W)
+    assert e.value.status == -3
+    X = torch.zeros((1, 128, 128), dtype=torch.bfloat16, device="cuda")
+    W = torch.zeros((128, 384), dtype=torch.bfloat16, device="cuda")
+    g = torch.zeros((1, 2, 128, 64), dtype=torch.bfloat16, device="cuda")
+    need = rsa.proj_workspace_bytes(desc, 128)
+    if need > 0:
+        with pytest.raises(rsa.RSAError) as e:
+            rsa.qkv_proj_bwd(desc, g, g, g, X, W, ws=torch.empty(16, dtype=torch.uint8, device="cuda"))
+        assert e.value.status == -4
