@@ -118,6 +118,45 @@ def time_workload(cfg, steps, warmup, torch, rsa, inputs, per_kernel=True):
     return res, x
 
 
+def projections_report(cfg, torch, rsa):
+    """The linear maps around RSA (Table 2, rows Q/K/V and Linear) on cfg's rows, H = Z*A:
+    forward (2 products) and backward (4 products) timed with HIP events."""
+    H = cfg.Z * cfg.A
+    rows = cfg.Lq
+    g = torch.Generator(device="cuda").manual_seed(0)
+    rnd = lambda *shape, s=1.0: (torch.randn(shape, generator=g, device="cuda") * s).to(torch.bfloat16)
+    X, dY = rnd(cfg.B, rows, H), rnd(cfg.B, rows, H)
+    W, Wo = rnd(H, 3 * H, s=H ** -0.5), rnd(H, H, s=H ** -0.5)
+    heads = lambda: rnd(cfg.B, cfg.Z, rows, cfg.A)
+    O, dQ, dK, dV = heads(), heads(), heads(), heads()
+    Kfull = torch.empty((cfg.B, cfg.Z, cfg.L, cfg.A), dtype=torch.bfloat16, device="cuda")
+    rb, re = cfg.ranks
+    desc = rsa.make_desc(Kfull, cfg.N, rank_begin=rb, rank_end=re)
+    Q, K, V = rsa.qkv_proj(desc, X, W)
+    Y = rsa.out_proj(desc, O, Wo)
+    ws = torch.empty(max(rsa.proj_workspace_bytes(desc, H), 16), dtype=torch.uint8, device="cuda")
+    dO, dWo = rsa.out_proj_bwd(desc, dY, O, Wo, ws=ws)
+    dX, dW = rsa.qkv_proj_bwd(desc, dQ, dK, dV, X, W, ws=ws)
+
+    def fwd():
+        rsa.qkv_proj(desc, X, W, Q, K, V)
+        rsa.out_proj(desc, O, Wo, Y)
+
+    def bwd():
+        rsa.out_proj_bwd(desc, dY, O, Wo, dO, dWo, ws)
+        rsa.qkv_proj_bwd(desc, dQ, dK, dV, X, W, dX, dW, ws)
+
+    for _ in range(100):
+        fwd(); bwd()
+    tf, tb = event_ms(fwd, 200, torch), event_ms(bwd, 200, torch)
+    M = cfg.B * rows
+    f_fwd = 2.0 * M * H * 4 * H            # X W (3H columns) + O Wo
+    return {"H": H, "rows": M, "fwd_ms": round(tf, 4), "bwd_ms": round(tb, 4),
+            "fwd_tflops": round(f_fwd / (tf * 1e-3) / 1e12, 1),
+            "bwd_tflops": round(2 * f_fwd / (tb * 1e-3) / 1e12, 1),
+            "frac_of_bf16_peak": round(3 * f_fwd / ((tf + tb) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+
+
 def staged_report(cfg, torch, rsa, inputs):
     """The paper's two-pass layout for one simulated rank (rank 0): time every ring step
     kernel with HIP events and price the memory-bound ones against HBM."""
@@ -231,6 +270,7 @@ def main():
             other[name] = {"tflops": round(r2["tflops"], 2), "ms_per_step": round(r2["ms_per_step"], 4),
                            "kernel_ms": {n: round(v, 4) for n, v in r2["kernel_ms"].items()}}
         out["other_workloads"] = other
+        out["projections"] = projections_report(cfg, torch, rsa)
     if a.staged:
         out["staged"] = staged_report(cfg, torch, rsa, inputs)
     if a.profile_copy > 0:

@@ -93,6 +93,10 @@ __device__ __forceinline__ void xhalf_pair(float x, float &lo, float &hi) {
   lo = __builtin_bit_cast(float, a);
   hi = __builtin_bit_cast(float, b);
 }
+// v_permlane32_swap a, b in general: lanes 32..63 of a change places with lanes 0..31 of b.
+__device__ __forceinline__ void permlane32_swap(uint32_t &a, uint32_t &b) {
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
 __device__ __forceinline__ float xhalf_max(float x) {
   float lo, hi;
   xhalf_pair(x, lo, hi);

@@ -51,15 +51,17 @@ struct TileLanes {
   }
 
   // The same operand with the k index of slice dk taken in the order read_cols delivers it
-  // (element e <-> column dk*16 + (e>>2)*8 + half*4 + (e&3)): two 8-byte reads.  For an MFMA
-  // whose other operand comes from read_cols.
-  __device__ __forceinline__ bf16x8 read_rows_perm(const unsigned char *tile, int row_base, int dk,
-                                                   int lane) const {
-    const int row = row_base + (lane & 31), half = lane >> 5;
-    const u32x2 lo = *reinterpret_cast<const u32x2 *>(tile + tile_off(row, dk * 2) + half * 8);
-    const u32x2 hi = *reinterpret_cast<const u32x2 *>(tile + tile_off(row, dk * 2 + 1) + half * 8);
-    const u32x4 w = {lo[0], lo[1], hi[0], hi[1]};
-    return __builtin_bit_cast(bf16x8, w);
+  // (element e <-> column dk*16 + (e>>2)*8 + half*4 + (e&3)), for an MFMA whose other operand
+  // comes from read_cols.  The row read gives lane (col, 0) columns 0..7 and lane (col, 1)
+  // columns 8..15 of the slice; the wanted order is (0..3, 8..11) and (4..7, 12..15), i.e. the
+  // upper 8 bytes of the first lane change places with the lower 8 bytes of the second.
+  __device__ __forceinline__ bf16x8 read_rows_perm(const unsigned char *tile, int row_base, int dk) const {
+    u32x4 w = __builtin_bit_cast(u32x4, read_rows(tile, row_base, dk));
+    uint32_t lo0 = w[0], lo1 = w[1], hi0 = w[2], hi1 = w[3];
+    permlane32_swap(lo0, hi0);
+    permlane32_swap(lo1, hi1);
+    const u32x4 r = {lo0, lo1, hi0, hi1};
+    return __builtin_bit_cast(bf16x8, r);
   }
 
   // Operand whose MFMA row index runs over the head dimension and whose k
@@ -75,33 +77,36 @@ struct TileLanes {
   }
 };
 
-// Direct global->LDS copy of one 64 x 64 bf16 tile by a 4-wave work-group: wave w moves
-// the 16-byte pieces (2 w + j) * 64 + lane, j = 0, 1; the piece at LDS position
+// Direct global->LDS copy of one 64 x 64 bf16 tile by a work-group of WAVES (4 or 8) waves:
+// wave w moves the 16-byte pieces (PER w + j) * 64 + lane, j < PER = 8 / WAVES; the piece at LDS position
 // p = 8 row + pc holds logical chunk pc ^ rot(row) of that row, so the tile lands in the
 // swizzled layout above.  `g` points at element [0][0] of the tile in global memory
 // (rows 64 elements apart, or `ld` elements apart in the second form of load).
 // Completion: wait_vmem(), then a barrier.
-struct TileDMA {
-  int g_off[2], l_off[2], g_row[2], g_col[2];
-  __device__ __forceinline__ TileDMA(int wave, int lane) {
+template <int WAVES>
+struct TileDMAT {
+  static constexpr int PER = 8 / WAVES;
+  int g_off[PER], l_off[PER], g_row[PER], g_col[PER];
+  __device__ __forceinline__ TileDMAT(int wave, int lane) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int p = (wave * 2 + j) * 64 + lane;
+    for (int j = 0; j < PER; ++j) {
+      const int p = (wave * PER + j) * 64 + lane;
       const int row = p >> 3, cc = (p & 7) ^ swz_rot(row);
       g_row[j] = row;
       g_col[j] = cc * 8;
       g_off[j] = row * 64 + cc * 8;
-      l_off[j] = (wave * 2 + j) * 1024;
+      l_off[j] = (wave * PER + j) * 1024;
     }
   }
   __device__ __forceinline__ void load(const uint16_t *g, unsigned char *tile) const {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) lds_dma16(g + g_off[j], tile + l_off[j]);
+    for (int j = 0; j < PER; ++j) lds_dma16(g + g_off[j], tile + l_off[j]);
   }
   __device__ __forceinline__ void load(const uint16_t *g, unsigned char *tile, int64_t ld) const {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) lds_dma16(g + g_row[j] * ld + g_col[j], tile + l_off[j]);
+    for (int j = 0; j < PER; ++j) lds_dma16(g + g_row[j] * ld + g_col[j], tile + l_off[j]);
   }
 };
+using TileDMA = TileDMAT<4>;
 
 }  // namespace rsa

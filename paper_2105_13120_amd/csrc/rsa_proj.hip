@@ -98,12 +98,12 @@ __global__ void __launch_bounds__(256, 2) proj_gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
         af[mb] = A_KROWS ? tl.read_cols(sc.a[wm], kk * 16, mb)
-                         : (B_KROWS ? tl.read_rows_perm(sc.a[wm], mb * 32, kk, lane)
+                         : (B_KROWS ? tl.read_rows_perm(sc.a[wm], mb * 32, kk)
                                     : tl.read_rows(sc.a[wm], mb * 32, kk));
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb)
         bf[nb] = B_KROWS ? tl.read_cols(sc.b[wn], kk * 16, nb)
-                         : (A_KROWS ? tl.read_rows_perm(sc.b[wn], nb * 32, kk, lane)
+                         : (A_KROWS ? tl.read_rows_perm(sc.b[wn], nb * 32, kk)
                                     : tl.read_rows(sc.b[wn], nb * 32, kk));
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb)
