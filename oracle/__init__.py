@@ -10,3 +10,4 @@ from .rsa_oracle import (  # noqa: F401
     threads,
 )
 from . import proj_oracle as proj  # noqa: F401  (the linear maps of Table 2 around RSA)
+from . import linformer_oracle as linformer  # noqa: F401  (Table 3: projected keys and values)

@@ -8,7 +8,10 @@
 static int bad_problem(const rsa_oracle_problem *p) {
   if (!p) return 1;
   if (p->B < 1 || p->Z < 1 || p->L < 1 || p->A < 1 || p->Lq < 1) return 1;
-  if (p->q0 < 0 || p->q0 + p->Lq > p->L) return 1;
+  /* query rows are tokens q0 .. q0+Lq-1 of the sequence only under the causal mask; without
+     it the row index never enters the arithmetic and the keys may be any set (Table 3's
+     projected keys are fewer than the queries) */
+  if (p->q0 < 0 || (p->causal && p->q0 + p->Lq > p->L)) return 1;
   return 0;
 }
 

@@ -273,7 +273,7 @@ def test_bad_arguments_are_rejected():
     Q = np.zeros((1, 1, 4, 2))
     K = np.zeros((1, 1, 4, 2))
     with pytest.raises(ValueError):
-        oracle.forward(Q, K, K, q0=1)            # rows run past L
+        oracle.forward(Q, K, K, q0=1, causal=True)   # causal rows run past L
     with pytest.raises(ValueError):
         oracle.backward(Q, K, K, Q, cols=[4])    # column out of range
     with pytest.raises(ValueError):
