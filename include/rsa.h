@@ -194,6 +194,34 @@ int rsa_qkv_proj_bwd(const rsa_desc *d, int32_t H, const void *dQ, const void *d
                      const void *dV, const void *X, const void *Wqkv, void *dX,
                      float *dWqkv, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * The Linformer variant of sequence-parallel attention (Table 3): keys and values are
+ * projected along the sequence to Kp rows, every rank with its row block of the (L, Kp)
+ * projection matrix, and the ranks' queries attend to the Kp projected rows (softmax of
+ * Eq. 1 over them; no mask, so d->causal must be 0; fused mode, contiguous ownership).
+ * Kp must be a multiple of 64.  bf16 with fp32 accumulation; dE is fp32.
+ *  rsa_linformer_project: Xp (B, Z, Kp, A) = sum over the tokens l of ranks
+ *    [rank_begin, rank_end) of E[l, :] X[b, z, l, :] -- the partial sum the ranks add up
+ *    (all of it for the whole ring).  X is (B, Z, L, A), E is (L, Kp).  Called for K with E
+ *    and for V with F.  ws: rsa_linformer_workspace_bytes(d, Kp) bytes.
+ *  rsa_linformer_forward / _backward: Q, O, dO, dQ (B, Z, Lq, A); Kp_, Vp_, dKp, dVp
+ *    (B, Z, Kp, A); dKp, dVp are the partial sums over the ranks' query rows.  The
+ *    backward's ws is the same workspace.
+ *  rsa_linformer_project_bwd: dX rows of the ranks' tokens = E dXp (other rows are left
+ *    untouched), dE rows of the ranks' tokens = sum_{b,z} X dXp^T (other rows untouched).
+ */
+size_t rsa_linformer_workspace_bytes(const rsa_desc *d, int32_t Kp);
+int rsa_linformer_project(const rsa_desc *d, int32_t Kp, const void *X, const void *E,
+                          void *Xp, void *ws, size_t ws_bytes, void *stream);
+int rsa_linformer_forward(const rsa_desc *d, int32_t Kp, const void *Q, const void *Kp_,
+                          const void *Vp_, void *O, float *LSE, void *stream);
+int rsa_linformer_backward(const rsa_desc *d, int32_t Kp, const void *dO, const void *Q,
+                           const void *Kp_, const void *Vp_, const void *O,
+                           const float *LSE, void *dQ, void *dKp, void *dVp, void *ws,
+                           size_t ws_bytes, void *stream);
+int rsa_linformer_project_bwd(const rsa_desc *d, int32_t Kp, const void *dXp, const void *X,
+                              const void *E, void *dX, float *dE, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -392,4 +392,79 @@ int rsa_qkv_proj_bwd(const rsa_desc *d, int32_t H, const void *dQ, const void *d
   return hip_status(rsa::proj_qkv_bwd(dm, H, dQ, dK, dV, X, Wqkv, dX, dWqkv, static_cast<float *>(ws), st));
 }
 
+// ---------------------------------------------------------- Linformer ------
+namespace {
+// The attention of the ranks' rows to Kp projected keys: one chunk of Kp keys, no mask.
+int linformer_dims(const rsa_desc *d, int32_t Kp, Dims *own, Dims *att) {
+  int rc = validate(d, own);
+  if (rc != RSA_OK) return rc;
+  if (own->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16 || own->zigzag || own->causal)
+    return RSA_ERR_UNSUPPORTED;
+  if (Kp < 64) return RSA_ERR_SHAPE;
+  if (Kp % 64 != 0) return RSA_ERR_UNSUPPORTED;
+  *att = *own;
+  att->N = 1; att->rank_begin = 0; att->rank_end = 1;
+  att->L = Kp; att->c = Kp;  // Lq stays: the ranks' rows
+  return RSA_OK;
+}
+size_t linformer_ws(const Dims &own, const Dims &att, int64_t Kp) {
+  const int64_t Zt = (int64_t)own.B * own.Z;
+  const size_t part = (size_t)rsa::linformer_splits(Kp, Zt, own.Lq) * Kp * Zt * 64 * 4;
+  const size_t bwd = workspace_bytes(att, RSA_BF16, 1);
+  return align256(part > bwd ? part : bwd);
+}
+}  // namespace
+
+size_t rsa_linformer_workspace_bytes(const rsa_desc *d, int32_t Kp) {
+  Dims own, att;
+  if (linformer_dims(d, Kp, &own, &att) != RSA_OK) return 0;
+  return linformer_ws(own, att, Kp);
+}
+
+#define RSA_LINF_PROLOGUE(ptr_ok, ...)                            \
+  Dims own, att;                                                  \
+  int rc = linformer_dims(d, Kp, &own, &att);                     \
+  if (rc != RSA_OK) return rc;                                    \
+  if (!(ptr_ok)) return RSA_ERR_NULL;                             \
+  { const void *ps_[] = {__VA_ARGS__};                            \
+    for (const void *p_ : ps_) if (misaligned(p_)) return RSA_ERR_UNSUPPORTED; } \
+  hipStream_t st = static_cast<hipStream_t>(stream);              \
+  const int64_t row0 = (int64_t)own.rank_begin * own.c, Zt = (int64_t)own.B * own.Z; \
+  (void)row0; (void)Zt
+
+int rsa_linformer_project(const rsa_desc *d, int32_t Kp, const void *X, const void *E, void *Xp,
+                          void *ws, size_t ws_bytes, void *stream) {
+  RSA_LINF_PROLOGUE(X && E && Xp && ws, X, E, Xp, ws);
+  if (ws_bytes < linformer_ws(own, att, Kp)) return RSA_ERR_WORKSPACE;
+  const char *Xr = static_cast<const char *>(X) + row0 * own.A * 2;
+  const char *Er = static_cast<const char *>(E) + row0 * Kp * 2;
+  return hip_status(rsa::linformer_project(Zt, own.L, own.Lq, Kp, Xr, Er, Xp, static_cast<float *>(ws), st));
+}
+
+int rsa_linformer_forward(const rsa_desc *d, int32_t Kp, const void *Q, const void *Kp_, const void *Vp_,
+                          void *O, float *LSE, void *stream) {
+  RSA_LINF_PROLOGUE(Q && Kp_ && Vp_ && O && LSE, Q, Kp_, Vp_, O, LSE);
+  return hip_status(rsa::fused_forward(att, Q, Kp_, Vp_, O, LSE, st));
+}
+
+int rsa_linformer_backward(const rsa_desc *d, int32_t Kp, const void *dO, const void *Q, const void *Kp_,
+                           const void *Vp_, const void *O, const float *LSE, void *dQ, void *dKp,
+                           void *dVp, void *ws, size_t ws_bytes, void *stream) {
+  RSA_LINF_PROLOGUE(dO && Q && Kp_ && Vp_ && O && LSE && dQ && dKp && dVp && ws, dO, Q, Kp_, Vp_, O, LSE,
+                    dQ, dKp, dVp, ws);
+  if (ws_bytes < linformer_ws(own, att, Kp)) return RSA_ERR_WORKSPACE;
+  return hip_status(rsa::fused_backward(att, dO, Q, Kp_, Vp_, O, LSE, dQ, dKp, dVp, fused_nD(ws),
+                                        fused_nL(att, ws), fused_Qs(att, ws), st));
+}
+
+int rsa_linformer_project_bwd(const rsa_desc *d, int32_t Kp, const void *dXp, const void *X, const void *E,
+                              void *dX, float *dE, void *stream) {
+  RSA_LINF_PROLOGUE(dXp && X && E && dX && dE, dXp, X, E, dX, dE);
+  const char *Xr = static_cast<const char *>(X) + row0 * own.A * 2;
+  const char *Er = static_cast<const char *>(E) + row0 * Kp * 2;
+  char *dXr = static_cast<char *>(dX) + row0 * own.A * 2;
+  float *dEr = dE + row0 * Kp;
+  return hip_status(rsa::linformer_project_bwd(Zt, own.L, own.Lq, Kp, dXp, Xr, Er, dXr, dEr, st));
+}
+
 }  // extern "C"

@@ -316,7 +316,7 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   // under the causal mask later rows see more keys: the long work-groups of a head start first
   const int64_t row0 =
       (CAUSAL ? a.tiles_per_head - 1 - wg % a.tiles_per_head : wg % a.tiles_per_head) * BM;
-  const int n = a.map.rb + (int)(row0 / a.c);  // rank that owns the first row
+  const int n = (a.map.rb + (int)(row0 / a.c)) % a.N;  // rank that owns the first row (see the forward)
   // last token any row of the work-group may look at (its 64-row tiles are runs of tokens)
   int64_t q_last = 0;
 #pragma unroll

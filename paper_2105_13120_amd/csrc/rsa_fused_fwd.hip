@@ -49,7 +49,9 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
   // under the causal mask later rows see more keys: the long work-groups of a head start first
   const int64_t qt = CAUSAL ? a.tiles_per_head - 1 - wg % a.tiles_per_head : wg % a.tiles_per_head;
   const int64_t row0 = qt * BM;  // first local row of this work-group
-  const int n = a.map.rb + (int)(row0 / a.c);  // rank that owns the first row
+  // rank that owns the first row (modulo N: with projected keys, Table 3, the rows are not
+  // tokens of the key sequence and any chunk may come first)
+  const int n = (a.map.rb + (int)(row0 / a.c)) % a.N;
   // last token any row of the work-group may look at (its 64-row tiles are runs of tokens)
   int64_t q_last = 0;
 #pragma unroll

@@ -22,6 +22,8 @@ EXPORTS = (
     "rsa_dp_step", "rsa_softmax_bwd", "rsa_dq_step", "rsa_dk_step", "rsa_store",
     "rsa_bwd_preprocess", "rsa_bwd_dkdv", "rsa_bwd_dq",
     "rsa_proj_workspace_bytes", "rsa_qkv_proj", "rsa_out_proj", "rsa_out_proj_bwd", "rsa_qkv_proj_bwd",
+    "rsa_linformer_workspace_bytes", "rsa_linformer_project", "rsa_linformer_forward",
+    "rsa_linformer_backward", "rsa_linformer_project_bwd",
 )
 
 
@@ -83,6 +85,12 @@ def lib():
         for name in EXPORTS[3:]:
             getattr(L, name).restype = i
         L.rsa_proj_workspace_bytes.restype = sz
+        L.rsa_linformer_workspace_bytes.argtypes = [dp, i]
+        L.rsa_linformer_workspace_bytes.restype = sz
+        L.rsa_linformer_project.argtypes = [dp, i, vp, vp, vp, vp, sz, vp]
+        L.rsa_linformer_forward.argtypes = [dp, i] + [vp] * 6
+        L.rsa_linformer_backward.argtypes = [dp, i] + [vp] * 10 + [sz, vp]
+        L.rsa_linformer_project_bwd.argtypes = [dp, i] + [vp] * 6
         _lib = L
     return _lib
 
@@ -271,3 +279,51 @@ def qkv_proj_bwd(desc, dQ, dK, dV, X, Wqkv, dX=None, dW=None, ws=None):
     _check(lib().rsa_qkv_proj_bwd(ctypes.byref(desc), H, _p(dQ), _p(dK), _p(dV), _p(X), _p(Wqkv), _p(dX),
                                   _p(dW), _p(ws), ws.numel(), _stream()))
     return dX, dW
+
+
+# ---- Linformer variant (Table 3): keys and values projected along the sequence ----
+def linformer_workspace_bytes(desc, Kp):
+    return int(lib().rsa_linformer_workspace_bytes(ctypes.byref(desc), int(Kp)))
+
+
+def _linf_ws(desc, Kp, device):
+    return torch.empty(max(linformer_workspace_bytes(desc, Kp), 16), dtype=torch.uint8, device=device)
+
+
+def linformer_project(desc, X, E, Xp=None, ws=None):
+    """X (B, Z, L, A), E (L, Kp) -> Xp (B, Z, Kp, A), over the tokens of the descriptor's ranks."""
+    Kp = E.shape[1]
+    if Xp is None:
+        Xp = torch.empty((X.shape[0], X.shape[1], Kp, X.shape[3]), dtype=X.dtype, device=X.device)
+    ws = _linf_ws(desc, Kp, X.device) if ws is None else ws
+    _check(lib().rsa_linformer_project(ctypes.byref(desc), Kp, _p(X), _p(E), _p(Xp), _p(ws), ws.numel(),
+                                       _stream()))
+    return Xp
+
+
+def linformer_forward(desc, Q, Kp_, Vp_, O=None, LSE=None):
+    O = torch.empty_like(Q) if O is None else O
+    LSE = torch.empty(Q.shape[:3], dtype=torch.float32, device=Q.device) if LSE is None else LSE
+    _check(lib().rsa_linformer_forward(ctypes.byref(desc), Kp_.shape[2], _p(Q), _p(Kp_), _p(Vp_), _p(O),
+                                       _p(LSE), _stream()))
+    return O, LSE
+
+
+def linformer_backward(desc, dO, Q, Kp_, Vp_, O, LSE, dQ=None, dKp=None, dVp=None, ws=None):
+    Kp = Kp_.shape[2]
+    dQ = torch.empty_like(Q) if dQ is None else dQ
+    dKp = torch.empty_like(Kp_) if dKp is None else dKp
+    dVp = torch.empty_like(Vp_) if dVp is None else dVp
+    ws = _linf_ws(desc, Kp, Q.device) if ws is None else ws
+    _check(lib().rsa_linformer_backward(ctypes.byref(desc), Kp, _p(dO), _p(Q), _p(Kp_), _p(Vp_), _p(O),
+                                        _p(LSE), _p(dQ), _p(dKp), _p(dVp), _p(ws), ws.numel(), _stream()))
+    return dQ, dKp, dVp
+
+
+def linformer_project_bwd(desc, dXp, X, E, dX=None, dE=None):
+    """dX (rows of the descriptor's ranks; a new tensor is zero elsewhere) and dE (fp32, same)."""
+    dX = torch.zeros_like(X) if dX is None else dX
+    dE = torch.zeros(E.shape, dtype=torch.float32, device=E.device) if dE is None else dE
+    _check(lib().rsa_linformer_project_bwd(ctypes.byref(desc), E.shape[1], _p(dXp), _p(X), _p(E), _p(dX),
+                                           _p(dE), _stream()))
+    return dX, dE
