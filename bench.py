@@ -157,6 +157,45 @@ def projections_report(cfg, torch, rsa):
             "frac_of_bf16_peak": round(3 * f_fwd / ((tf + tb) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
 
 
+def linformer_report(torch, rsa):
+    """The Linformer variant (Table 3) at the paper's sequence-length upper bound (section 4.4):
+    114688 tokens, batch 4, BERT-Base heads (Z = 12, A = 64), 32 ranks simulated on the one GPU,
+    projection dimension 256.  Forward = 2 projections + attention; backward = attention backward +
+    2 projection backwards.  Flops: 4*B*Z*L*Kp*A per projection pair and per attention product pair."""
+    B, Z, A, L, N, Kp = 4, 12, 64, 114688, 32, 256
+    g = torch.Generator(device="cuda").manual_seed(0)
+    rnd = lambda *shape, s=1.0: (torch.randn(shape, generator=g, device="cuda") * s).to(torch.bfloat16)
+    Q, K, V, dO = (rnd(B, Z, L, A) for _ in range(4))
+    E, F = rnd(L, Kp, s=L ** -0.5), rnd(L, Kp, s=L ** -0.5)
+    desc = rsa.make_desc(K, N)
+    ws = torch.empty(max(rsa.linformer_workspace_bytes(desc, Kp), 16), dtype=torch.uint8, device="cuda")
+    Kp_, Vp_ = rsa.linformer_project(desc, K, E, ws=ws), rsa.linformer_project(desc, V, F, ws=ws)
+    O, LSE = rsa.linformer_forward(desc, Q, Kp_, Vp_)
+    dQ, dKp, dVp = rsa.linformer_backward(desc, dO, Q, Kp_, Vp_, O, LSE, ws=ws)
+    dK, dE = rsa.linformer_project_bwd(desc, dKp, K, E)
+    dV, dF = rsa.linformer_project_bwd(desc, dVp, V, F)
+
+    def fwd():
+        rsa.linformer_project(desc, K, E, Kp_, ws)
+        rsa.linformer_project(desc, V, F, Vp_, ws)
+        rsa.linformer_forward(desc, Q, Kp_, Vp_, O, LSE)
+
+    def bwd():
+        rsa.linformer_backward(desc, dO, Q, Kp_, Vp_, O, LSE, dQ, dKp, dVp, ws)
+        rsa.linformer_project_bwd(desc, dKp, K, E, dK, dE)
+        rsa.linformer_project_bwd(desc, dVp, V, F, dV, dF)
+
+    for _ in range(10):
+        fwd(); bwd()
+    tf, tb = event_ms(fwd, 20, torch), event_ms(bwd, 20, torch)
+    pair = 4.0 * B * Z * L * Kp * A            # two products of 2*B*Z*L*Kp*A flops
+    flops_f, flops_b = 2 * pair, 4 * pair      # fwd: projections + QK^T, PV; bwd: twice that
+    return {"B": B, "Z": Z, "L": L, "N": N, "Kp": Kp, "fwd_ms": round(tf, 3), "bwd_ms": round(tb, 3),
+            "tflops": round((flops_f + flops_b) / ((tf + tb) * 1e-3) / 1e12, 1),
+            "tokens_per_s": round(B * L / ((tf + tb) * 1e-3), 1),
+            "hbm_gb_resident": round(torch.cuda.max_memory_allocated() / 1e9, 2)}
+
+
 def staged_report(cfg, torch, rsa, inputs):
     """The paper's two-pass layout for one simulated rank (rank 0): time every ring step
     kernel with HIP events and price the memory-bound ones against HBM."""
@@ -271,6 +310,7 @@ def main():
                            "kernel_ms": {n: round(v, 4) for n, v in r2["kernel_ms"].items()}}
         out["other_workloads"] = other
         out["projections"] = projections_report(cfg, torch, rsa)
+        out["linformer_114k"] = linformer_report(torch, rsa)
     if a.staged:
         out["staged"] = staged_report(cfg, torch, rsa, inputs)
     if a.profile_copy > 0:

@@ -410,7 +410,10 @@ int linformer_dims(const rsa_desc *d, int32_t Kp, Dims *own, Dims *att) {
 size_t linformer_ws(const Dims &own, const Dims &att, int64_t Kp) {
   const int64_t Zt = (int64_t)own.B * own.Z;
   const size_t part = (size_t)rsa::linformer_splits(Kp, Zt, own.Lq) * Kp * Zt * 64 * 4;
-  const size_t bwd = workspace_bytes(att, RSA_BF16, 1);
+  // backward: row terms and Qs, then the fp32 partial dV, dK of the split query walk
+  const int qs = rsa::fused_bwd_dkdv_splits(att);
+  const size_t bwd = workspace_bytes(att, RSA_BF16, 1) +
+                     (qs > 1 ? (size_t)2 * qs * Zt * Kp * 64 * 4 : 0);
   return align256(part > bwd ? part : bwd);
 }
 }  // namespace
@@ -453,8 +456,11 @@ int rsa_linformer_backward(const rsa_desc *d, int32_t Kp, const void *dO, const 
   RSA_LINF_PROLOGUE(dO && Q && Kp_ && Vp_ && O && LSE && dQ && dKp && dVp && ws, dO, Q, Kp_, Vp_, O, LSE,
                     dQ, dKp, dVp, ws);
   if (ws_bytes < linformer_ws(own, att, Kp)) return RSA_ERR_WORKSPACE;
+  const int qs = rsa::fused_bwd_dkdv_splits(att);
+  float *part = qs > 1 ? reinterpret_cast<float *>(static_cast<char *>(ws) + workspace_bytes(att, RSA_BF16, 1))
+                       : nullptr;
   return hip_status(rsa::fused_backward(att, dO, Q, Kp_, Vp_, O, LSE, dQ, dKp, dVp, fused_nD(ws),
-                                        fused_nL(att, ws), fused_Qs(att, ws), st));
+                                        fused_nL(att, ws), fused_Qs(att, ws), st, part, qs));
 }
 
 int rsa_linformer_project_bwd(const rsa_desc *d, int32_t Kp, const void *dXp, const void *X, const void *E,

@@ -22,6 +22,7 @@ struct BwdArgs {
   const uint16_t *Q, *Qs, *K, *V, *dO;  // Qs = bf16(Q * scale * log2 e)
   const float *nL, *nD;                 // -LSE log2e and -D per query row
   uint16_t *dQ, *dK, *dV;
+  float *part;  // dK/dV kernel with a split query walk: fp32 partial dV, then dK, per split
   int64_t L, c, Lq;
   RowMap map;  // local query row -> global token index
   int N, tiles_per_head;
@@ -136,7 +137,12 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
       v = v || (qt + u < nqt && a.map((int64_t)(qt + u) * 64) + 63 >= key0);
     return v;
   };
-  auto advance = [&](int i) { ++i; while (i < nst && !visible(i)) ++i; return i; };
+  // With few keys (Table 3's projected keys) the walk over the query stages is split over
+  // gridDim.y work-groups, each writing fp32 partial sums that a second kernel adds up.
+  const int per_split = (nst + (int)gridDim.y - 1) / (int)gridDim.y;
+  const int i_begin = (int)blockIdx.y * per_split;
+  const int i_end = i_begin + per_split < nst ? i_begin + per_split : nst;
+  auto advance = [&](int i) { ++i; while (i < i_end && !visible(i)) ++i; return i; };
 
   const TileDMA dma(wave, lane);
   auto load_stage = [&](int i, Stage &sn) __attribute__((always_inline)) {
@@ -156,14 +162,15 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
     }
   };
 
-  int i = visible(0) ? 0 : advance(0);
-  if (i < nst) load_stage(i, stage0);
+  int i = i_begin;
+  if (i < i_end && !visible(i)) i = advance(i);
+  if (i < i_end) load_stage(i, stage0);
   wait_vmem();
   __syncthreads();
   // one stage: start the loads of the next stage into sn, compute on sc
   auto stage = [&](Stage &sc, Stage &sn) __attribute__((always_inline)) {
     const int inext = advance(i);
-    if (inext < nst) load_stage(inext, sn);
+    if (inext < i_end) load_stage(inext, sn);
 
     // The 32 MFMAs of a tile go in four groups of eight -- S', dP' of rows 0..31 (G0) and of
     // rows 32..63 (G1), then dV, dK over rows 0..31 (H0) and 32..63 (H1) -- and the vector work
@@ -273,29 +280,40 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
     __syncthreads();
     i = inext;
   };
-  while (i < nst) {
+  while (i < i_end) {
     stage(stage0, stage1);
-    if (i >= nst) break;
+    if (i >= i_end) break;
     stage(stage1, stage0);
   }
 
-  uint16_t *dKh = a.dK + head * a.L * 64;
-  uint16_t *dVh = a.dV + head * a.L * 64;
-  const int64_t key = wkey0 + col;
-  if (key < a.L) {
+  if (gridDim.y > 1) {  // fp32 partial sums: [dV | dK][split][head][key][64]
+    const int64_t heads = gridDim.x / a.tiles_per_head;
+    const int64_t key = wkey0 + col;
+    float *pv = a.part + (((int64_t)blockIdx.y * heads + head) * a.L + key) * 64;
+    float *pk = pv + (int64_t)gridDim.y * heads * a.L * 64;
+    if (key < a.L) {
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+      for (int db = 0; db < 2; ++db)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int64_t off = key * 64 + db * 32 + g * 8 + half * 4;
-        u32x2 w = {pack_bf16(dv[db][g * 4 + 0], dv[db][g * 4 + 1]),
-                   pack_bf16(dv[db][g * 4 + 2], dv[db][g * 4 + 3])};
-        *reinterpret_cast<u32x2 *>(dVh + off) = w;
-        u32x2 x = {pack_bf16(dk_[db][g * 4 + 0] * kLn2, dk_[db][g * 4 + 1] * kLn2),
-                   pack_bf16(dk_[db][g * 4 + 2] * kLn2, dk_[db][g * 4 + 3] * kLn2)};
-        *reinterpret_cast<u32x2 *>(dKh + off) = x;
-      }
+        for (int g = 0; g < 4; ++g) {
+          const int off = db * 32 + g * 8 + half * 4;
+          const f32x4 w = {dv[db][g * 4 + 0], dv[db][g * 4 + 1], dv[db][g * 4 + 2], dv[db][g * 4 + 3]};
+          *reinterpret_cast<f32x4 *>(pv + off) = w;
+          const f32x4 x = {dk_[db][g * 4 + 0] * kLn2, dk_[db][g * 4 + 1] * kLn2, dk_[db][g * 4 + 2] * kLn2,
+                           dk_[db][g * 4 + 3] * kLn2};
+          *reinterpret_cast<f32x4 *>(pk + off) = x;
+        }
+    }
+    return;
   }
+
+  // the wave's 32 x 64 blocks of dV and dK leave through its own LDS tile as whole 128-byte rows
+  // (every wave is past the loop's last barrier and no load is in flight: the buffers are free)
+  unsigned char *ot = wave < 2 ? stage0.Qs[wave] : stage0.dOs[wave - 2];
+  stage_block_T(ot, 0, dv[0], dv[1], 1.0f, lane);
+  stage_block_T(ot, 32, dk_[0], dk_[1], kLn2, lane);
+  flush_rows<32>(ot, 0, a.dV + (head * a.L + wkey0) * 64, a.L - wkey0, lane);
+  flush_rows<32>(ot, 32, a.dK + (head * a.L + wkey0) * 64, a.L - wkey0, lane);
 }
 
 // ---------------------------------------------------------------------- dQ ---
@@ -474,21 +492,23 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
     stage(Ks1, Vs1, Ks0, Vs0);
   }
 
-  uint16_t *dQh = a.dQ + head * a.Lq * 64;
+  // the wave's R x 64 block of dQ leaves through its own LDS tile as whole 128-byte rows
+  unsigned char *ot = wave == 0 ? Ks0[0] : (wave == 1 ? Ks1[0] : (wave == 2 ? Vs0[0] : Vs1[0]));
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const int64_t r = row0 + wave * R + qb * 32 + col;
-    if (r < a.Lq) {
-#pragma unroll
-      for (int db = 0; db < 2; ++db)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          u32x2 w = {pack_bf16(dq[db][qb][g * 4 + 0] * a.scale, dq[db][qb][g * 4 + 1] * a.scale),
-                     pack_bf16(dq[db][qb][g * 4 + 2] * a.scale, dq[db][qb][g * 4 + 3] * a.scale)};
-          *reinterpret_cast<u32x2 *>(dQh + r * 64 + db * 32 + g * 8 + half * 4) = w;
-        }
-    }
-  }
+  for (int qb = 0; qb < QB; ++qb) stage_block_T(ot, qb * 32, dq[0][qb], dq[1][qb], a.scale, lane);
+  const int64_t wr0 = row0 + wave * R;
+  flush_rows<R>(ot, 0, a.dQ + (head * a.Lq + wr0) * 64, a.Lq - wr0, lane);
+}
+
+// out (bf16) = sum over the splits of part[s][i], in a fixed order; n4 groups of four per split
+__global__ void __launch_bounds__(256) qsplit_reduce_kernel(const float *part, uint16_t *out, int64_t n4,
+                                                            int splits) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n4) return;
+  f32x4 s = reinterpret_cast<const f32x4 *>(part)[i];
+  for (int k = 1; k < splits; ++k) s += reinterpret_cast<const f32x4 *>(part)[(int64_t)k * n4 + i];
+  const u32x2 w = {pack_bf16(s[0], s[1]), pack_bf16(s[2], s[3])};
+  reinterpret_cast<u32x2 *>(out)[i] = w;
 }
 
 static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const void *Qs,
@@ -499,6 +519,7 @@ static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const
   a.K = (const uint16_t *)K; a.V = (const uint16_t *)V;
   a.dO = (const uint16_t *)dO; a.nL = nL; a.nD = nD;
   a.dQ = (uint16_t *)dQ; a.dK = (uint16_t *)dK; a.dV = (uint16_t *)dV;
+  a.part = nullptr;
   a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.map = make_row_map(d);
   a.N = d.N; a.cl2 = d.scale * kLog2e; a.scale = d.scale;
   a.tiles_per_head = 0;
@@ -515,16 +536,33 @@ hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, co
   return hipGetLastError();
 }
 
+int fused_bwd_dkdv_splits(const Dims &d) {
+  const int64_t wgs = (int64_t)d.B * d.Z * ((d.L + 127) / 128), stages = (d.Lq / 64 + 1) / 2;
+  int64_t s = 1024 / wgs;  // aim at two work-groups per CU's worth of them
+  if (s > stages / 8) s = stages / 8;
+  if (s > 64) s = 64;
+  return s < 2 ? 1 : (int)s;
+}
+
 hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Qs, const void *K,
                           const void *V, const float *nL, const float *nD, void *dK, void *dV,
-                          hipStream_t st) {
+                          hipStream_t st, float *part, int splits) {
   BwdArgs a = make_bwd_args(d, dO, nullptr, Qs, K, V, nL, nD, nullptr, dK, dV);
   a.tiles_per_head = (int)((d.L + 127) / 128);
-  dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head));
+  a.part = part;
+  if (!part) splits = 1;
+  dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head), (unsigned)splits);
   if (d.causal)
     hipLaunchKernelGGL((fused_bwd_dkdv_kernel<2, true>), grid, dim3(256), 0, st, a);
   else
     hipLaunchKernelGGL((fused_bwd_dkdv_kernel<2, false>), grid, dim3(256), 0, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || splits == 1) return e;
+  const int64_t n4 = (int64_t)d.B * d.Z * d.L * 16;
+  const dim3 rg((unsigned)((n4 + 255) / 256));
+  hipLaunchKernelGGL(qsplit_reduce_kernel, rg, dim3(256), 0, st, part, (uint16_t *)dV, n4, splits);
+  hipLaunchKernelGGL(qsplit_reduce_kernel, rg, dim3(256), 0, st, part + (int64_t)splits * n4 * 4,
+                     (uint16_t *)dK, n4, splits);
   return hipGetLastError();
 }
 
@@ -542,10 +580,11 @@ hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void
 
 hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const void *K,
                           const void *V, const void *O, const float *LSE, void *dQ, void *dK,
-                          void *dV, float *nD, float *nL, void *Qs, hipStream_t st) {
+                          void *dV, float *nD, float *nL, void *Qs, hipStream_t st, float *part,
+                          int splits) {
   hipError_t e = fused_bwd_preprocess(d, dO, O, Q, LSE, nD, nL, Qs, st);
   if (e != hipSuccess) return e;
-  e = fused_bwd_dkdv(d, dO, Qs, K, V, nL, nD, dK, dV, st);
+  e = fused_bwd_dkdv(d, dO, Qs, K, V, nL, nD, dK, dV, st, part, splits);
   if (e != hipSuccess) return e;
   return fused_bwd_dq(d, dO, Q, K, V, nL, nD, dQ, st);
 }

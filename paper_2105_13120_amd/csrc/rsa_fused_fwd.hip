@@ -247,25 +247,20 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
     stage(Ks1, Vs1, Ks0, Vs0);
   }
 
-  // ---- epilogue: O = O^T / l, LSE = s m + ln l
-  uint16_t *Oh = a.O + head * a.Lq * 64;
+  // ---- epilogue: O = O^T / l, LSE = s m + ln l.  The wave's R x 64 block of O goes through its
+  // own LDS tile (every wave is past the loop's last barrier and no load is in flight, so the
+  // stage buffers are free) and leaves as whole 128-byte rows.
+  unsigned char *ot = wave == 0 ? Ks0[0] : (wave == 1 ? Ks1[0] : (wave == 2 ? Vs0[0] : Vs1[0]));
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const float lt = xhalf_sum(l[qb]);
     const float inv = 1.0f / lt;
     const int64_t r = row0 + wave * R + qb * 32 + col;
-    if (r < a.Lq) {
-#pragma unroll
-      for (int db = 0; db < 2; ++db)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          u32x2 w = {pack_bf16(o[db][qb][g * 4 + 0] * inv, o[db][qb][g * 4 + 1] * inv),
-                     pack_bf16(o[db][qb][g * 4 + 2] * inv, o[db][qb][g * 4 + 3] * inv)};
-          *reinterpret_cast<u32x2 *>(Oh + r * 64 + db * 32 + g * 8 + half * 4) = w;
-        }
-      if (half == 0) a.LSE[head * a.Lq + r] = (mc[qb] + __builtin_amdgcn_logf(lt)) * kLn2;
-    }
+    stage_block_T(ot, qb * 32, o[0][qb], o[1][qb], inv, lane);
+    if (r < a.Lq && half == 0) a.LSE[head * a.Lq + r] = (mc[qb] + __builtin_amdgcn_logf(lt)) * kLn2;
   }
+  const int64_t wr0 = row0 + wave * R;
+  flush_rows<R>(ot, 0, a.O + (head * a.Lq + wr0) * 64, a.Lq - wr0, lane);
 }
 
 template <int R>

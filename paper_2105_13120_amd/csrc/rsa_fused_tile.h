@@ -83,6 +83,38 @@ struct TileLanes {
 // swizzled layout above.  `g` points at element [0][0] of the tile in global memory
 // (rows 64 elements apart, or `ld` elements apart in the second form of load).
 // Completion: wait_vmem(), then a barrier.
+// A wave's block of 32 output rows x 64 columns, held transposed in two accumulators
+// (acc[db]: rows = columns db*32 .. +32 of the output, column = output row), is put into rows
+// row_base .. +32 of the wave's own LDS tile as bf16 (times `scale`).
+__device__ __forceinline__ void stage_block_T(unsigned char *tile, int row_base, const f32x16 &acc0,
+                                              const f32x16 &acc1, float scale, int lane) {
+  const int col = lane & 31, half = lane >> 5;
+#pragma unroll
+  for (int db = 0; db < 2; ++db) {
+    const f32x16 &c = db == 0 ? acc0 : acc1;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const u32x2 w = {pack_bf16(c[g * 4 + 0] * scale, c[g * 4 + 1] * scale),
+                       pack_bf16(c[g * 4 + 2] * scale, c[g * 4 + 3] * scale)};
+      *reinterpret_cast<u32x2 *>(tile + tile_off(row_base + col, db * 4 + g) + half * 8) = w;
+    }
+  }
+}
+// ... and rows [first, first + ROWS) of the tile leave for global memory (rows of 64 bf16, 128
+// bytes apart) as 16-byte pieces: one wave instruction stores 8 whole rows = 1 KiB in a row.
+// Rows at or beyond rows_valid (counted from row 0 of g) are skipped.
+template <int ROWS>
+__device__ __forceinline__ void flush_rows(const unsigned char *tile, int first, uint16_t *g,
+                                           int64_t rows_valid, int lane) {
+#pragma unroll
+  for (int it = 0; it < ROWS / 8; ++it) {
+    const int row = it * 8 + (lane >> 3), cc = lane & 7;
+    if (row < rows_valid)
+      *reinterpret_cast<u32x4 *>(g + (int64_t)row * 64 + cc * 8) =
+          *reinterpret_cast<const u32x4 *>(tile + tile_off(first + row, cc));
+  }
+}
+
 template <int WAVES>
 struct TileDMAT {
   static constexpr int PER = 8 / WAVES;

@@ -36,14 +36,18 @@ hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void
 // nD = -rowsum(dO o O) and nL = -LSE log2e, (B,Z,Lq) fp32; Qs = bf16(Q * scale * log2 e) (B,Z,Lq,64)
 hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, const void *Q,
                                 const float *LSE, float *nD, float *nL, void *Qs, hipStream_t st);
+// part / splits: optional split of the walk over the query rows (few keys, many rows): fp32
+// partial dV and dK, 2 * splits * B*Z*L*64 floats, added up in a fixed order; nullptr / 1: none
+int fused_bwd_dkdv_splits(const Dims &d);
 hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Qs, const void *K,
                           const void *V, const float *nL, const float *nD, void *dK, void *dV,
-                          hipStream_t st);
+                          hipStream_t st, float *part = nullptr, int splits = 1);
 hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void *K, const void *V,
                         const float *nL, const float *nD, void *dQ, hipStream_t st);
 hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const void *K,
                           const void *V, const void *O, const float *LSE, void *dQ, void *dK,
-                          void *dV, float *nD, float *nL, void *Qs, hipStream_t st);
+                          void *dV, float *nD, float *nL, void *Qs, hipStream_t st,
+                          float *part = nullptr, int splits = 1);
 
 // --- the linear maps around RSA (Table 2, rows Q/K/V and Linear), bf16, A = 64 ---
 // X, dX, Y, dY: (B, Lq, H); W: (H, 3*Z*64), columns [Q | K | V] head-major; Wo: (Z*64, H);

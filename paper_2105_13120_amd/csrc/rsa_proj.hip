@@ -121,6 +121,49 @@ __global__ void __launch_bounds__(256, 2) proj_gemm_kernel(GemmArgs g) {
   }
 
   // lane (col, half) holds, for output row m, the columns n = nb*32 + grp*8 + half*4 .. +4
+  if (!OUT_F32) {
+    // bf16: the wave's 64 x 64 block goes through its own LDS tile (every wave is past the last
+    // barrier of the loop, so the stage buffers are free) and leaves as 16-byte pieces, eight
+    // lanes per 128-byte row segment, instead of 8-byte pieces 128 bytes or more apart.
+    unsigned char *t = wave < 2 ? stage0.a[wave] : stage0.b[wave - 2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int grp = 0; grp < 4; ++grp) {
+          const f32x16 &c = acc[nb][mb];
+          const u32x2 w = {pack_bf16(c[grp * 4 + 0], c[grp * 4 + 1]), pack_bf16(c[grp * 4 + 2], c[grp * 4 + 3])};
+          *reinterpret_cast<u32x2 *>(t + tile_off(mb * 32 + col, nb * 4 + grp) + half * 8) = w;
+        }
+    const int64_t nw = n0 + wn * 64;  // the block's 64 columns: one head of a head-split output
+    if (nw < g.N) {
+      int which = 0;
+      int64_t zoff = 0;
+      if (g.out_split) {
+        const int64_t hb = nw / 64;
+        which = (int)(hb / g.out_Z);
+        zoff = hb % g.out_Z;
+      }
+      uint16_t *base = static_cast<uint16_t *>(which == 0 ? g.out[0] : (which == 1 ? g.out[1] : g.out[2]));
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int row = it * 8 + (lane >> 3), cc = lane & 7;
+        const int64_t m = m0 + wm * 64 + row;
+        if (m >= g.M) continue;
+        const u32x4 w = *reinterpret_cast<const u32x4 *>(t + tile_off(row, cc));
+        int64_t off;
+        if (!g.out_split) {
+          off = m * g.out_ld + nw + cc * 8;
+        } else {
+          const int64_t b = m / g.out_rows, r = m % g.out_rows;
+          off = ((b * g.out_Z + zoff) * g.out_rows + r) * 64 + cc * 8;
+        }
+        *reinterpret_cast<u32x4 *>(base + off) = w;
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb) {
     const int64_t m = m0 + wm * 64 + mb * 32 + col;
@@ -131,24 +174,10 @@ __global__ void __launch_bounds__(256, 2) proj_gemm_kernel(GemmArgs g) {
       for (int grp = 0; grp < 4; ++grp) {
         const int64_t n = n0 + wn * 64 + nb * 32 + grp * 8 + half * 4;
         if (n >= g.N) continue;
-        int64_t off;
-        int which = 0;
-        if (!g.out_split) {
-          off = ((int64_t)blockIdx.y * g.M + m) * g.out_ld + n;
-        } else {
-          const int64_t hb = n / 64;
-          which = (int)(hb / g.out_Z);
-          const int64_t z = hb % g.out_Z, b = m / g.out_rows, r = m % g.out_rows;
-          off = ((b * g.out_Z + z) * g.out_rows + r) * 64 + (n & 63);
-        }
+        const int64_t off = ((int64_t)blockIdx.y * g.M + m) * g.out_ld + n;  // fp32 outputs are plain matrices
         const f32x16 &c = acc[nb][mb];
-        if (OUT_F32) {
-          const f32x4 w = {c[grp * 4 + 0], c[grp * 4 + 1], c[grp * 4 + 2], c[grp * 4 + 3]};
-          *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out[which]) + off) = w;
-        } else {
-          const u32x2 w = {pack_bf16(c[grp * 4 + 0], c[grp * 4 + 1]), pack_bf16(c[grp * 4 + 2], c[grp * 4 + 3])};
-          *reinterpret_cast<u32x2 *>(static_cast<uint16_t *>(g.out[which]) + off) = w;
-        }
+        const f32x4 w = {c[grp * 4 + 0], c[grp * 4 + 1], c[grp * 4 + 2], c[grp * 4 + 3]};
+        *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out[0]) + off) = w;
       }
   }
 }
