@@ -6,11 +6,11 @@
 // 64 x 64 tiles that are either blocks of a plain row-major matrix or the (64 rows, one head)
 // blocks of up to three (B, Z, rows, 64) tensors, so no tensor is ever re-laid out in memory.
 //
-// Work-group: 128 x 128 outputs, 4 waves of 64 x 64 (2 x 2 MFMA blocks of 32 x 32), k in slabs
-// of 64 through the swizzled LDS tiles of the attention kernels (direct global->LDS loads,
-// two named stage buffers, one barrier per slab).  The product is formed transposed
-// (accumulator rows = n, columns = m): a lane then owns one output row m and four consecutive
-// n per register group, which is an 8- or 16-byte store.
+// Work-group: 256 x 256 outputs, 8 waves of 128 x 64 (4 x 2 MFMA blocks of 32 x 32), k in slabs
+// of 64 through the swizzled LDS tiles of the attention kernels, double-buffered, one barrier
+// per slab.  The product is formed transposed (accumulator rows = n, columns = m): a lane then
+// owns one output row m and four consecutive n per register group; bf16 blocks leave through
+// LDS as whole 128-byte row segments, fp32 blocks as 16-byte pieces.
 #include "rsa_fused_tile.h"
 #include "rsa_kernels.h"
 
@@ -35,6 +35,74 @@ struct MatView {
   }
 };
 
+// A value that is the same in every lane, moved to scalar registers (integer division leaves
+// its result in vector registers even when its operands are uniform).
+__device__ __forceinline__ int64_t uniform64(int64_t x) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)x >> 32));
+  return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+// How the tiles of one operand move along k, slab by slab, with additions only (the divisions
+// that place a head-split tile are done once, in TileCursor's constructor): `step` per slab, and
+// after `period` steps an extra jump to the next batch element (mode 1) or to the next tensor of
+// the view (mode 2: jump1 into tensor 1, jump2 into tensor 2).
+struct ViewWalk {
+  int64_t ld, step, jump1, jump2;
+  int period, mode;
+  // krows: k runs over the row tiles of the view; else over its column tiles
+  __device__ __forceinline__ ViewWalk(const MatView &v, bool krows) {
+    jump1 = 0; jump2 = 0; period = 0x7fffffff; mode = 0;
+    if (!v.split) {
+      ld = v.ld;
+      step = krows ? 64 * v.ld : 64;
+    } else if (!krows) {  // k runs over heads, then over the tensors of the view
+      ld = 64;
+      step = v.rows * 64;
+      // after the last head of a tensor the pointer has moved Z steps; the next tensor starts over
+      jump1 = (v.p[1] - v.p[0]) - (int64_t)v.Z * step;
+      jump2 = (v.p[2] - v.p[1]) - (int64_t)v.Z * step;
+      period = v.Z; mode = 2;
+    } else {  // k runs over the rows of a batch element, then over batch elements
+      ld = 64;
+      step = 64 * 64;
+      jump1 = (int64_t)(v.Z - 1) * v.rows * 64;
+      period = (int)(v.rows / 64); mode = 1;
+    }
+  }
+};
+
+struct TileCursor {
+  const uint16_t *ptr;
+  int cnt, which;
+  // krows: the tile index `fixed` selects columns and k (slab ks) selects rows; else the reverse
+  __device__ __forceinline__ TileCursor(const MatView &v, bool krows, int64_t fixed, int64_t ks) {
+    cnt = 0; which = 0;
+    if (!v.split) {
+      ptr = krows ? v.p[0] + ks * 64 * v.ld + fixed * 64 : v.p[0] + fixed * 64 * v.ld + ks * 64;
+    } else {
+      const uint32_t ct = (uint32_t)(krows ? fixed : ks), rt = (uint32_t)(krows ? ks : fixed);
+      which = (int)(ct / (uint32_t)v.Z);
+      const int64_t z = ct % (uint32_t)v.Z;
+      const uint32_t m0 = rt * 64u, b = m0 / (uint32_t)v.rows, r0 = m0 % (uint32_t)v.rows;
+      const uint16_t *t = which == 0 ? v.p[0] : (which == 1 ? v.p[1] : v.p[2]);
+      ptr = t + (((int64_t)b * v.Z + z) * v.rows + r0) * 64;
+      cnt = krows ? (int)(r0 / 64) : (int)z;
+    }
+    ptr = reinterpret_cast<const uint16_t *>(uniform64(reinterpret_cast<int64_t>(ptr)));
+    cnt = __builtin_amdgcn_readfirstlane(cnt);
+    which = __builtin_amdgcn_readfirstlane(which);
+  }
+  __device__ __forceinline__ void advance(const ViewWalk &w) {
+    ptr += w.step;
+    if (++cnt == w.period) {
+      cnt = 0;
+      if (w.mode == 1) ptr += w.jump1;
+      if (w.mode == 2) { ptr += which == 0 ? w.jump1 : w.jump2; ++which; }
+    }
+  }
+};
+
 struct GemmArgs {
   MatView A, B;       // m-side and n-side operands
   int64_t M, N, K;    // multiples of 64
@@ -47,117 +115,131 @@ struct GemmArgs {
 
 // A_KROWS / B_KROWS: the operand's tiles hold k along their rows (the view is [K][M] or [K][N])
 // instead of along their columns ([M][K], [N][K]).
+// Work-group: 8 waves, 256 (m) x 256 (n) outputs; wave (wm, wn) of a 2 x 4 grid owns 128 x 64
+// (4 x 2 MFMA blocks).  The tile is this large because a CU takes at most about 40 bytes per clock
+// from global memory (measured, L2-resident data): a 128 x 128 tile needs 32 KiB per 512 matrix-pipe
+// cycles and is bound by that at 30 % of the peak; this one needs 64 KiB per 2048.
+// A slab of 64 k is 8 tiles = 64 KiB; the next slab is fetched into registers (8 x 16 bytes per
+// lane) while the current one is used from LDS, then written to the other LDS buffer: one barrier
+// per slab.  (Direct global->LDS loads would save the registers, but the compiler only lets LDS
+// reads pass outstanding direct loads when the buffers are distinct objects, i.e. with two copies
+// of the loop body, and two copies of a body with 128 accumulator registers do not agree on
+// where the accumulators live.)
+constexpr int kGemmBM = 256, kGemmBN = 256;
 template <bool A_KROWS, bool B_KROWS, bool OUT_F32>
-__global__ void __launch_bounds__(256, 2) proj_gemm_kernel(GemmArgs g) {
-  struct Stage { unsigned char a[2][kTileBytes], b[2][kTileBytes]; };
-  __shared__ __attribute__((aligned(16))) Stage stage0, stage1;
+__global__ void __launch_bounds__(512, 1) proj_gemm_kernel(GemmArgs g) {
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2][8][kTileBytes];  // [buffer][A0..A3, B0..B3]
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 2, wn = wave & 3;
   const int col = lane & 31, half = lane >> 5;
   const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x);
-  const int64_t m0 = (int64_t)(wg / g.ntiles) * 128, n0 = (int64_t)(wg % g.ntiles) * 128;
+  const int64_t m0 = (int64_t)(wg / g.ntiles) * kGemmBM, n0 = (int64_t)(wg % g.ntiles) * kGemmBN;
   const int64_t mt_last = g.M / 64 - 1, nt_last = g.N / 64 - 1;
   const int64_t ks_begin = (int64_t)blockIdx.y * g.kslabs;
   int64_t ks_end = ks_begin + g.kslabs;
   if (ks_end > g.K / 64) ks_end = g.K / 64;
 
   const TileLanes tl(lane);
-  const TileDMA dma(wave, lane);
-  auto load_stage = [&](int64_t ks, Stage &s) __attribute__((always_inline)) {
+  const ViewWalk wa(g.A, A_KROWS), wb(g.B, B_KROWS);
+  // (a ragged edge refetches the last tile; its outputs are never stored)
+  auto mt_of = [&](int t) { const int64_t mt = m0 / 64 + t; return mt > mt_last ? mt_last : mt; };
+  auto nt_of = [&](int t) { const int64_t nt = n0 / 64 + t; return nt > nt_last ? nt_last : nt; };
+  TileCursor ca[4] = {TileCursor(g.A, A_KROWS, mt_of(0), ks_begin), TileCursor(g.A, A_KROWS, mt_of(1), ks_begin),
+                      TileCursor(g.A, A_KROWS, mt_of(2), ks_begin), TileCursor(g.A, A_KROWS, mt_of(3), ks_begin)};
+  TileCursor cb[4] = {TileCursor(g.B, B_KROWS, nt_of(0), ks_begin), TileCursor(g.B, B_KROWS, nt_of(1), ks_begin),
+                      TileCursor(g.B, B_KROWS, nt_of(2), ks_begin), TileCursor(g.B, B_KROWS, nt_of(3), ks_begin)};
+  // this thread's 16-byte piece of every tile: row tid / 8, logical chunk tid % 8
+  const int prow = tid >> 3, pcc = tid & 7;
+  const int64_t ga_off = prow * wa.ld + pcc * 8, gb_off = prow * wb.ld + pcc * 8;
+  const int l_off = tile_off(prow, pcc);
+  u32x4 stg[8];
+  auto fetch = [&]() __attribute__((always_inline)) {  // the slab the cursors point at, then move them on
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      int64_t mt = m0 / 64 + t, nt = n0 / 64 + t, ld;
-      if (mt > mt_last) mt = mt_last;  // ragged edge: refetch the last tile (never stored)
-      if (nt > nt_last) nt = nt_last;
-      const uint16_t *pa = A_KROWS ? g.A.tile(ks, mt, ld) : g.A.tile(mt, ks, ld);
-      dma.load(pa, s.a[t], ld);
-      const uint16_t *pb = B_KROWS ? g.B.tile(ks, nt, ld) : g.B.tile(nt, ks, ld);
-      dma.load(pb, s.b[t], ld);
-    }
+    for (int t = 0; t < 4; ++t) stg[t] = *reinterpret_cast<const u32x4 *>(ca[t].ptr + ga_off);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) stg[4 + t] = *reinterpret_cast<const u32x4 *>(cb[t].ptr + gb_off);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) { ca[t].advance(wa); cb[t].advance(wb); }
+  };
+  auto put = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) *reinterpret_cast<u32x4 *>(lds[buf][t] + l_off) = stg[t];
   };
 
-  f32x16 acc[2][2];  // [nb][mb]: rows n, columns m
+  f32x16 acc[2][4];  // [nb][mb]: rows n, columns m
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[nb][mb][v] = 0.f;
 
-  int64_t ks = ks_begin;
-  if (ks < ks_end) load_stage(ks, stage0);
-  wait_vmem();
+  int buf = 0;
+  if (ks_begin < ks_end) {  // uniform over the work-group
+    fetch();
+    put(0);
+  }
   __syncthreads();
-  auto stage = [&](Stage &sc, Stage &sn) __attribute__((always_inline)) {
-    if (ks + 1 < ks_end) load_stage(ks + 1, sn);
+  for (int64_t ks = ks_begin; ks < ks_end; ++ks) {
+    const bool more = ks + 1 < ks_end;
+    if (more) fetch();
+    const unsigned char(*sc)[kTileBytes] = lds[buf];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 af[2], bf[2];
+      bf16x8 af[4], bf[2];
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
-        af[mb] = A_KROWS ? tl.read_cols(sc.a[wm], kk * 16, mb)
-                         : (B_KROWS ? tl.read_rows_perm(sc.a[wm], mb * 32, kk)
-                                    : tl.read_rows(sc.a[wm], mb * 32, kk));
+      for (int mb = 0; mb < 4; ++mb) {
+        const unsigned char *ta = sc[wm * 2 + (mb >> 1)];
+        af[mb] = A_KROWS ? tl.read_cols(ta, kk * 16, mb & 1)
+                         : (B_KROWS ? tl.read_rows_perm(ta, (mb & 1) * 32, kk) : tl.read_rows(ta, (mb & 1) * 32, kk));
+      }
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        const unsigned char *tb = sc[4 + wn];
+        bf[nb] = B_KROWS ? tl.read_cols(tb, kk * 16, nb)
+                         : (A_KROWS ? tl.read_rows_perm(tb, nb * 32, kk) : tl.read_rows(tb, nb * 32, kk));
+      }
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb)
-        bf[nb] = B_KROWS ? tl.read_cols(sc.b[wn], kk * 16, nb)
-                         : (A_KROWS ? tl.read_rows_perm(sc.b[wn], nb * 32, kk)
-                                    : tl.read_rows(sc.b[wn], nb * 32, kk));
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb) acc[nb][mb] = mfma_32x32x16(bf[nb], af[mb], acc[nb][mb]);
+        for (int mb = 0; mb < 4; ++mb) acc[nb][mb] = mfma_32x32x16(bf[nb], af[mb], acc[nb][mb]);
     }
-    wait_vmem();
+    if (more) put(buf ^ 1);  // last read one slab ago, before the barrier that ended it
     __syncthreads();
-    ++ks;
-  };
-  while (ks < ks_end) {
-    stage(stage0, stage1);
-    if (ks >= ks_end) break;
-    stage(stage1, stage0);
+    buf ^= 1;
   }
 
   // lane (col, half) holds, for output row m, the columns n = nb*32 + grp*8 + half*4 .. +4
   if (!OUT_F32) {
-    // bf16: the wave's 64 x 64 block goes through its own LDS tile (every wave is past the last
-    // barrier of the loop, so the stage buffers are free) and leaves as 16-byte pieces, eight
-    // lanes per 128-byte row segment, instead of 8-byte pieces 128 bytes or more apart.
-    unsigned char *t = wave < 2 ? stage0.a[wave] : stage0.b[wave - 2];
+    // bf16: the wave's 128 x 64 block goes through two LDS tiles of its own (every wave is past
+    // the loop's last barrier) and leaves as whole 128-byte row segments.
+    unsigned char *t0 = lds[0][wave], *t1 = lds[1][wave];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-        for (int grp = 0; grp < 4; ++grp) {
-          const f32x16 &c = acc[nb][mb];
-          const u32x2 w = {pack_bf16(c[grp * 4 + 0], c[grp * 4 + 1]), pack_bf16(c[grp * 4 + 2], c[grp * 4 + 3])};
-          *reinterpret_cast<u32x2 *>(t + tile_off(mb * 32 + col, nb * 4 + grp) + half * 8) = w;
-        }
+    for (int mb = 0; mb < 4; ++mb) stage_block_T(mb < 2 ? t0 : t1, (mb & 1) * 32, acc[0][mb], acc[1][mb], 1.0f, lane);
     const int64_t nw = n0 + wn * 64;  // the block's 64 columns: one head of a head-split output
     if (nw < g.N) {
       int which = 0;
       int64_t zoff = 0;
       if (g.out_split) {
-        const int64_t hb = nw / 64;
-        which = (int)(hb / g.out_Z);
-        zoff = hb % g.out_Z;
+        const uint32_t hb = (uint32_t)(nw / 64);
+        which = (int)(hb / (uint32_t)g.out_Z);
+        zoff = hb % (uint32_t)g.out_Z;
       }
       uint16_t *base = static_cast<uint16_t *>(which == 0 ? g.out[0] : (which == 1 ? g.out[1] : g.out[2]));
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int row = it * 8 + (lane >> 3), cc = lane & 7;
-        const int64_t m = m0 + wm * 64 + row;
+      for (int it = 0; it < 16; ++it) {
+        const int row = it * 8 + (lane >> 3), cc = lane & 7;  // row of the wave's 128
+        const int64_t m = m0 + wm * 128 + row;
         if (m >= g.M) continue;
-        const u32x4 w = *reinterpret_cast<const u32x4 *>(t + tile_off(row, cc));
+        const u32x4 w = *reinterpret_cast<const u32x4 *>((row < 64 ? t0 : t1) + tile_off(row & 63, cc));
         int64_t off;
         if (!g.out_split) {
           off = m * g.out_ld + nw + cc * 8;
         } else {
-          const int64_t b = m / g.out_rows, r = m % g.out_rows;
-          off = ((b * g.out_Z + zoff) * g.out_rows + r) * 64 + cc * 8;
+          const uint32_t b = (uint32_t)m / (uint32_t)g.out_rows, r = (uint32_t)m % (uint32_t)g.out_rows;
+          off = (((int64_t)b * g.out_Z + zoff) * g.out_rows + r) * 64 + cc * 8;
         }
         *reinterpret_cast<u32x4 *>(base + off) = w;
       }
@@ -165,8 +247,8 @@ __global__ void __launch_bounds__(256, 2) proj_gemm_kernel(GemmArgs g) {
     return;
   }
 #pragma unroll
-  for (int mb = 0; mb < 2; ++mb) {
-    const int64_t m = m0 + wm * 64 + mb * 32 + col;
+  for (int mb = 0; mb < 4; ++mb) {
+    const int64_t m = m0 + wm * 128 + mb * 32 + col;
     if (m >= g.M) continue;
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
@@ -206,18 +288,18 @@ static MatView heads(const void *p0, const void *p1, const void *p2, int64_t row
 
 template <bool A_KROWS, bool B_KROWS, bool OUT_F32>
 static hipError_t launch_gemm(GemmArgs &g, int splits, hipStream_t st) {
-  g.ntiles = (int)((g.N + 127) / 128);
-  const int64_t mtiles = (g.M + 127) / 128;
+  g.ntiles = (int)((g.N + kGemmBN - 1) / kGemmBN);
+  const int64_t mtiles = (g.M + kGemmBM - 1) / kGemmBM;
   g.kslabs = (g.K / 64 + splits - 1) / splits;
   dim3 grid((unsigned)(mtiles * g.ntiles), (unsigned)splits);
-  hipLaunchKernelGGL((proj_gemm_kernel<A_KROWS, B_KROWS, OUT_F32>), grid, dim3(256), 0, st, g);
+  hipLaunchKernelGGL((proj_gemm_kernel<A_KROWS, B_KROWS, OUT_F32>), grid, dim3(512), 0, st, g);
   return hipGetLastError();
 }
 
 // k splits of a weight-gradient product: enough work-groups to fill the chip twice
 int proj_wgrad_splits(int64_t Mout, int64_t Nout, int64_t K) {
-  const int64_t tiles = ((Mout + 127) / 128) * ((Nout + 127) / 128);
-  int64_t s = (1024 + tiles - 1) / tiles;
+  const int64_t tiles = ((Mout + kGemmBM - 1) / kGemmBM) * ((Nout + kGemmBN - 1) / kGemmBN);
+  int64_t s = (512 + tiles - 1) / tiles;
   const int64_t slabs = K / 64;
   if (s > slabs / 4) s = slabs / 4;
   if (s < 1) s = 1;
