@@ -339,6 +339,8 @@ int proj_check(const rsa_desc *d, int32_t H, Dims *dm) {
   if (dm->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16) return RSA_ERR_UNSUPPORTED;
   if (H < 64) return RSA_ERR_SHAPE;
   if (H % 64 != 0) return RSA_ERR_UNSUPPORTED;
+  // the GEMM kernel indexes rows and columns of its operands with 32 bits
+  if ((int64_t)dm->B * dm->Lq >= (1LL << 31)) return RSA_ERR_UNSUPPORTED;
   return RSA_OK;
 }
 size_t proj_ws(const Dims &dm, int64_t H) {
@@ -402,6 +404,8 @@ int linformer_dims(const rsa_desc *d, int32_t Kp, Dims *own, Dims *att) {
     return RSA_ERR_UNSUPPORTED;
   if (Kp < 64) return RSA_ERR_SHAPE;
   if (Kp % 64 != 0) return RSA_ERR_UNSUPPORTED;
+  // the GEMM kernel indexes rows and columns of its operands with 32 bits
+  if (own->L >= (1LL << 31) || (int64_t)own->B * own->Z * 64 >= (1LL << 31)) return RSA_ERR_UNSUPPORTED;
   *att = *own;
   att->N = 1; att->rank_begin = 0; att->rank_end = 1;
   att->L = Kp; att->c = Kp;  // Lq stays: the ranks' rows
