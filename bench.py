@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0
 # rocprofv3 --pmc runs (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same
 # counter reads for a 1 GiB device copy (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); the
 # summary is profiles/rsa_fused_bert_large_hbm_traffic.txt.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"bert_large": 204.9e6}
+MEASURED_TRAFFIC_BYTES = {"bert_large": 204.8e6}
 
 
 def parse():
@@ -41,7 +41,10 @@ def parse():
                              "causal_ring_32k", "zigzag_rank0_64k_causal"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true", help="(default) also time the other workloads briefly")
-    ap.add_argument("--only", action="store_true", help="time the chosen workload only")
+    ap.add_argument("--only", action="store_true", help="time the chosen workload only (no extra legs)")
+    ap.add_argument("--legs", default="others,projections,linformer",
+                    help="extra legs after the timed region: the other workloads, the projections around RSA, "
+                         "the Linformer variant (comma-separated subset)")
     ap.add_argument("--staged", action="store_true",
                     help="also time the staged (two-pass) kernels of one rank: HBM GB/s of the score strip")
     ap.add_argument("--profile-copy", type=int, default=0, metavar="BYTES",
@@ -296,7 +299,8 @@ def main():
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name)},
     }
-    if not a.only:
+    legs = set() if a.only else set(a.legs.split(","))
+    if "others" in legs:
         other = {}
         for name in ("bert_base", "bert_large", "long_32k", "rank15_64k_causal", "causal_ring_32k",
                      "zigzag_rank0_64k_causal"):
@@ -309,7 +313,9 @@ def main():
             other[name] = {"tflops": round(r2["tflops"], 2), "ms_per_step": round(r2["ms_per_step"], 4),
                            "kernel_ms": {n: round(v, 4) for n, v in r2["kernel_ms"].items()}}
         out["other_workloads"] = other
+    if "projections" in legs:
         out["projections"] = projections_report(cfg, torch, rsa)
+    if "linformer" in legs:
         out["linformer_114k"] = linformer_report(torch, rsa)
     if a.staged:
         out["staged"] = staged_report(cfg, torch, rsa, inputs)
