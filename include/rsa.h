@@ -147,8 +147,10 @@ int rsa_store(const rsa_desc *d, const float *src, void *dst, size_t count,
 
 /*
  * The kernels of the fused backward on their own (bf16, fused mode), for
- * profiling and tests; rsa_backward = these three in this order, on one
- * workspace `ws` of rsa_workspace_bytes(d, 1) bytes.
+ * profiling and tests, on one workspace `ws` of rsa_workspace_bytes(d, 1)
+ * bytes.  rsa_backward runs the dQ kernel first, with the preprocess folded
+ * into its prologue, then the dK/dV kernel; the three calls below in the order
+ * given produce the same gradients up to the fp32 summation order of D.
  *  rsa_bwd_preprocess: fills ws with the row terms -D_i = -sum_a dO_ia O_ia and
  *    -LSE_i log2(e) (fp32) and with Qs, a bf16 copy of Q multiplied by
  *    s * log2(e), the operand from which both other kernels recompute

@@ -2,7 +2,8 @@
 // with the ring structure of section 3.2.2, without the score strip in memory.
 // P is recomputed from Q, K and the forward's LSE: P = exp(s QK^T - LSE).
 //
-//   preprocess: the row terms -D = -rowsum(dO o O) and -LSE log2e, and Qs = bf16(Q * s * log2 e).
+//   preprocess: the row terms -D = -rowsum(dO o O) and -LSE log2e, and Qs = bf16(Q * s * log2 e);
+//     a kernel of its own for the step-level entry point, the prologue of the dQ kernel in rsa_backward.
 //   dkdv kernel: a work-group owns 4*32 keys and walks the query tiles of every
 //     simulated rank, starting with the rank that holds those keys (ring
 //     order); the sum over ranks that the ring would all-reduce is its loop.
@@ -21,6 +22,12 @@ namespace rsa {
 struct BwdArgs {
   const uint16_t *Q, *Qs, *K, *V, *dO;  // Qs = bf16(Q * scale * log2 e)
   const float *nL, *nD;                 // -LSE log2e and -D per query row
+  // dQ kernel with the preprocess folded in: it forms the row terms and Qs from O and LSE
+  // itself and leaves them in nL_out, nD_out, Qs_out for the dK/dV kernel that follows
+  const uint16_t *O;
+  const float *LSE;
+  float *nL_out, *nD_out;
+  uint16_t *Qs_out;
   uint16_t *dQ, *dK, *dV;
   float *part;  // dK/dV kernel with a split query walk: fp32 partial dV, then dK, per split
   int64_t L, c, Lq;
@@ -317,7 +324,7 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
 }
 
 // ---------------------------------------------------------------------- dQ ---
-template <int R, bool CAUSAL>
+template <int R, bool CAUSAL, bool PRE>
 __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdArgs a) {
   constexpr int QB = R / 32;
   constexpr int BM = 4 * R;
@@ -371,8 +378,35 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
           *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * 64 + dk * 16 + half * 8), a.cl2);
       greg[qb][dk] = *reinterpret_cast<const bf16x8 *>(dOh + qrow[qb] * 64 + dk * 16 + half * 8);
     }
-    const float l2 = a.nL[head * a.Lq + qrow[qb]];
-    const float dd = a.nD[head * a.Lq + qrow[qb]];
+    float l2, dd;
+    if (PRE) {
+      // D = sum_a dO_a O_a: this lane holds 32 of the row's 64 elements, the lane 32 away the rest
+      float acc = 0.f;
+#pragma unroll
+      for (int dk = 0; dk < 4; ++dk) {
+        const u32x4 x = __builtin_bit_cast(u32x4, greg[qb][dk]);
+        const u32x4 y = *reinterpret_cast<const u32x4 *>(a.O + (head * a.Lq + qrow[qb]) * 64 + dk * 16 + half * 8);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc = fmaf(bf16_to_f32(x[e] & 0xffffu), bf16_to_f32(y[e] & 0xffffu), acc);
+          acc = fmaf(bf16_to_f32(x[e] >> 16), bf16_to_f32(y[e] >> 16), acc);
+        }
+      }
+      dd = -xhalf_sum(acc);
+      l2 = -a.LSE[head * a.Lq + qrow[qb]] * kLog2e;
+      if (r < a.Lq) {
+        if (half == 0) {
+          a.nD_out[head * a.Lq + r] = dd;
+          a.nL_out[head * a.Lq + r] = l2;
+        }
+#pragma unroll
+        for (int dk = 0; dk < 4; ++dk)
+          *reinterpret_cast<bf16x8 *>(a.Qs_out + (head * a.Lq + r) * 64 + dk * 16 + half * 8) = qreg[qb][dk];
+      }
+    } else {
+      l2 = a.nL[head * a.Lq + qrow[qb]];
+      dd = a.nD[head * a.Lq + qrow[qb]];
+    }
 #pragma unroll
     for (int v = 0; v < 16; ++v) { negl[qb][v] = l2; negd[qb][v] = dd; }
   }
@@ -520,6 +554,7 @@ static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const
   a.dO = (const uint16_t *)dO; a.nL = nL; a.nD = nD;
   a.dQ = (uint16_t *)dQ; a.dK = (uint16_t *)dK; a.dV = (uint16_t *)dV;
   a.part = nullptr;
+  a.O = nullptr; a.LSE = nullptr; a.nL_out = nullptr; a.nD_out = nullptr; a.Qs_out = nullptr;
   a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.map = make_row_map(d);
   a.N = d.N; a.cl2 = d.scale * kLog2e; a.scale = d.scale;
   a.tiles_per_head = 0;
@@ -572,9 +607,24 @@ hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void
   a.tiles_per_head = (int)((d.Lq + 127) / 128);
   dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head));
   if (d.causal)
-    hipLaunchKernelGGL((fused_bwd_dq_kernel<32, true>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((fused_bwd_dq_kernel<32, true, false>), grid, dim3(256), 0, st, a);
   else
-    hipLaunchKernelGGL((fused_bwd_dq_kernel<32, false>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((fused_bwd_dq_kernel<32, false, false>), grid, dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
+// The dQ kernel with the preprocess in its prologue: also writes -D, -LSE log2e and Qs.
+hipError_t fused_bwd_dq_pre(const Dims &d, const void *dO, const void *Q, const void *K, const void *V,
+                            const void *O, const float *LSE, float *nL, float *nD, void *Qs, void *dQ,
+                            hipStream_t st) {
+  BwdArgs a = make_bwd_args(d, dO, Q, nullptr, K, V, nullptr, nullptr, dQ, nullptr, nullptr);
+  a.O = (const uint16_t *)O; a.LSE = LSE; a.nL_out = nL; a.nD_out = nD; a.Qs_out = (uint16_t *)Qs;
+  a.tiles_per_head = (int)((d.Lq + 127) / 128);
+  dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head));
+  if (d.causal)
+    hipLaunchKernelGGL((fused_bwd_dq_kernel<32, true, true>), grid, dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL((fused_bwd_dq_kernel<32, false, true>), grid, dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
@@ -582,11 +632,10 @@ hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const vo
                           const void *V, const void *O, const float *LSE, void *dQ, void *dK,
                           void *dV, float *nD, float *nL, void *Qs, hipStream_t st, float *part,
                           int splits) {
-  hipError_t e = fused_bwd_preprocess(d, dO, O, Q, LSE, nD, nL, Qs, st);
+  // the dQ kernel first: its prologue forms the row terms and Qs that the dK/dV kernel reads
+  hipError_t e = fused_bwd_dq_pre(d, dO, Q, K, V, O, LSE, nL, nD, Qs, dQ, st);
   if (e != hipSuccess) return e;
-  e = fused_bwd_dkdv(d, dO, Qs, K, V, nL, nD, dK, dV, st, part, splits);
-  if (e != hipSuccess) return e;
-  return fused_bwd_dq(d, dO, Q, K, V, nL, nD, dQ, st);
+  return fused_bwd_dkdv(d, dO, Qs, K, V, nL, nD, dK, dV, st, part, splits);
 }
 
 }  // namespace rsa

@@ -177,7 +177,9 @@ def test_outputs_do_not_depend_on_buffer_contents():
 
 
 def test_backward_parts_equal_the_whole():
-    """rsa_backward = rsa_bwd_preprocess + rsa_bwd_dkdv + rsa_bwd_dq, bit for bit."""
+    """rsa_bwd_preprocess + rsa_bwd_dkdv + rsa_bwd_dq against rsa_backward, which folds the
+    preprocess into the dQ kernel: the same gradients up to the fp32 summation order of D
+    (a last-bit difference in D moves an occasional bf16 output by one ulp)."""
     cfg = cfg_of(1, 3, 512, 4, causal=True, seed=37)
     x = inputs.make_inputs(cfg)
     Q, K, V, dO = (upload(x[k], "bf16") for k in ("Q", "K", "V", "dO"))
@@ -190,7 +192,12 @@ def test_backward_parts_equal_the_whole():
     rsa.bwd_dkdv(desc, dO, K, V, ws, dK2, dV2)
     rsa.bwd_dq(desc, dO, Q, K, V, ws, dQ2)
     torch.cuda.synchronize()
-    assert torch.equal(dQ, dQ2) and torch.equal(dK, dK2) and torch.equal(dV, dV2)
+    for name, a, b in (("dQ", dQ, dQ2), ("dK", dK, dK2), ("dV", dV, dV2)):
+        a, b = download(a), download(b)
+        rms = np.sqrt(np.mean(a * a))
+        assert np.abs(a - b).max() <= 2.0 ** -7 * np.abs(a).max() + 1e-30, name   # within one bf16 ulp
+        assert np.sqrt(np.mean((a - b) ** 2)) <= 1e-3 * rms, name
+    compare_heads(cfg, x, dict(O=O, LSE=LSE, dQ=dQ2, dK=dK2, dV=dV2), [0, 1, 2])
 
 
 def test_error_codes_on_the_device_path():
