@@ -25,6 +25,16 @@ from paper_2105_13120_amd import inputs, rsa
 #  on the first rows of a causal mask, where a row has few keys (the ideal
 #  pipeline reaches 1.2e-2 of such an element).  The RMS criterion keeps the whole
 #  tensor tight (the ideal pipeline sits at 2.4e-3 to 3.5e-3).
+#  dQ carries one more term.  Every bf16 backward forms D_i = sum_a dO_ia O_ia from the
+#  *stored* O, whose rounding (|dO_ia| 2^-9 |O_ia| per term, independent signs) leaves an error
+#  delta_i in D_i with standard deviation 2^-9 / sqrt(3) * sqrt(sum_a dO_ia^2 O_ia^2).  It enters
+#  dS_ij = P_ij (dP_ij - D_i) for every key of the row with the same sign, so
+#  dQ_i = s sum_j dS_ij K_j moves by s * delta_i * (sum_j P_ij K_j): the row's attention-weighted
+#  mean key.  For rows that see many keys O_i is small and the term vanishes; on the first rows
+#  of a causal mask (one or two keys, O_i of the size of a value vector) it is the largest error
+#  in the tensor: the ideal pipeline of tests/test_tolerance_model.py is 1.34 times the bound
+#  above on such an element.  The dQ bound is therefore widened by four standard deviations of
+#  that term, computed from the oracle's own O and P (dq_extra below).
 F32_ATOL = 1e-4
 BF16_REL_RMS = 2e-2
 BF16_RTOL = 2.0 ** -6
@@ -56,9 +66,18 @@ def rel_rms_err(got, ref):
     return float(np.abs(got - ref).max()) / max(rms, 1e-30)
 
 
-def check(name, got, ref, dtype):
+def dq_extra(Q, K, V, dO, O_ref, q0, causal, scale=None):
+    """The allowance for the rounding of the stored O inside D (see the comment on top):
+    4 * 2^-9 / sqrt(3) * sqrt(sum_a dO^2 O^2) * s * |sum_j P_ij K_j|, per element of dQ."""
+    s = 1.0 / np.sqrt(Q.shape[-1]) if scale is None else scale
+    PK, _ = oracle.forward(Q, K, K, q0=q0, causal=causal, scale=scale)   # attention-weighted mean key
+    sigma = 2.0 ** -9 / np.sqrt(3.0) * np.sqrt(np.sum(np.square(dO * O_ref), axis=-1, keepdims=True))
+    return 4.0 * sigma * s * np.abs(PK)
+
+
+def check(name, got, ref, dtype, extra=None):
     """Assert the tolerance for one output tensor; returns max abs err (f32) or
-    max abs err / rms (bf16)."""
+    max abs err / rms (bf16).  extra: per-element addition to the bf16 bound."""
     assert got.shape == ref.shape, (name, got.shape, ref.shape)
     assert np.isfinite(got).all(), f"{name}: non-finite values"
     diff = np.abs(got - ref)
@@ -68,6 +87,8 @@ def check(name, got, ref, dtype):
         return err
     rms = max(float(np.sqrt(np.mean(np.square(ref)))), 1e-30)
     bound = BF16_REL_RMS * rms + BF16_RTOL * np.abs(ref).max(axis=-1, keepdims=True)
+    if extra is not None:
+        bound = bound + extra
     worst = float((diff / bound).max())
     assert worst <= 1.0, (f"{name}: error is {worst:.3f} of the bound "
                           f"(max abs err / rms = {diff.max() / rms:.3e})")
@@ -99,24 +120,26 @@ def oracle_on_segments(cfg, Qh, Kh, Vh, dOh=None):
     O = np.empty_like(Qh)
     LSE = np.empty(Qh.shape[:3])
     dQ = np.empty_like(Qh) if dOh is not None else None
+    extra = np.empty_like(Qh) if dOh is not None else None
     dK = dV = None
     for r0, t0, n in cfg.segments():
         Qs = np.ascontiguousarray(Qh[:, :, r0:r0 + n])
         O[:, :, r0:r0 + n], LSE[:, :, r0:r0 + n] = oracle.forward(Qs, Kh, Vh, q0=t0, causal=cfg.causal)
         if dOh is not None:
-            g = oracle.backward(Qs, Kh, Vh, np.ascontiguousarray(dOh[:, :, r0:r0 + n]), q0=t0,
-                                causal=cfg.causal)
+            dOs = np.ascontiguousarray(dOh[:, :, r0:r0 + n])
+            g = oracle.backward(Qs, Kh, Vh, dOs, q0=t0, causal=cfg.causal)
             dQ[:, :, r0:r0 + n] = g[0]
             dK = g[1] if dK is None else dK + g[1]
             dV = g[2] if dV is None else dV + g[2]
-    return O, LSE, dQ, dK, dV
+            extra[:, :, r0:r0 + n] = dq_extra(Qs, Kh, Vh, dOs, O[:, :, r0:r0 + n], t0, cfg.causal)
+    return O, LSE, dQ, dK, dV, extra
 
 
 def compare_heads(cfg, x, out, heads, backward=True):
     """Full comparison with the oracle on the listed flat head indices."""
     Qh, Kh, Vh = (heads_view(x[k], heads) for k in ("Q", "K", "V"))
     dOh = heads_view(x["dO"], heads) if backward else None
-    O_ref, LSE_ref, dQ_ref, dK_ref, dV_ref = oracle_on_segments(cfg, Qh, Kh, Vh, dOh)
+    O_ref, LSE_ref, dQ_ref, dK_ref, dV_ref, dq_x = oracle_on_segments(cfg, Qh, Kh, Vh, dOh)
     errs = {}
     errs["O"] = check("O", heads_view(download(out["O"]), heads), O_ref, cfg.dtype)
     lse = download(out["LSE"]).reshape(-1, cfg.Lq)[heads][None]
@@ -125,5 +148,6 @@ def compare_heads(cfg, x, out, heads, backward=True):
     errs["LSE"] = err
     if backward:
         for name, ref in (("dQ", dQ_ref), ("dK", dK_ref), ("dV", dV_ref)):
-            errs[name] = check(name, heads_view(download(out[name]), heads), ref, cfg.dtype)
+            errs[name] = check(name, heads_view(download(out[name]), heads), ref, cfg.dtype,
+                               extra=dq_x if name == "dQ" and cfg.dtype == "bf16" else None)
     return errs

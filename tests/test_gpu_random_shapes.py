@@ -1,0 +1,34 @@
+"""Seeded random shapes through the fused path: ring sizes, rank sub-ranges, masks and ownerships
+drawn at random, every head compared with the oracle.  Catches what the hand-picked cases miss."""
+import numpy as np
+import pytest
+
+from helpers import compare_heads, gpu_forward_backward
+from paper_2105_13120_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def draw_case(rng):
+    N = int(rng.choice([1, 2, 3, 4, 5, 6, 8]))
+    zigzag = bool(rng.integers(0, 2))
+    unit = 128 if zigzag else 64
+    c = unit * int(rng.integers(1, 5))
+    rb = int(rng.integers(0, N))
+    re = int(rng.integers(rb + 1, N + 1))
+    return dict(B=int(rng.integers(1, 3)), Z=int(rng.integers(1, 4)), L=N * c, N=N, rb=rb, re=re,
+                causal=bool(rng.integers(0, 2)), zigzag=zigzag, seed=int(rng.integers(0, 1 << 30)))
+
+
+CASES = [draw_case(np.random.Generator(np.random.PCG64(1000 + i))) for i in range(24)]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "B{B}Z{Z}L{L}N{N}r{rb}-{re}{c}{z}".format(
+    c="c" if c["causal"] else "", z="z" if c["zigzag"] else "", **c))
+def test_random_shape(case):
+    cfg = inputs.RSAConfig("r", B=case["B"], Z=case["Z"], L=case["L"], A=64, N=case["N"], dtype="bf16",
+                           causal=case["causal"], rank_begin=case["rb"], rank_end=case["re"],
+                           seed=case["seed"], zigzag=case["zigzag"])
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x)
+    compare_heads(cfg, x, out, list(range(cfg.B * cfg.Z)))
