@@ -155,11 +155,14 @@ __global__ void __launch_bounds__(512, 1) proj_gemm_kernel(GemmArgs g) {
   const int64_t ga_off = prow * wa.ld + pcc * 8, gb_off = prow * wb.ld + pcc * 8;
   const int l_off = tile_off(prow, pcc);
   u32x4 stg[8];
+  // (loads through global-address-space pointers: a flat load would also count as an LDS
+  // operation and every wait for an LDS read would then wait for the slab in flight)
+  typedef __attribute__((address_space(1))) const u32x4 *gvec_t;
   auto fetch = [&]() __attribute__((always_inline)) {  // the slab the cursors point at, then move them on
 #pragma unroll
-    for (int t = 0; t < 4; ++t) stg[t] = *reinterpret_cast<const u32x4 *>(ca[t].ptr + ga_off);
+    for (int t = 0; t < 4; ++t) stg[t] = *(gvec_t)(ca[t].ptr + ga_off);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) stg[4 + t] = *reinterpret_cast<const u32x4 *>(cb[t].ptr + gb_off);
+    for (int t = 0; t < 4; ++t) stg[4 + t] = *(gvec_t)(cb[t].ptr + gb_off);
 #pragma unroll
     for (int t = 0; t < 4; ++t) { ca[t].advance(wa); cb[t].advance(wb); }
   };
@@ -186,25 +189,32 @@ __global__ void __launch_bounds__(512, 1) proj_gemm_kernel(GemmArgs g) {
     const bool more = ks + 1 < ks_end;
     if (more) fetch();
     const unsigned char(*sc)[kTileBytes] = lds[buf];
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 af[4], bf[2];
+    // the fragments of k-slice kk + 1 are read while the MFMAs of slice kk run
+    bf16x8 af[2][4], bf[2][2];
+    auto frags = [&](int kk, bf16x8(&a4)[4], bf16x8(&b2)[2]) __attribute__((always_inline)) {
 #pragma unroll
       for (int mb = 0; mb < 4; ++mb) {
         const unsigned char *ta = sc[wm * 2 + (mb >> 1)];
-        af[mb] = A_KROWS ? tl.read_cols(ta, kk * 16, mb & 1)
+        a4[mb] = A_KROWS ? tl.read_cols(ta, kk * 16, mb & 1)
                          : (B_KROWS ? tl.read_rows_perm(ta, (mb & 1) * 32, kk) : tl.read_rows(ta, (mb & 1) * 32, kk));
       }
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
         const unsigned char *tb = sc[4 + wn];
-        bf[nb] = B_KROWS ? tl.read_cols(tb, kk * 16, nb)
+        b2[nb] = B_KROWS ? tl.read_cols(tb, kk * 16, nb)
                          : (A_KROWS ? tl.read_rows_perm(tb, nb * 32, kk) : tl.read_rows(tb, nb * 32, kk));
       }
+    };
+    frags(0, af[0], bf[0]);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      if (kk < 3) frags(kk + 1, af[(kk + 1) & 1], bf[(kk + 1) & 1]);
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb) acc[nb][mb] = mfma_32x32x16(bf[nb], af[mb], acc[nb][mb]);
+        for (int mb = 0; mb < 4; ++mb)
+          acc[nb][mb] = mfma_32x32x16(bf[kk & 1][nb], af[kk & 1][mb], acc[nb][mb]);
+      __builtin_amdgcn_sched_barrier(0);  // keep the slices in this order
     }
     if (more) put(buf ^ 1);  // last read one slab ago, before the barrier that ended it
     __syncthreads();
