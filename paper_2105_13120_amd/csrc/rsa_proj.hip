@@ -96,6 +96,7 @@ struct TileCursor {
   __device__ __forceinline__ void advance(const ViewWalk &w) {
     ptr += w.step;
     if (++cnt == w.period) {
+      asm volatile("" ::: "memory");  // a real (rarely taken, uniform) branch instead of a chain of selects per slab
       cnt = 0;
       if (w.mode == 1) ptr += w.jump1;
       if (w.mode == 2) { ptr += which == 0 ? w.jump1 : w.jump2; ++which; }
