@@ -307,10 +307,74 @@ __global__ void __launch_bounds__(256) row_softmax_kernel(const float *S, OutT *
   }
 }
 
+// The same for rows of L = 256 NV scores with NV <= 16: the row stays in the wave's registers
+// (4 NV values per lane), so it is read from memory once, all its loads are in flight together,
+// and the maximum is exact before the first exponential.
+template <typename OutT, int NV>
+__global__ void __launch_bounds__(256) row_softmax_reg_kernel(const float *S, OutT *P, float *LSE,
+                                                              int64_t rows, int64_t c, int64_t Lq,
+                                                              int64_t row_off) {
+  constexpr int64_t L = 256 * NV;
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const float *s = S + row * L;
+  f32x4 x[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) x[v] = *reinterpret_cast<const f32x4 *>(s + v * 256 + lane * 4);
+  float m = -INFINITY;
+#pragma unroll
+  for (int v = 0; v < NV; ++v) m = fmaxf(m, fmaxf(fmaxf(x[v][0], x[v][1]), fmaxf(x[v][2], x[v][3])));
+  const float M = wave_max(m);  // finite: every row has at least one unmasked score
+  const float mc = M * kLog2e;
+  float l = 0.f;
+#pragma unroll
+  for (int v = 0; v < NV; ++v)
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      x[v][k] = exp2f(fmaf(x[v][k], kLog2e, -mc));
+      l += x[v][k];
+    }
+  const float lsum = wave_sum(l);
+  const float inv = 1.0f / lsum;
+  OutT *p = P + row * L;
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    if constexpr (sizeof(OutT) == 2) {
+      u32x2 o = {pack_bf16(x[v][0] * inv, x[v][1] * inv), pack_bf16(x[v][2] * inv, x[v][3] * inv)};
+      *reinterpret_cast<u32x2 *>(p + v * 256 + lane * 4) = o;
+    } else {
+      *reinterpret_cast<f32x4 *>(p + v * 256 + lane * 4) = x[v] * inv;
+    }
+  }
+  if (lane == 0) {
+    const int64_t head = row / c, r = row % c;
+    LSE[head * Lq + row_off + r] = M + logf(lsum);
+  }
+}
+
+template <typename OutT>
+static bool launch_row_softmax_reg(const float *S, OutT *P, float *LSE, int64_t rows, int64_t L, int64_t c,
+                                   int64_t Lq, int64_t row_off, hipStream_t st) {
+  dim3 grid((unsigned)((rows + 3) / 4));
+#define RSA_ROWSM(NV)                                                                              \
+  if (L == 256 * NV) {                                                                             \
+    hipLaunchKernelGGL((row_softmax_reg_kernel<OutT, NV>), grid, dim3(256), 0, st, S, P, LSE, rows, \
+                       c, Lq, row_off);                                                            \
+    return true;                                                                                   \
+  }
+  RSA_ROWSM(1) RSA_ROWSM(2) RSA_ROWSM(4) RSA_ROWSM(8) RSA_ROWSM(16)
+#undef RSA_ROWSM
+  return false;
+}
+
 hipError_t staged_row_softmax(const Dims &d, int dtype, int n, const float *S, void *P, float *LSE,
                               hipStream_t st) {
   const int64_t rows = (int64_t)d.B * d.Z * d.c;
   const int64_t row_off = (int64_t)(n - d.rank_begin) * d.c;
+  if (dtype == RSA_BF16 ? launch_row_softmax_reg(S, (uint16_t *)P, LSE, rows, d.L, d.c, d.Lq, row_off, st)
+                        : launch_row_softmax_reg(S, (float *)P, LSE, rows, d.L, d.c, d.Lq, row_off, st))
+    return hipGetLastError();
   dim3 grid((unsigned)((rows + 3) / 4));
   if (dtype == RSA_BF16)
     hipLaunchKernelGGL(row_softmax_kernel<uint16_t>, grid, dim3(256), 0, st, S, (uint16_t *)P, LSE,
@@ -335,6 +399,7 @@ __global__ void __launch_bounds__(256) softmax_bwd_kernel(const T *P, const floa
   const T *p = P + row * L;
   const float *g = dP + row * L;
   T *o = dS + row * L;
+#pragma unroll 4
   for (int64_t i = lane * 4; i < L; i += 256) {
     const f32x4 gp = *reinterpret_cast<const f32x4 *>(g + i);
     float pv[4];
