@@ -75,6 +75,7 @@ def setup(cfg, torch, rsa, inputs):
         O=torch.empty_like(t["Q"]), LSE=torch.empty(t["Q"].shape[:3], dtype=torch.float32, device="cuda"),
         dQ=torch.empty_like(t["Q"]), dK=torch.empty_like(t["K"]), dV=torch.empty_like(t["V"]),
         ws=torch.empty(max(rsa.workspace_bytes(desc, True), 16), dtype=torch.uint8, device="cuda"),
+        ws_fwd=torch.empty(max(rsa.workspace_bytes(desc, False), 16), dtype=torch.uint8, device="cuda"),
     )
     return x, t, desc, buf
 
@@ -83,7 +84,7 @@ def time_workload(cfg, steps, warmup, torch, rsa, inputs, per_kernel=True):
     x, t, desc, b = setup(cfg, torch, rsa, inputs)
 
     def fwd():
-        rsa.forward(desc, t["Q"], t["K"], t["V"], O=b["O"], LSE=b["LSE"])
+        rsa.forward(desc, t["Q"], t["K"], t["V"], O=b["O"], LSE=b["LSE"], ws=b["ws_fwd"])
 
     def bwd():
         rsa.backward(desc, t["dO"], t["Q"], t["K"], t["V"], b["O"], b["LSE"],

@@ -158,7 +158,11 @@ int rsa_store(const rsa_desc *d, const float *src, void *dst, size_t count,
  *  rsa_bwd_dkdv: for every key chunk, the walk over the query rows of all
  *    simulated ranks -- dV = sum_n P^T dO, dK = s sum_n dS^T Q (the sums the
  *    ring all-reduces, section 3.2.2).  Also forms dP = dO V^T for its tiles.
- *  rsa_bwd_dq: for every rank, the K ring pass dQ^n = s sum_j dS^n_j K^j.
+ *  rsa_bwd_dq: for every rank, the K ring pass dQ^n = s sum_j dS^n_j K^j.  When the
+ *    descriptor has few query rows and many keys (one rank's share of a long
+ *    sequence) the pass over the keys is divided over several work-groups per
+ *    row tile, as in rsa_forward and rsa_backward; their fp32 partial sums use
+ *    the part of ws behind the row terms and Qs, which is why ws is writable.
  */
 int rsa_bwd_preprocess(const rsa_desc *d, const void *dO, const void *O,
                        const void *Q, const float *LSE, void *ws,
@@ -166,7 +170,7 @@ int rsa_bwd_preprocess(const rsa_desc *d, const void *dO, const void *O,
 int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *K, const void *V,
                  const void *ws, void *dK, void *dV, void *stream);
 int rsa_bwd_dq(const rsa_desc *d, const void *dO, const void *Q, const void *K,
-               const void *V, const void *ws, void *dQ, void *stream);
+               const void *V, void *ws, void *dQ, void *stream);
 
 /*
  * The two linear maps around RSA on the simulated ranks' rows (Table 2, sequence

@@ -61,13 +61,24 @@ StagedWs staged_layout(const Dims &d, int dtype, int pass) {
   return w;
 }
 
+// Fused backward: -D and -LSE log2e (fp32 per row), then Qs (pre-scaled bf16 copy of Q)
+size_t fused_bwd_base(const Dims &d) {
+  const size_t rows = (size_t)d.B * d.Z * d.Lq;
+  return 2 * align256(rows * 4) + align256(rows * d.A * 2);
+}
+
+// Fused path: the partial results of a split key walk (forward: unnormalised O and the pair
+// (max, sum) per split and row; backward: partial dQ per split and row, after the base part).
 size_t workspace_bytes(const Dims &d, int dtype, int pass) {
   if (d.mode == RSA_MODE_STAGED) return staged_layout(d, dtype, pass).total;
-  if (pass == 1) {  // -D and -LSE log2e (fp32 per row), then Qs (pre-scaled bf16 copy of Q)
-    const size_t rows = (size_t)d.B * d.Z * d.Lq;
-    return 2 * align256(rows * 4) + align256(rows * d.A * 2);
-  }
-  return 0;
+  const size_t rows = (size_t)d.B * d.Z * d.Lq;
+  const int ks = rsa::fused_key_splits(d);
+  if (pass == 1) return fused_bwd_base(d) + (ks > 1 ? align256(ks * rows * 64 * 4) : 0);
+  return ks > 1 ? align256(ks * rows * 66 * 4) : 0;
+}
+// where the split walks' partial sums start in the backward workspace
+inline float *fused_part(const Dims &d, void *ws) {
+  return reinterpret_cast<float *>(static_cast<char *>(ws) + fused_bwd_base(d));
 }
 
 // Fused backward workspace: -D at the start, -LSE log2e next, Qs after them.
@@ -207,7 +218,8 @@ int rsa_forward(const rsa_desc *d, const void *Q, const void *K, const void *V, 
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (dm.mode == RSA_MODE_STAGED)
     return staged_forward(dm, d->dtype, Q, K, V, O, LSE, static_cast<char *>(ws), st);
-  return hip_status(rsa::fused_forward(dm, Q, K, V, O, LSE, st));
+  return hip_status(rsa::fused_forward(dm, Q, K, V, O, LSE, st, static_cast<float *>(ws),
+                                       rsa::fused_key_splits(dm)));
 }
 
 int rsa_backward(const rsa_desc *d, const void *dO, const void *Q, const void *K, const void *V,
@@ -226,7 +238,8 @@ int rsa_backward(const rsa_desc *d, const void *dO, const void *Q, const void *K
   if (dm.mode == RSA_MODE_STAGED)
     return staged_backward(dm, d->dtype, dO, Q, K, V, O, dQ, dK, dV, static_cast<char *>(ws), st);
   return hip_status(rsa::fused_backward(dm, dO, Q, K, V, O, LSE, dQ, dK, dV, fused_nD(ws),
-                                        fused_nL(dm, ws), fused_Qs(dm, ws), st));
+                                        fused_nL(dm, ws), fused_Qs(dm, ws), st, fused_part(dm, ws), 1,
+                                        rsa::fused_key_splits(dm)));
 }
 
 // ------------------------------------------------------------ step level ----
@@ -324,11 +337,11 @@ int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *K, const void *V
 }
 
 int rsa_bwd_dq(const rsa_desc *d, const void *dO, const void *Q, const void *K, const void *V,
-               const void *ws, void *dQ, void *stream) {
+               void *ws, void *dQ, void *stream) {
   RSA_STEP_PROLOGUE(dO && Q && K && V && ws && dQ, dO, Q, K, V, ws, dQ);
   if (d->dtype != RSA_BF16 || dm.mode != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
-  void *w = const_cast<void *>(ws);
-  return hip_status(rsa::fused_bwd_dq(dm, dO, Q, K, V, fused_nL(dm, w), fused_nD(w), dQ, st));
+  return hip_status(rsa::fused_bwd_dq(dm, dO, Q, K, V, fused_nL(dm, ws), fused_nD(ws), dQ, st,
+                                      fused_part(dm, ws), rsa::fused_key_splits(dm)));
 }
 
 // ----------------------------------------------- projections around RSA ----
@@ -416,7 +429,7 @@ size_t linformer_ws(const Dims &own, const Dims &att, int64_t Kp) {
   const size_t part = (size_t)rsa::linformer_splits(Kp, Zt, own.Lq) * Kp * Zt * 64 * 4;
   // backward: row terms and Qs, then the fp32 partial dV, dK of the split query walk
   const int qs = rsa::fused_bwd_dkdv_splits(att);
-  const size_t bwd = workspace_bytes(att, RSA_BF16, 1) +
+  const size_t bwd = fused_bwd_base(att) +
                      (qs > 1 ? (size_t)2 * qs * Zt * Kp * 64 * 4 : 0);
   return align256(part > bwd ? part : bwd);
 }
@@ -451,7 +464,7 @@ int rsa_linformer_project(const rsa_desc *d, int32_t Kp, const void *X, const vo
 int rsa_linformer_forward(const rsa_desc *d, int32_t Kp, const void *Q, const void *Kp_, const void *Vp_,
                           void *O, float *LSE, void *stream) {
   RSA_LINF_PROLOGUE(Q && Kp_ && Vp_ && O && LSE, Q, Kp_, Vp_, O, LSE);
-  return hip_status(rsa::fused_forward(att, Q, Kp_, Vp_, O, LSE, st));
+  return hip_status(rsa::fused_forward(att, Q, Kp_, Vp_, O, LSE, st, nullptr, 1));
 }
 
 int rsa_linformer_backward(const rsa_desc *d, int32_t Kp, const void *dO, const void *Q, const void *Kp_,
@@ -461,10 +474,9 @@ int rsa_linformer_backward(const rsa_desc *d, int32_t Kp, const void *dO, const 
                     dQ, dKp, dVp, ws);
   if (ws_bytes < linformer_ws(own, att, Kp)) return RSA_ERR_WORKSPACE;
   const int qs = rsa::fused_bwd_dkdv_splits(att);
-  float *part = qs > 1 ? reinterpret_cast<float *>(static_cast<char *>(ws) + workspace_bytes(att, RSA_BF16, 1))
-                       : nullptr;
+  float *part = qs > 1 ? fused_part(att, ws) : nullptr;
   return hip_status(rsa::fused_backward(att, dO, Q, Kp_, Vp_, O, LSE, dQ, dKp, dVp, fused_nD(ws),
-                                        fused_nL(att, ws), fused_Qs(att, ws), st, part, qs));
+                                        fused_nL(att, ws), fused_Qs(att, ws), st, part, qs, 1));
 }
 
 int rsa_linformer_project_bwd(const rsa_desc *d, int32_t Kp, const void *dXp, const void *X, const void *E,

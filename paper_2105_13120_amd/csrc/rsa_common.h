@@ -123,10 +123,13 @@ __device__ __forceinline__ float wave_sum(float x) {
 // ids to XCDs round-robin, so id i runs on XCD i % 8.  Returns a logical id
 // such that each XCD gets one contiguous range of logical ids (work-groups
 // that share K/V then share that XCD's L2).  `n` must be the grid size.
-__device__ __forceinline__ uint32_t xcd_remap(uint32_t id, uint32_t n) {
+// `rot` turns the assignment of ranges to XCDs: with a second grid dimension that
+// repeats the ids (splits of a walk), rot = blockIdx.y lets every XCD take every
+// range in turn, so ranges of unequal work (causal mask) do not load the XCDs unequally.
+__device__ __forceinline__ uint32_t xcd_remap(uint32_t id, uint32_t n, uint32_t rot = 0) {
   const uint32_t per = n >> 3;
   if (per == 0 || id >= per * 8) return id;  // tail keeps its id
-  return (id & 7) * per + (id >> 3);
+  return ((id + rot) & 7) * per + (id >> 3);
 }
 
 // Derived sizes of a validated descriptor, shared by host code and kernels.

@@ -29,7 +29,9 @@ struct BwdArgs {
   float *nL_out, *nD_out;
   uint16_t *Qs_out;
   uint16_t *dQ, *dK, *dV;
-  float *part;  // dK/dV kernel with a split query walk: fp32 partial dV, then dK, per split
+  // fp32 partial sums per split: dV then dK of the dK/dV kernel with a split query walk,
+  // dQ of the dQ kernel with a split key walk
+  float *part;
   int64_t L, c, Lq;
   RowMap map;  // local query row -> global token index
   int N, tiles_per_head;
@@ -336,7 +338,7 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
-  const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x);
+  const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x, blockIdx.y);
   const int64_t head = wg / a.tiles_per_head;
   // under the causal mask later rows see more keys: the long work-groups of a head start first
   const int64_t row0 =
@@ -394,7 +396,7 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
       }
       dd = -xhalf_sum(acc);
       l2 = -a.LSE[head * a.Lq + qrow[qb]] * kLog2e;
-      if (r < a.Lq) {
+      if (r < a.Lq && blockIdx.y == 0) {
         if (half == 0) {
           a.nD_out[head * a.Lq + r] = dd;
           a.nL_out[head * a.Lq + r] = l2;
@@ -429,6 +431,10 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   // a stage never straddles chunks when tiles-per-chunk is even, otherwise NK falls to 1.
   const int nk = (tpr % NK == 0) ? NK : 1;
   const int spc = tpc / nk;  // stages per chunk
+  // the walk's stages, numbered t * spc + ks, divided over gridDim.y work-groups (see the forward)
+  const int per_split = (a.N * spc + (int)gridDim.y - 1) / (int)gridDim.y;
+  const int f_begin = (int)blockIdx.y * per_split;
+  const int f_end = f_begin + per_split < a.N * spc ? f_begin + per_split : a.N * spc;
   auto k0_of = [&](int t, int ks) -> int64_t {
     int j = n - t;
     if (j < 0) j += a.N;
@@ -438,7 +444,7 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
     ++ks;
     for (;;) {
       if (ks >= spc) { ++t; ks = 0; }
-      if (t >= a.N) return false;
+      if (t * spc + ks >= f_end) return false;
       if (!CAUSAL || k0_of(t, ks) <= q_last) return true;
       ks = spc;
     }
@@ -454,11 +460,12 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
     }
   };
 
-  int t = 0, kt = 0;
-  load_stage(k0_of(0, 0), Ks0, Vs0);
+  int t = f_begin / spc, kt = f_begin % spc;
+  bool have = f_begin < f_end;
+  if (CAUSAL && have && k0_of(t, kt) > q_last) have = advance(t, kt);
+  if (have) load_stage(k0_of(t, kt), Ks0, Vs0);
   wait_vmem();
   __syncthreads();
-  bool have = true;
   // one stage: start the loads of the next stage into (Kn, Vn), compute on (Kc, Vc)
   auto stage = [&](auto &Kc, auto &Vc, auto &Kn, auto &Vn) __attribute__((always_inline)) {
     const int64_t ks0 = k0_of(t, kt);
@@ -524,6 +531,26 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
     stage(Ks0, Vs0, Ks1, Vs1);
     if (!have) break;
     stage(Ks1, Vs1, Ks0, Vs0);
+  }
+
+  if (gridDim.y > 1) {  // fp32 partial sum of this split: [split][head][row][64]
+    const int64_t heads = gridDim.x / a.tiles_per_head;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      const int64_t r = row0 + wave * R + qb * 32 + col;
+      if (r < a.Lq) {
+        float *po = a.part + (((int64_t)blockIdx.y * heads + head) * a.Lq + r) * 64 + half * 4;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const f32x4 w = {dq[db][qb][g * 4 + 0] * a.scale, dq[db][qb][g * 4 + 1] * a.scale,
+                             dq[db][qb][g * 4 + 2] * a.scale, dq[db][qb][g * 4 + 3] * a.scale};
+            *reinterpret_cast<f32x4 *>(po + db * 32 + g * 8) = w;
+          }
+      }
+    }
+    return;
   }
 
   // the wave's R x 64 block of dQ leaves through its own LDS tile as whole 128-byte rows
@@ -601,41 +628,59 @@ hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Qs, const v
   return hipGetLastError();
 }
 
+// dQ = sum of the split walks' partial sums
+static hipError_t dq_reduce(const Dims &d, const float *part, void *dQ, int splits, hipStream_t st) {
+  const int64_t n4 = (int64_t)d.B * d.Z * d.Lq * 16;
+  hipLaunchKernelGGL(qsplit_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, part,
+                     (uint16_t *)dQ, n4, splits);
+  return hipGetLastError();
+}
+
 hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void *K, const void *V,
-                        const float *nL, const float *nD, void *dQ, hipStream_t st) {
+                        const float *nL, const float *nD, void *dQ, hipStream_t st, float *part,
+                        int splits) {
   BwdArgs a = make_bwd_args(d, dO, Q, nullptr, K, V, nL, nD, dQ, nullptr, nullptr);
   a.tiles_per_head = (int)((d.Lq + 127) / 128);
-  dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head));
+  a.part = part;
+  if (!part) splits = 1;
+  dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head), (unsigned)splits);
   if (d.causal)
     hipLaunchKernelGGL((fused_bwd_dq_kernel<32, true, false>), grid, dim3(256), 0, st, a);
   else
     hipLaunchKernelGGL((fused_bwd_dq_kernel<32, false, false>), grid, dim3(256), 0, st, a);
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || splits == 1) return e;
+  return dq_reduce(d, part, dQ, splits, st);
 }
 
 // The dQ kernel with the preprocess in its prologue: also writes -D, -LSE log2e and Qs.
 hipError_t fused_bwd_dq_pre(const Dims &d, const void *dO, const void *Q, const void *K, const void *V,
                             const void *O, const float *LSE, float *nL, float *nD, void *Qs, void *dQ,
-                            hipStream_t st) {
+                            hipStream_t st, float *part, int splits) {
   BwdArgs a = make_bwd_args(d, dO, Q, nullptr, K, V, nullptr, nullptr, dQ, nullptr, nullptr);
   a.O = (const uint16_t *)O; a.LSE = LSE; a.nL_out = nL; a.nD_out = nD; a.Qs_out = (uint16_t *)Qs;
   a.tiles_per_head = (int)((d.Lq + 127) / 128);
-  dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head));
+  a.part = part;
+  if (!part) splits = 1;
+  dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head), (unsigned)splits);
   if (d.causal)
     hipLaunchKernelGGL((fused_bwd_dq_kernel<32, true, true>), grid, dim3(256), 0, st, a);
   else
     hipLaunchKernelGGL((fused_bwd_dq_kernel<32, false, true>), grid, dim3(256), 0, st, a);
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || splits == 1) return e;
+  return dq_reduce(d, part, dQ, splits, st);
 }
 
 hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const void *K,
                           const void *V, const void *O, const float *LSE, void *dQ, void *dK,
                           void *dV, float *nD, float *nL, void *Qs, hipStream_t st, float *part,
-                          int splits) {
-  // the dQ kernel first: its prologue forms the row terms and Qs that the dK/dV kernel reads
-  hipError_t e = fused_bwd_dq_pre(d, dO, Q, K, V, O, LSE, nL, nD, Qs, dQ, st);
+                          int qsplits, int ksplits) {
+  // the dQ kernel first: its prologue forms the row terms and Qs that the dK/dV kernel reads;
+  // the two kernels' partial sums share `part`, one after the other
+  hipError_t e = fused_bwd_dq_pre(d, dO, Q, K, V, O, LSE, nL, nD, Qs, dQ, st, part, ksplits);
   if (e != hipSuccess) return e;
-  return fused_bwd_dkdv(d, dO, Qs, K, V, nL, nD, dK, dV, st, part, splits);
+  return fused_bwd_dkdv(d, dO, Qs, K, V, nL, nD, dK, dV, st, part, qsplits);
 }
 
 }  // namespace rsa

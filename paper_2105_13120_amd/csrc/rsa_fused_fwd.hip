@@ -28,6 +28,9 @@ struct FwdArgs {
   RowMap map;            // local query row -> global token index
   int N, tiles_per_head;
   float cl2;             // scale * log2(e)
+  // split key walk (gridDim.y > 1): per split, head and row the unnormalised fp32 O and the pair
+  // (stale max * cl2, row sum) it is relative to
+  float *part_o, *part_ml;
 };
 
 template <int R, bool CAUSAL>
@@ -44,7 +47,7 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
-  const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x);
+  const uint32_t wg = xcd_remap(blockIdx.x, gridDim.x, blockIdx.y);
   const int64_t head = wg / a.tiles_per_head;
   // under the causal mask later rows see more keys: the long work-groups of a head start first
   const int64_t qt = CAUSAL ? a.tiles_per_head - 1 - wg % a.tiles_per_head : wg % a.tiles_per_head;
@@ -104,6 +107,11 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
   // a stage never straddles chunks when tiles-per-chunk is even, otherwise NK falls to 1.
   const int nk = (tpr % NK == 0) ? NK : 1;
   const int spc = tpc / nk;  // stages per chunk
+  // With few work-groups the walk's stages, numbered t * spc + ks, are divided over gridDim.y
+  // work-groups, each leaving an unnormalised partial result that a second kernel merges.
+  const int per_split = (a.N * spc + (int)gridDim.y - 1) / (int)gridDim.y;
+  const int f_begin = (int)blockIdx.y * per_split;
+  const int f_end = f_begin + per_split < a.N * spc ? f_begin + per_split : a.N * spc;
   auto k0_of = [&](int t, int ks) -> int64_t {
     int j = n - t;
     if (j < 0) j += a.N;
@@ -114,7 +122,7 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
     ++ks;
     for (;;) {
       if (ks >= spc) { ++t; ks = 0; }
-      if (t >= a.N) return false;
+      if (t * spc + ks >= f_end) return false;
       if (!CAUSAL || k0_of(t, ks) <= q_last) return true;
       ks = spc;  // later stages of this chunk start even further right
     }
@@ -130,11 +138,12 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
     }
   };
 
-  int t = 0, kt = 0;
-  load_stage(k0_of(0, 0), Ks0, Vs0);
+  int t = f_begin / spc, kt = f_begin % spc;
+  bool have = f_begin < f_end;
+  if (CAUSAL && have && k0_of(t, kt) > q_last) have = advance(t, kt);
+  if (have) load_stage(k0_of(t, kt), Ks0, Vs0);
   wait_vmem();
   __syncthreads();
-  bool have = true;
   // one stage: start the loads of the next stage into (Kn, Vn), compute on (Kc, Vc)
   auto stage = [&](auto &Kc, auto &Vc, auto &Kn, auto &Vn) __attribute__((always_inline)) {
     const int64_t ks0 = k0_of(t, kt);
@@ -191,10 +200,12 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
       if (__builtin_amdgcn_ballot_w64(need) != 0) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
+          // a row that has seen no key yet (a split walk can start right of it) keeps mc = 0
           const float mn = fmaxf(m[qb], tm[qb]);
-          const float alpha = __builtin_amdgcn_exp2f((m[qb] - mn) * a.cl2);
+          const bool seen = mn > -INFINITY;
+          const float alpha = seen ? __builtin_amdgcn_exp2f((m[qb] - mn) * a.cl2) : 1.0f;
           m[qb] = mn;
-          mc[qb] = mn * a.cl2;
+          mc[qb] = seen ? mn * a.cl2 : 0.f;
           l[qb] *= alpha;
 #pragma unroll
           for (int db = 0; db < 2; ++db)
@@ -247,6 +258,31 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
     stage(Ks1, Vs1, Ks0, Vs0);
   }
 
+  if (gridDim.y > 1) {  // partial result of this split
+    const int64_t heads = gridDim.x / a.tiles_per_head;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      const float lt = xhalf_sum(l[qb]);
+      const int64_t r = row0 + wave * R + qb * 32 + col;
+      if (r < a.Lq) {
+        const int64_t pr = ((int64_t)blockIdx.y * heads + head) * a.Lq + r;
+        float *po = a.part_o + pr * 64 + half * 4;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const f32x4 w = {o[db][qb][g * 4 + 0], o[db][qb][g * 4 + 1], o[db][qb][g * 4 + 2], o[db][qb][g * 4 + 3]};
+            *reinterpret_cast<f32x4 *>(po + db * 32 + g * 8) = w;
+          }
+        if (half == 0) {
+          a.part_ml[pr * 2] = lt > 0.f ? mc[qb] : -INFINITY;
+          a.part_ml[pr * 2 + 1] = lt;
+        }
+      }
+    }
+    return;
+  }
+
   // ---- epilogue: O = O^T / l, LSE = s m + ln l.  The wave's R x 64 block of O goes through its
   // own LDS tile (every wave is past the loop's last barrier and no load is in flight, so the
   // stage buffers are free) and leaves as whole 128-byte rows.
@@ -263,9 +299,37 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
   flush_rows<R>(ot, 0, a.O + (head * a.Lq + wr0) * 64, a.Lq - wr0, lane);
 }
 
+// Merge of the split walks' partial results: with M the largest stale max of a row,
+// O = sum_s 2^(mc_s - M) o_s / sum_s 2^(mc_s - M) l_s and LSE = (M + log2 of that denominator) ln 2.
+// A split that saw no key of the row has mc = -inf and is left out.  16 lanes x 4 columns per row.
+__global__ void __launch_bounds__(256) fwd_combine_kernel(const float *part_o, const float *part_ml,
+                                                          uint16_t *O, float *LSE, int64_t rows, int splits) {
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t row = gid >> 4;
+  const int sub = (int)(gid & 15);
+  if (row >= rows) return;
+  float M = -INFINITY;
+  for (int s = 0; s < splits; ++s) M = fmaxf(M, part_ml[((int64_t)s * rows + row) * 2]);
+  float lsum = 0.f;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < splits; ++s) {
+    const int64_t pr = (int64_t)s * rows + row;
+    const float mc = part_ml[pr * 2];
+    if (mc > -INFINITY) {
+      const float w = __builtin_amdgcn_exp2f(mc - M);
+      lsum = fmaf(w, part_ml[pr * 2 + 1], lsum);
+      acc += *reinterpret_cast<const f32x4 *>(part_o + pr * 64 + sub * 4) * w;
+    }
+  }
+  const float inv = 1.0f / lsum;
+  const u32x2 w = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv)};
+  *reinterpret_cast<u32x2 *>(O + row * 64 + sub * 4) = w;
+  if (sub == 0) LSE[row] = (M + __builtin_amdgcn_logf(lsum)) * kLn2;
+}
+
 template <int R>
-static hipError_t launch_fwd(const Dims &d, const FwdArgs &a, int64_t heads, hipStream_t st) {
-  dim3 grid((unsigned)(heads * a.tiles_per_head));
+static hipError_t launch_fwd(const Dims &d, const FwdArgs &a, int64_t heads, int splits, hipStream_t st) {
+  dim3 grid((unsigned)(heads * a.tiles_per_head), (unsigned)splits);
   if (d.causal)
     hipLaunchKernelGGL((fused_fwd_kernel<R, true>), grid, dim3(256), 0, st, a);
   else
@@ -273,8 +337,23 @@ static hipError_t launch_fwd(const Dims &d, const FwdArgs &a, int64_t heads, hip
   return hipGetLastError();
 }
 
+// Splits of the key walk for the forward and dQ kernels (both own 128 query rows per
+// work-group when the problem is small): 1 when the rows alone fill the chip.  A split
+// keeps at least 8 stages of 128 keys.  Under the causal mask the walks differ in length,
+// so more, shorter work-groups are wanted.
+int fused_key_splits(const Dims &d) {
+  const int64_t wgs = (int64_t)d.B * d.Z * ((d.Lq + 127) / 128);
+  const int64_t stages = d.L / 128;
+  const int64_t want = d.causal ? 3072 : 1536;
+  if (wgs >= 1024) return 1;
+  int64_t s = (want + wgs - 1) / wgs;
+  if (s > stages / 8) s = stages / 8;
+  if (s > 32) s = 32;
+  return s < 2 ? 1 : (int)s;
+}
+
 hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void *V, void *O,
-                         float *LSE, hipStream_t st) {
+                         float *LSE, hipStream_t st, float *part, int splits) {
   FwdArgs a;
   a.Q = (const uint16_t *)Q; a.K = (const uint16_t *)K; a.V = (const uint16_t *)V;
   a.O = (uint16_t *)O; a.LSE = LSE;
@@ -284,13 +363,17 @@ hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void
   const int64_t heads = (int64_t)d.B * d.Z;
   // 64 rows per wave halves the LDS traffic per flop; 32 rows per wave gives
   // twice the work-groups when the problem is too small to fill 256 CUs twice over.
-  const bool big = (d.Lq % 256 == 0) && heads * (d.Lq / 256) >= 512;
-  if (big) {
-    a.tiles_per_head = (int)(d.Lq / 256);
-    return launch_fwd<64>(d, a, heads, st);
-  }
-  a.tiles_per_head = (int)((d.Lq + 127) / 128);
-  return launch_fwd<32>(d, a, heads, st);
+  if (!part) splits = 1;
+  const bool big = (d.Lq % 256 == 0) && heads * (d.Lq / 256) * splits >= 512;
+  const int64_t rows = heads * d.Lq;
+  a.part_o = part;
+  a.part_ml = part ? part + (int64_t)splits * rows * 64 : nullptr;
+  a.tiles_per_head = big ? (int)(d.Lq / 256) : (int)((d.Lq + 127) / 128);
+  hipError_t e = big ? launch_fwd<64>(d, a, heads, splits, st) : launch_fwd<32>(d, a, heads, splits, st);
+  if (e != hipSuccess || splits == 1) return e;
+  hipLaunchKernelGGL(fwd_combine_kernel, dim3((unsigned)((rows * 16 + 255) / 256)), dim3(256), 0, st,
+                     a.part_o, a.part_ml, (uint16_t *)O, LSE, rows, splits);
+  return hipGetLastError();
 }
 
 }  // namespace rsa

@@ -31,8 +31,11 @@ hipError_t store_rows(int dtype, const float *src, void *dst, int64_t batches,
                       hipStream_t st);
 
 // --- fused (online-softmax) path, bf16, A = 64 ---
+// part / splits: optional split of the walk over the keys (few query rows, many keys), see
+// fused_key_splits: fp32 partial results, splits * B*Z*Lq * 66 floats; nullptr / 1: none
+int fused_key_splits(const Dims &d);
 hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void *V, void *O,
-                         float *LSE, hipStream_t st);
+                         float *LSE, hipStream_t st, float *part, int splits);
 // nD = -rowsum(dO o O) and nL = -LSE log2e, (B,Z,Lq) fp32; Qs = bf16(Q * scale * log2 e) (B,Z,Lq,64)
 hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, const void *Q,
                                 const float *LSE, float *nD, float *nL, void *Qs, hipStream_t st);
@@ -42,12 +45,14 @@ int fused_bwd_dkdv_splits(const Dims &d);
 hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Qs, const void *K,
                           const void *V, const float *nL, const float *nD, void *dK, void *dV,
                           hipStream_t st, float *part = nullptr, int splits = 1);
+// part / splits: the split key walk again, fp32 partial dQ, splits * B*Z*Lq * 64 floats
 hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void *K, const void *V,
-                        const float *nL, const float *nD, void *dQ, hipStream_t st);
+                        const float *nL, const float *nD, void *dQ, hipStream_t st,
+                        float *part = nullptr, int splits = 1);
 hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const void *K,
                           const void *V, const void *O, const float *LSE, void *dQ, void *dK,
                           void *dV, float *nD, float *nL, void *Qs, hipStream_t st,
-                          float *part = nullptr, int splits = 1);
+                          float *part = nullptr, int qsplits = 1, int ksplits = 1);
 
 // --- the linear maps around RSA (Table 2, rows Q/K/V and Linear), bf16, A = 64 ---
 // X, dX, Y, dY: (B, Lq, H); W: (H, 3*Z*64), columns [Q | K | V] head-major; Wo: (Z*64, H);
