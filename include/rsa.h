@@ -26,8 +26,9 @@
  *  - dtype RSA_BF16: bf16 storage, fp32 accumulation and fp32 softmax, one
  *    round-to-nearest-even per stored element.  dtype RSA_F32: fp32
  *    throughout (staged mode only).
- *  - Supported: A = 64; L divisible by N (section 4.2: the sequence length
- *    must be divisible by the sequence-parallel size); c divisible by 64.
+ *  - Supported: A = 64 in fused mode, any multiple of 64 up to 256 in staged
+ *    mode; L divisible by N (section 4.2: the sequence length must be
+ *    divisible by the sequence-parallel size); c divisible by 64.
  */
 #ifndef RSA_H
 #define RSA_H
@@ -85,7 +86,10 @@ size_t rsa_workspace_bytes(const rsa_desc *d, int pass);
  * scores of Q^n against K^j, full-row softmax over all L keys, O^n = sum_j
  * P^n_j V^j.  Writes O (dtype) and LSE_i = log sum_j exp(S_ij) (fp32).
  * ws: workspace of at least rsa_workspace_bytes(d, 0) bytes (may be NULL if
- * that is 0).
+ * that is 0).  Staged mode keeps the score strip there; fused mode needs it
+ * only when the descriptor has so few query rows for its keys (one rank's
+ * share of a long sequence) that the pass over the keys is divided among
+ * several work-groups per row tile, whose fp32 partial results it holds.
  */
 int rsa_forward(const rsa_desc *d, const void *Q, const void *K, const void *V,
                 void *O, float *LSE, void *ws, size_t ws_bytes, void *stream);

@@ -13,12 +13,13 @@ int validate(const rsa_desc *d, Dims *out) {
   if (d->B < 1 || d->Z < 1 || d->A < 1 || d->L < 1 || d->N < 1) return RSA_ERR_SHAPE;
   if (d->L % d->N != 0) return RSA_ERR_SHAPE;  // section 4.2: L divisible by the ring size
   if (d->rank_begin < 0 || d->rank_end > d->N || d->rank_begin >= d->rank_end) return RSA_ERR_SHAPE;
-  if (d->A != 64) return RSA_ERR_UNSUPPORTED;
+  if (d->A % 64 != 0 || d->A > 256) return RSA_ERR_UNSUPPORTED;
   if (d->dtype != RSA_F32 && d->dtype != RSA_BF16) return RSA_ERR_UNSUPPORTED;
   if (d->flags & ~(RSA_MODE_STAGED | RSA_OWN_ZIGZAG)) return RSA_ERR_UNSUPPORTED;
   const int mode = (int)(d->flags & RSA_MODE_STAGED);
   const int zigzag = (d->flags & RSA_OWN_ZIGZAG) ? 1 : 0;
-  if (mode == RSA_MODE_FUSED && d->dtype != RSA_BF16) return RSA_ERR_UNSUPPORTED;
+  // the fused kernels are written for bf16 heads of 64 elements
+  if (mode == RSA_MODE_FUSED && (d->dtype != RSA_BF16 || d->A != 64)) return RSA_ERR_UNSUPPORTED;
   const int64_t c = d->L / d->N;
   if (c % 64 != 0) return RSA_ERR_UNSUPPORTED;
   if (zigzag && (mode == RSA_MODE_STAGED || c % 128 != 0)) return RSA_ERR_UNSUPPORTED;
@@ -146,8 +147,8 @@ int staged_backward(const Dims &d, int dtype, const void *dO, const void *Q, con
   const size_t es = dtype == RSA_BF16 ? 2 : 4;
   const int64_t heads = (int64_t)d.B * d.Z;
   // chunks that no simulated rank looks at keep a zero gradient
-  RSA_TRY(hipMemsetAsync(dKacc, 0, (size_t)heads * d.L * d.A * 4, st));
-  RSA_TRY(hipMemsetAsync(dVacc, 0, (size_t)heads * d.L * d.A * 4, st));
+  RSA_TRY(rsa::zero_f32(dKacc, heads * d.L * d.A, st));
+  RSA_TRY(rsa::zero_f32(dVacc, heads * d.L * d.A, st));
   RSA_TRY(rsa::rowdot(d, dtype, 0, d.Lq, dO, O, D, st));
   // the softmax statistics are recomputed; the LSE written here is scratch
   float *lse_scratch = dQacc;  // (heads * c) floats fit in (heads * c * A)

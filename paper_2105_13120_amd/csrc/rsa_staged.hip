@@ -434,11 +434,12 @@ hipError_t staged_softmax_bwd(const Dims &d, int dtype, int n, const void *P, co
 }
 
 // --------------------------------------------------------------- row dot ----
-// D_i = sum_a dO_ia O_ia over A = 64: 8 lanes x 8 elements per row.
+// D_i = sum_a dO_ia O_ia over the A elements of a row (A a multiple of 64): 8 lanes per row,
+// each taking 8 elements of every 64.
 template <typename T>
 __global__ void __launch_bounds__(256) rowdot_kernel(const T *dO, const T *O, float *D,
                                                      int64_t rows_per_head, int64_t Lq,
-                                                     int64_t row_off, int64_t total_rows) {
+                                                     int64_t row_off, int64_t total_rows, int A) {
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t row = gid >> 3;
   const int sub = (int)(gid & 7);
@@ -447,19 +448,21 @@ __global__ void __launch_bounds__(256) rowdot_kernel(const T *dO, const T *O, fl
   if (row < total_rows) {
     const int64_t head = row / rows_per_head, r = row % rows_per_head;
     idx = head * Lq + row_off + r;
-    const T *a = dO + idx * 64 + sub * 8;
-    const T *b = O + idx * 64 + sub * 8;
-    if constexpr (sizeof(T) == 2) {
-      const u32x4 x = *reinterpret_cast<const u32x4 *>(a);
-      const u32x4 y = *reinterpret_cast<const u32x4 *>(b);
+    for (int a0 = 0; a0 < A; a0 += 64) {
+      const T *a = dO + idx * A + a0 + sub * 8;
+      const T *b = O + idx * A + a0 + sub * 8;
+      if constexpr (sizeof(T) == 2) {
+        const u32x4 x = *reinterpret_cast<const u32x4 *>(a);
+        const u32x4 y = *reinterpret_cast<const u32x4 *>(b);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        acc = fmaf(bf16_to_f32(x[e] & 0xffffu), bf16_to_f32(y[e] & 0xffffu), acc);
-        acc = fmaf(bf16_to_f32(x[e] >> 16), bf16_to_f32(y[e] >> 16), acc);
+        for (int e = 0; e < 4; ++e) {
+          acc = fmaf(bf16_to_f32(x[e] & 0xffffu), bf16_to_f32(y[e] & 0xffffu), acc);
+          acc = fmaf(bf16_to_f32(x[e] >> 16), bf16_to_f32(y[e] >> 16), acc);
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc = fmaf(a[e], b[e], acc);
       }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc = fmaf(a[e], b[e], acc);
     }
   }
   acc += __shfl_xor(acc, 1);
@@ -474,10 +477,25 @@ hipError_t rowdot(const Dims &d, int dtype, int64_t row_off, int64_t rows_per_he
   dim3 grid((unsigned)((total * 8 + 255) / 256));
   if (dtype == RSA_BF16)
     hipLaunchKernelGGL(rowdot_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t *)dO,
-                       (const uint16_t *)O, D, rows_per_head, d.Lq, row_off, total);
+                       (const uint16_t *)O, D, rows_per_head, d.Lq, row_off, total, d.A);
   else
     hipLaunchKernelGGL(rowdot_kernel<float>, grid, dim3(256), 0, st, (const float *)dO,
-                       (const float *)O, D, rows_per_head, d.Lq, row_off, total);
+                       (const float *)O, D, rows_per_head, d.Lq, row_off, total, d.A);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ fill ----
+// A kernel rather than a memset, so that a caller may capture the launch sequence in a graph.
+__global__ void __launch_bounds__(256) zero_kernel(f32x4 *p, int64_t n4) {
+  const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) p[i] = z;
+}
+
+hipError_t zero_f32(float *p, int64_t n, hipStream_t st) {  // n: a multiple of 4
+  const int64_t n4 = n / 4;
+  const int64_t blocks = (n4 + 255) / 256;
+  hipLaunchKernelGGL(zero_kernel, dim3((unsigned)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, st,
+                     reinterpret_cast<f32x4 *>(p), n4);
   return hipGetLastError();
 }
 

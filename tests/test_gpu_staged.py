@@ -10,8 +10,8 @@ from paper_2105_13120_amd import inputs, rsa
 pytestmark = pytest.mark.gpu
 
 
-def small_cfg(dtype, causal=False, B=2, Z=2, L=256, N=4, rb=0, re=-1, seed=3):
-    return inputs.RSAConfig("t", B=B, Z=Z, L=L, A=64, N=N, dtype=dtype, causal=causal,
+def small_cfg(dtype, causal=False, B=2, Z=2, L=256, N=4, rb=0, re=-1, seed=3, A=64):
+    return inputs.RSAConfig("t", B=B, Z=Z, L=L, A=A, N=N, dtype=dtype, causal=causal,
                             rank_begin=rb, rank_end=re, seed=seed)
 
 
@@ -115,3 +115,13 @@ def test_staged_forward_backward(dtype, causal, rb, re):
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED)
     compare_heads(cfg, x, out, [0, 1, 2])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("A,causal,rb,re", [(128, False, 0, -1), (128, True, 1, 3), (192, True, 0, -1)])
+def test_staged_heads_wider_than_64(dtype, A, causal, rb, re):
+    """The two-pass layout takes any head size that is a multiple of 64 (up to 256)."""
+    cfg = small_cfg(dtype, causal, B=1, Z=2, L=384, N=3, rb=rb, re=re, seed=29, A=A)
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED)
+    compare_heads(cfg, x, out, [0, 1])
