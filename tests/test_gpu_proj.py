@@ -87,6 +87,44 @@ def test_projection_outputs_feed_rsa_without_relayout():
     check("Y", download(Y), oracle.proj.out_proj(download(O), Wo), "bf16")
 
 
+def test_attention_block_backward_chain():
+    """dY -> Linear backward -> RSA backward -> Q/K/V projection backward: the whole block's
+    gradients, each stage against the oracle on the rounded tensors that stage received."""
+    B, Z, L, N, H, A = 2, 4, 512, 4, 256, 64
+    X = draw((B, L, H), 21)
+    W = draw((H, 3 * Z * A), 22, H ** -0.5)
+    Wo = draw((Z * A, H), 23, (Z * A) ** -0.5)
+    dY = draw((B, L, H), 24)
+    tX, tW, tWo, tdY = (upload(v, "bf16") for v in (X, W, Wo, dY))
+    desc = rsa.make_desc(torch.empty((B, Z, L, A), dtype=torch.bfloat16), N)
+    Q, K, V = rsa.qkv_proj(desc, tX, tW)
+    O, LSE = rsa.forward(desc, Q, K, V)
+    dO, dWo = rsa.out_proj_bwd(desc, tdY, O, tWo)
+    dQ, dK, dV = rsa.backward(desc, dO, Q, K, V, O, LSE)
+    dX, dW = rsa.qkv_proj_bwd(desc, dQ, dK, dV, tX, tW)
+    torch.cuda.synchronize()
+    P = oracle.proj
+    rO, rWo = P.out_proj_bwd(dY, download(O), Wo)
+    check("dO", download(dO), rO, "bf16")
+    check_f32("dWo", download(dWo), rWo)
+    g = oracle.backward(download(Q), download(K), download(V), download(dO))
+    for name, got, ref in zip(("dQ", "dK", "dV"), (dQ, dK, dV), g):
+        # O was rounded before D was formed from it, as in the kernels
+        check(name, download(got), ref, "bf16")
+    rX, rW = P.qkv_proj_bwd(download(dQ), download(dK), download(dV), X, W)
+    check("dX", download(dX), rX, "bf16")
+    check_f32("dWqkv", download(dW), rW)
+    # and the block as a whole against fp64 end to end: errors of the stages compound,
+    # so only the relative RMS error is held, to a few bf16 roundings
+    fQ, fK, fV = P.qkv_proj(X, W, Z, A)
+    fO, _ = oracle.forward(fQ, fK, fV)
+    fdO, _ = P.out_proj_bwd(dY, fO, Wo)
+    fg = oracle.backward(fQ, fK, fV, fdO)
+    fdX, _ = P.qkv_proj_bwd(fg[0], fg[1], fg[2], X, W)
+    err = download(dX) - fdX
+    assert np.sqrt(np.mean(err ** 2)) <= 2e-2 * np.sqrt(np.mean(fdX ** 2))
+
+
 def test_projection_error_codes():
     Kfull = torch.empty((1, 2, 128, 64), dtype=torch.bfloat16, device="cuda")
     desc = rsa.make_desc(Kfull, 2)
