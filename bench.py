@@ -110,10 +110,11 @@ def time_workload(cfg, steps, warmup, torch, rsa, inputs, per_kernel=True):
             step()
         k = {
             "fwd": event_ms(fwd, it, torch),
-            "bwd_preprocess": event_ms(lambda: rsa.bwd_preprocess(desc, t["dO"], b["O"], t["Q"], b["LSE"],
+            "bwd_preprocess": event_ms(lambda: rsa.bwd_preprocess(desc, t["dO"], b["O"], b["LSE"],
                                                                   b["ws"]),
                                        it, torch),
-            "bwd_dkdv": event_ms(lambda: rsa.bwd_dkdv(desc, t["dO"], t["K"], t["V"], b["ws"], b["dK"], b["dV"]),
+            "bwd_dkdv": event_ms(lambda: rsa.bwd_dkdv(desc, t["dO"], t["Q"], t["K"], t["V"], b["ws"], b["dK"],
+                                                      b["dV"]),
                                  it, torch),
             "bwd_dq": event_ms(lambda: rsa.bwd_dq(desc, t["dO"], t["Q"], t["K"], t["V"], b["ws"], b["dQ"]),
                                it, torch),

@@ -156,9 +156,10 @@ int rsa_store(const rsa_desc *d, const float *src, void *dst, size_t count,
  * into its prologue, then the dK/dV kernel; the three calls below in the order
  * given produce the same gradients up to the fp32 summation order of D.
  *  rsa_bwd_preprocess: fills ws with the row terms -D_i = -sum_a dO_ia O_ia and
- *    -LSE_i log2(e) (fp32) and with Qs, a bf16 copy of Q multiplied by
- *    s * log2(e), the operand from which both other kernels recompute
- *    P = exp2(Qs K^T - LSE log2 e) tile by tile.  The other two read ws only.
+ *    -LSE_i log2(e) (fp32).  Both other kernels recompute
+ *    P = exp2(s log2(e) Q K^T - LSE log2 e) tile by tile, with the factor
+ *    s log2(e) folded into the operand they keep in registers (K in the dK/dV
+ *    kernel, Q in the dQ kernel; one rounding to bf16), and read the row terms.
  *  rsa_bwd_dkdv: for every key chunk, the walk over the query rows of all
  *    simulated ranks -- dV = sum_n P^T dO, dK = s sum_n dS^T Q (the sums the
  *    ring all-reduces, section 3.2.2).  Also forms dP = dO V^T for its tiles.
@@ -166,13 +167,13 @@ int rsa_store(const rsa_desc *d, const float *src, void *dst, size_t count,
  *    descriptor has few query rows and many keys (one rank's share of a long
  *    sequence) the pass over the keys is divided over several work-groups per
  *    row tile, as in rsa_forward and rsa_backward; their fp32 partial sums use
- *    the part of ws behind the row terms and Qs, which is why ws is writable.
+ *    the part of ws behind the row terms, which is why ws is writable.
  */
 int rsa_bwd_preprocess(const rsa_desc *d, const void *dO, const void *O,
-                       const void *Q, const float *LSE, void *ws,
-                       size_t ws_bytes, void *stream);
-int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *K, const void *V,
-                 const void *ws, void *dK, void *dV, void *stream);
+                       const float *LSE, void *ws, size_t ws_bytes,
+                       void *stream);
+int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *Q, const void *K,
+                 const void *V, const void *ws, void *dK, void *dV, void *stream);
 int rsa_bwd_dq(const rsa_desc *d, const void *dO, const void *Q, const void *K,
                const void *V, void *ws, void *dQ, void *stream);
 

@@ -62,10 +62,10 @@ StagedWs staged_layout(const Dims &d, int dtype, int pass) {
   return w;
 }
 
-// Fused backward: -D and -LSE log2e (fp32 per row), then Qs (pre-scaled bf16 copy of Q)
+// Fused backward: the row terms -D and -LSE log2e (fp32 per row)
 size_t fused_bwd_base(const Dims &d) {
   const size_t rows = (size_t)d.B * d.Z * d.Lq;
-  return 2 * align256(rows * 4) + align256(rows * d.A * 2);
+  return 2 * align256(rows * 4);
 }
 
 // Fused path: the partial results of a split key walk (forward: unnormalised O and the pair
@@ -82,13 +82,10 @@ inline float *fused_part(const Dims &d, void *ws) {
   return reinterpret_cast<float *>(static_cast<char *>(ws) + fused_bwd_base(d));
 }
 
-// Fused backward workspace: -D at the start, -LSE log2e next, Qs after them.
+// Fused backward workspace: -D at the start, -LSE log2e next.
 inline float *fused_nD(void *ws) { return static_cast<float *>(ws); }
 inline float *fused_nL(const Dims &d, void *ws) {
   return reinterpret_cast<float *>(static_cast<char *>(ws) + align256((size_t)d.B * d.Z * d.Lq * 4));
-}
-inline void *fused_Qs(const Dims &d, void *ws) {
-  return static_cast<char *>(ws) + 2 * align256((size_t)d.B * d.Z * d.Lq * 4);
 }
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? RSA_OK : RSA_ERR_HIP; }
@@ -239,7 +236,7 @@ int rsa_backward(const rsa_desc *d, const void *dO, const void *Q, const void *K
   if (dm.mode == RSA_MODE_STAGED)
     return staged_backward(dm, d->dtype, dO, Q, K, V, O, dQ, dK, dV, static_cast<char *>(ws), st);
   return hip_status(rsa::fused_backward(dm, dO, Q, K, V, O, LSE, dQ, dK, dV, fused_nD(ws),
-                                        fused_nL(dm, ws), fused_Qs(dm, ws), st, fused_part(dm, ws), 1,
+                                        fused_nL(dm, ws), st, fused_part(dm, ws), 1,
                                         rsa::fused_key_splits(dm)));
 }
 
@@ -319,22 +316,20 @@ int rsa_store(const rsa_desc *d, const float *src, void *dst, size_t count, void
   return hip_status(rsa::store_rows(d->dtype, src, dst, 1, 1, (int64_t)count, 0, 0, st));
 }
 
-int rsa_bwd_preprocess(const rsa_desc *d, const void *dO, const void *O, const void *Q,
-                       const float *LSE, void *ws, size_t ws_bytes, void *stream) {
-  RSA_STEP_PROLOGUE(dO && O && Q && LSE, dO, O, Q, LSE, ws);
+int rsa_bwd_preprocess(const rsa_desc *d, const void *dO, const void *O, const float *LSE,
+                       void *ws, size_t ws_bytes, void *stream) {
+  RSA_STEP_PROLOGUE(dO && O && LSE, dO, O, LSE, ws);
   if (d->dtype != RSA_BF16 || dm.mode != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
   if (!ws || ws_bytes < workspace_bytes(dm, d->dtype, 1)) return RSA_ERR_WORKSPACE;
-  return hip_status(rsa::fused_bwd_preprocess(dm, dO, O, Q, LSE, fused_nD(ws), fused_nL(dm, ws),
-                                              fused_Qs(dm, ws), st));
+  return hip_status(rsa::fused_bwd_preprocess(dm, dO, O, LSE, fused_nD(ws), fused_nL(dm, ws), st));
 }
 
-int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *K, const void *V, const void *ws,
-                 void *dK, void *dV, void *stream) {
-  RSA_STEP_PROLOGUE(dO && K && V && ws && dK && dV, dO, K, V, ws, dK, dV);
+int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *Q, const void *K, const void *V,
+                 const void *ws, void *dK, void *dV, void *stream) {
+  RSA_STEP_PROLOGUE(dO && Q && K && V && ws && dK && dV, dO, Q, K, V, ws, dK, dV);
   if (d->dtype != RSA_BF16 || dm.mode != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
   void *w = const_cast<void *>(ws);
-  return hip_status(rsa::fused_bwd_dkdv(dm, dO, fused_Qs(dm, w), K, V, fused_nL(dm, w), fused_nD(w),
-                                        dK, dV, st));
+  return hip_status(rsa::fused_bwd_dkdv(dm, dO, Q, K, V, fused_nL(dm, w), fused_nD(w), dK, dV, st));
 }
 
 int rsa_bwd_dq(const rsa_desc *d, const void *dO, const void *Q, const void *K, const void *V,
@@ -428,7 +423,7 @@ int linformer_dims(const rsa_desc *d, int32_t Kp, Dims *own, Dims *att) {
 size_t linformer_ws(const Dims &own, const Dims &att, int64_t Kp) {
   const int64_t Zt = (int64_t)own.B * own.Z;
   const size_t part = (size_t)rsa::linformer_splits(Kp, Zt, own.Lq) * Kp * Zt * 64 * 4;
-  // backward: row terms and Qs, then the fp32 partial dV, dK of the split query walk
+  // backward: row terms, then the fp32 partial dV, dK of the split query walk
   const int qs = rsa::fused_bwd_dkdv_splits(att);
   const size_t bwd = fused_bwd_base(att) +
                      (qs > 1 ? (size_t)2 * qs * Zt * Kp * 64 * 4 : 0);
@@ -477,7 +472,7 @@ int rsa_linformer_backward(const rsa_desc *d, int32_t Kp, const void *dO, const 
   const int qs = rsa::fused_bwd_dkdv_splits(att);
   float *part = qs > 1 ? fused_part(att, ws) : nullptr;
   return hip_status(rsa::fused_backward(att, dO, Q, Kp_, Vp_, O, LSE, dQ, dKp, dVp, fused_nD(ws),
-                                        fused_nL(att, ws), fused_Qs(att, ws), st, part, qs, 1));
+                                        fused_nL(att, ws), st, part, qs, 1));
 }
 
 int rsa_linformer_project_bwd(const rsa_desc *d, int32_t Kp, const void *dXp, const void *X, const void *E,

@@ -2,32 +2,34 @@
 // with the ring structure of section 3.2.2, without the score strip in memory.
 // P is recomputed from Q, K and the forward's LSE: P = exp(s QK^T - LSE).
 //
-//   preprocess: the row terms -D = -rowsum(dO o O) and -LSE log2e, and Qs = bf16(Q * s * log2 e);
-//     a kernel of its own for the step-level entry point, the prologue of the dQ kernel in rsa_backward.
+//   preprocess: the row terms -D = -rowsum(dO o O) and -LSE log2e; a kernel of its own for the
+//     step-level entry point, the prologue of the dQ kernel in rsa_backward.
+//   Both kernels recompute P = exp2(s log2e Q K^T - LSE log2e) with the factor s log2e folded into
+//   the operand they hold in registers, rounded to bf16: K in the dK/dV kernel, Q in the dQ kernel.
 //   dkdv kernel: a work-group owns 4*32 keys and walks the query tiles of every
 //     simulated rank, starting with the rank that holds those keys (ring
 //     order); the sum over ranks that the ring would all-reduce is its loop.
-//       S' = Qs K^T - LSE log2e, dP' = dO V^T - D   (A: Qs / dO rows from LDS; B: K / V registers;
+//       S' = Q Ks^T - LSE log2e, dP' = dO V^T - D   (A: Q / dO rows from LDS; B: Ks / V registers;
 //                                                    the row terms are the accumulators' start)
 //       P = exp2(S'), dS = P o dP'
-//       dV^T += dO^T P, dK^T += Qs^T dS   (A operand: LDS transpose reads; B: P / dS registers)
+//       dV^T += dO^T P, dK^T += Q^T dS   (A operand: LDS transpose reads; B: P / dS registers)
 //   dq kernel: a work-group owns 4*R query rows and walks the K/V tiles in ring
 //     order (the paper's second K ring pass):
-//       S'^T = K Qs^T - LSE log2e, dP'^T = V dO^T - D, dS^T = P^T o dP'^T, dQ^T += K^T dS^T
+//       S'^T = K Qs^T - LSE log2e (Qs = bf16(Q * scale * log2 e), formed in registers),
+//       dP'^T = V dO^T - D, dS^T = P^T o dP'^T, dQ^T += K^T dS^T
 #include "rsa_fused_tile.h"
 #include "rsa_kernels.h"
 
 namespace rsa {
 
 struct BwdArgs {
-  const uint16_t *Q, *Qs, *K, *V, *dO;  // Qs = bf16(Q * scale * log2 e)
+  const uint16_t *Q, *K, *V, *dO;
   const float *nL, *nD;                 // -LSE log2e and -D per query row
-  // dQ kernel with the preprocess folded in: it forms the row terms and Qs from O and LSE
-  // itself and leaves them in nL_out, nD_out, Qs_out for the dK/dV kernel that follows
+  // dQ kernel with the preprocess folded in: it forms the row terms from O and LSE
+  // itself and leaves them in nL_out, nD_out for the dK/dV kernel that follows
   const uint16_t *O;
   const float *LSE;
   float *nL_out, *nD_out;
-  uint16_t *Qs_out;
   uint16_t *dQ, *dK, *dV;
   // fp32 partial sums per split: dV then dK of the dK/dV kernel with a split query walk,
   // dQ of the dQ kernel with a split key walk
@@ -39,12 +41,10 @@ struct BwdArgs {
 };
 
 // ------------------------------------------------------------- preprocess ---
-// nD_i = -sum_a dO_ia O_ia, nL_i = -LSE_i log2e and Qs = bf16(Q * scale * log2 e):
-// 8 lanes x 8 elements per row.
+// nD_i = -sum_a dO_ia O_ia and nL_i = -LSE_i log2e: 8 lanes x 8 elements per row.
 __global__ void __launch_bounds__(256) bwd_preprocess_kernel(const uint16_t *dO, const uint16_t *O,
-                                                             const uint16_t *Q, const float *LSE,
-                                                             float *nD, float *nL, uint16_t *Qs,
-                                                             int64_t rows, float cl2) {
+                                                             const float *LSE, float *nD, float *nL,
+                                                             int64_t rows) {
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t row = gid >> 3;
   const int sub = (int)(gid & 7);
@@ -58,8 +58,6 @@ __global__ void __launch_bounds__(256) bwd_preprocess_kernel(const uint16_t *dO,
       acc = fmaf(bf16_to_f32(x[e] & 0xffffu), bf16_to_f32(y[e] & 0xffffu), acc);
       acc = fmaf(bf16_to_f32(x[e] >> 16), bf16_to_f32(y[e] >> 16), acc);
     }
-    const bf16x8 q = *reinterpret_cast<const bf16x8 *>(Q + off);
-    *reinterpret_cast<bf16x8 *>(Qs + off) = scale_bf16x8(q, cl2);
   }
   acc += __shfl_xor(acc, 1);
   acc += __shfl_xor(acc, 2);
@@ -71,14 +69,14 @@ __global__ void __launch_bounds__(256) bwd_preprocess_kernel(const uint16_t *dO,
 }
 
 // ------------------------------------------------------------------ dK, dV ---
-// Work-group: 4 waves x 32 keys.  K and V of a wave's keys stay in registers as B
-// operands; the work-group walks the query rows in stages of NQ tiles of 64 rows of Qs
-// (pre-scaled Q) and dO, double-buffered in LDS and filled by direct global->LDS loads
-// (no staging registers), one barrier per stage.
+// Work-group: 4 waves x 32 keys.  Ks = bf16(K * scale * log2 e) and V of a wave's keys stay in
+// registers as B operands; the work-group walks the query rows in stages of NQ tiles of 64 rows
+// of Q and dO, double-buffered in LDS and filled by direct global->LDS loads (no staging
+// registers), one barrier per stage.
 // The row terms of the softmax backward ride on the accumulator init of the MFMAs:
-//   S'  = Qs K^T - LSE log2e   (so P = exp2(S') needs no multiply or subtract)
+//   S'  = Q Ks^T - LSE log2e   (so P = exp2(S') needs no multiply or subtract)
 //   dP' = dO V^T - D           (so dS = P dP' is one multiply)
-// dK is formed from Qs as well: dK = ln2 * sum_i dS_ij Qs_i.
+// and dK = scale * sum_i dS_ij Q_i.
 template <int NQ, bool CAUSAL>
 __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
   constexpr int KW = 32;      // keys per wave
@@ -86,7 +84,7 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
   // The two stage buffers are separate objects, each addressed by name, so that the
   // compiler knows a direct load into one cannot alias the LDS reads of the other.
   struct Stage {
-    unsigned char Qs[NQ][kTileBytes], dOs[NQ][kTileBytes];
+    unsigned char Qt[NQ][kTileBytes], dOs[NQ][kTileBytes];
     float lse[NQ][64], d[NQ][64];
   };
   __shared__ __attribute__((aligned(16))) Stage stage0, stage1;
@@ -99,22 +97,22 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
   const int64_t key0 = (wg % a.tiles_per_head) * BK;  // first key of the work-group
   const int64_t wkey0 = key0 + wave * KW;             // first key of this wave
 
-  const uint16_t *Qh = a.Qs + head * a.Lq * 64;
+  const uint16_t *Qh = a.Q + head * a.Lq * 64;
   const uint16_t *dOh = a.dO + head * a.Lq * 64;
   const uint16_t *Kh = a.K + head * a.L * 64;
   const uint16_t *Vh = a.V + head * a.L * 64;
   const float *nLh = a.nL + head * a.Lq;
   const float *nDh = a.nD + head * a.Lq;
 
-  // K and V rows of this wave as B operands: lane (col, half) holds row
-  // key = wkey0 + col, elements dk*16 + half*8 .. +8.
+  // K (times scale * log2 e, rounded to bf16) and V rows of this wave as B operands:
+  // lane (col, half) holds row key = wkey0 + col, elements dk*16 + half*8 .. +8.
   bf16x8 kreg[4], vreg[4];
   {
     int64_t key = wkey0 + col;
     if (key >= a.L) key = a.L - 1;  // ragged tail: clamped here, not stored below
 #pragma unroll
     for (int dk = 0; dk < 4; ++dk) {
-      kreg[dk] = *reinterpret_cast<const bf16x8 *>(Kh + key * 64 + dk * 16 + half * 8);
+      kreg[dk] = scale_bf16x8(*reinterpret_cast<const bf16x8 *>(Kh + key * 64 + dk * 16 + half * 8), a.cl2);
       vreg[dk] = *reinterpret_cast<const bf16x8 *>(Vh + key * 64 + dk * 16 + half * 8);
     }
   }
@@ -161,7 +159,7 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
       int qt = st * NQ + u;
       if (qt >= nqt) qt = nqt - 1;  // past the last tile: refetch it (never used)
       const int64_t r0 = (int64_t)qt * 64;
-      dma.load(Qh + r0 * 64, sn.Qs[u]);
+      dma.load(Qh + r0 * 64, sn.Qt[u]);
       dma.load(dOh + r0 * 64, sn.dOs[u]);
       // the 64 row terms of the tile, one dword per lane: waves 0/1 fetch -LSE log2e, 2/3 fetch -D
       if ((wave & 1) == (u & 1)) {
@@ -206,7 +204,7 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
       }
 #pragma unroll
       for (int dk = 0; dk < 4; ++dk) {
-        qa[qb][dk] = tl.read_rows(sc.Qs[u], qb * 32, dk);
+        qa[qb][dk] = tl.read_rows(sc.Qt[u], qb * 32, dk);
         ga[qb][dk] = tl.read_rows(sc.dOs[u], qb * 32, dk);
       }
     };
@@ -248,14 +246,14 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
             sf[qb * 2 + w2] = __builtin_bit_cast(bf16x8, x);
           }
         };
-        bf16x8 gt[2][2][2], qt2[2][2][2];  // [qb][kk & 1][db]: dO^T and Qs^T fragments
+        bf16x8 gt[2][2][2], qt2[2][2][2];  // [qb][kk & 1][db]: dO^T and Q^T fragments
         auto fetch_t = [&](int qb) __attribute__((always_inline)) {
 #pragma unroll
           for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
             for (int db = 0; db < 2; ++db) {
               gt[qb][k2][db] = tl.read_cols(sc.dOs[u], (qb * 2 + k2) * 16, db);
-              qt2[qb][k2][db] = tl.read_cols(sc.Qs[u], (qb * 2 + k2) * 16, db);
+              qt2[qb][k2][db] = tl.read_cols(sc.Qt[u], (qb * 2 + k2) * 16, db);
             }
         };
         auto g34 = [&](int qb) __attribute__((always_inline)) {
@@ -308,8 +306,8 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
           const int off = db * 32 + g * 8 + half * 4;
           const f32x4 w = {dv[db][g * 4 + 0], dv[db][g * 4 + 1], dv[db][g * 4 + 2], dv[db][g * 4 + 3]};
           *reinterpret_cast<f32x4 *>(pv + off) = w;
-          const f32x4 x = {dk_[db][g * 4 + 0] * kLn2, dk_[db][g * 4 + 1] * kLn2, dk_[db][g * 4 + 2] * kLn2,
-                           dk_[db][g * 4 + 3] * kLn2};
+          const f32x4 x = {dk_[db][g * 4 + 0] * a.scale, dk_[db][g * 4 + 1] * a.scale,
+                           dk_[db][g * 4 + 2] * a.scale, dk_[db][g * 4 + 3] * a.scale};
           *reinterpret_cast<f32x4 *>(pk + off) = x;
         }
     }
@@ -318,9 +316,9 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
 
   // the wave's 32 x 64 blocks of dV and dK leave through its own LDS tile as whole 128-byte rows
   // (every wave is past the loop's last barrier and no load is in flight: the buffers are free)
-  unsigned char *ot = wave < 2 ? stage0.Qs[wave] : stage0.dOs[wave - 2];
+  unsigned char *ot = wave < 2 ? stage0.Qt[wave] : stage0.dOs[wave - 2];
   stage_block_T(ot, 0, dv[0], dv[1], 1.0f, lane);
-  stage_block_T(ot, 32, dk_[0], dk_[1], kLn2, lane);
+  stage_block_T(ot, 32, dk_[0], dk_[1], a.scale, lane);
   flush_rows<32>(ot, 0, a.dV + (head * a.L + wkey0) * 64, a.L - wkey0, lane);
   flush_rows<32>(ot, 32, a.dK + (head * a.L + wkey0) * 64, a.L - wkey0, lane);
 }
@@ -361,8 +359,7 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   const uint16_t *Kh = a.K + head * a.L * 64;
   const uint16_t *Vh = a.V + head * a.L * 64;
 
-  // Q (pre-multiplied by scale * log2 e, rounded to bf16 exactly as the preprocess
-  // kernel does) and dO as B operands; -LSE log2e and -D of the lane's row, broadcast
+  // Q (times scale * log2 e, rounded to bf16) and dO as B operands; -LSE log2e and -D of the lane's row, broadcast
   // over an accumulator, are what S'^T and dP'^T start from.
   bf16x8 qreg[QB][4], greg[QB][4];
   int64_t qrow[QB];
@@ -401,9 +398,6 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
           a.nD_out[head * a.Lq + r] = dd;
           a.nL_out[head * a.Lq + r] = l2;
         }
-#pragma unroll
-        for (int dk = 0; dk < 4; ++dk)
-          *reinterpret_cast<bf16x8 *>(a.Qs_out + (head * a.Lq + r) * 64 + dk * 16 + half * 8) = qreg[qb][dk];
       }
     } else {
       l2 = a.nL[head * a.Lq + qrow[qb]];
@@ -572,29 +566,28 @@ __global__ void __launch_bounds__(256) qsplit_reduce_kernel(const float *part, u
   reinterpret_cast<u32x2 *>(out)[i] = w;
 }
 
-static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const void *Qs,
-                             const void *K, const void *V, const float *nL, const float *nD,
-                             void *dQ, void *dK, void *dV) {
+static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const void *K,
+                             const void *V, const float *nL, const float *nD, void *dQ, void *dK,
+                             void *dV) {
   BwdArgs a;
-  a.Q = (const uint16_t *)Q; a.Qs = (const uint16_t *)Qs;
+  a.Q = (const uint16_t *)Q;
   a.K = (const uint16_t *)K; a.V = (const uint16_t *)V;
   a.dO = (const uint16_t *)dO; a.nL = nL; a.nD = nD;
   a.dQ = (uint16_t *)dQ; a.dK = (uint16_t *)dK; a.dV = (uint16_t *)dV;
   a.part = nullptr;
-  a.O = nullptr; a.LSE = nullptr; a.nL_out = nullptr; a.nD_out = nullptr; a.Qs_out = nullptr;
+  a.O = nullptr; a.LSE = nullptr; a.nL_out = nullptr; a.nD_out = nullptr;
   a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.map = make_row_map(d);
   a.N = d.N; a.cl2 = d.scale * kLog2e; a.scale = d.scale;
   a.tiles_per_head = 0;
   return a;
 }
 
-hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, const void *Q,
-                                const float *LSE, float *nD, float *nL, void *Qs, hipStream_t st) {
+hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, const float *LSE,
+                                float *nD, float *nL, hipStream_t st) {
   const int64_t rows = (int64_t)d.B * d.Z * d.Lq;
   dim3 grid((unsigned)((rows * 8 + 255) / 256));
   hipLaunchKernelGGL(bwd_preprocess_kernel, grid, dim3(256), 0, st, (const uint16_t *)dO,
-                     (const uint16_t *)O, (const uint16_t *)Q, LSE, nD, nL, (uint16_t *)Qs, rows,
-                     d.scale * kLog2e);
+                     (const uint16_t *)O, LSE, nD, nL, rows);
   return hipGetLastError();
 }
 
@@ -606,10 +599,10 @@ int fused_bwd_dkdv_splits(const Dims &d) {
   return s < 2 ? 1 : (int)s;
 }
 
-hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Qs, const void *K,
+hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Q, const void *K,
                           const void *V, const float *nL, const float *nD, void *dK, void *dV,
                           hipStream_t st, float *part, int splits) {
-  BwdArgs a = make_bwd_args(d, dO, nullptr, Qs, K, V, nL, nD, nullptr, dK, dV);
+  BwdArgs a = make_bwd_args(d, dO, Q, K, V, nL, nD, nullptr, dK, dV);
   a.tiles_per_head = (int)((d.L + 127) / 128);
   a.part = part;
   if (!part) splits = 1;
@@ -639,7 +632,7 @@ static hipError_t dq_reduce(const Dims &d, const float *part, void *dQ, int spli
 hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void *K, const void *V,
                         const float *nL, const float *nD, void *dQ, hipStream_t st, float *part,
                         int splits) {
-  BwdArgs a = make_bwd_args(d, dO, Q, nullptr, K, V, nL, nD, dQ, nullptr, nullptr);
+  BwdArgs a = make_bwd_args(d, dO, Q, K, V, nL, nD, dQ, nullptr, nullptr);
   a.tiles_per_head = (int)((d.Lq + 127) / 128);
   a.part = part;
   if (!part) splits = 1;
@@ -653,12 +646,12 @@ hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void
   return dq_reduce(d, part, dQ, splits, st);
 }
 
-// The dQ kernel with the preprocess in its prologue: also writes -D, -LSE log2e and Qs.
+// The dQ kernel with the preprocess in its prologue: also writes -D and -LSE log2e.
 hipError_t fused_bwd_dq_pre(const Dims &d, const void *dO, const void *Q, const void *K, const void *V,
-                            const void *O, const float *LSE, float *nL, float *nD, void *Qs, void *dQ,
+                            const void *O, const float *LSE, float *nL, float *nD, void *dQ,
                             hipStream_t st, float *part, int splits) {
-  BwdArgs a = make_bwd_args(d, dO, Q, nullptr, K, V, nullptr, nullptr, dQ, nullptr, nullptr);
-  a.O = (const uint16_t *)O; a.LSE = LSE; a.nL_out = nL; a.nD_out = nD; a.Qs_out = (uint16_t *)Qs;
+  BwdArgs a = make_bwd_args(d, dO, Q, K, V, nullptr, nullptr, dQ, nullptr, nullptr);
+  a.O = (const uint16_t *)O; a.LSE = LSE; a.nL_out = nL; a.nD_out = nD;
   a.tiles_per_head = (int)((d.Lq + 127) / 128);
   a.part = part;
   if (!part) splits = 1;
@@ -674,13 +667,13 @@ hipError_t fused_bwd_dq_pre(const Dims &d, const void *dO, const void *Q, const 
 
 hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const void *K,
                           const void *V, const void *O, const float *LSE, void *dQ, void *dK,
-                          void *dV, float *nD, float *nL, void *Qs, hipStream_t st, float *part,
+                          void *dV, float *nD, float *nL, hipStream_t st, float *part,
                           int qsplits, int ksplits) {
-  // the dQ kernel first: its prologue forms the row terms and Qs that the dK/dV kernel reads;
+  // the dQ kernel first: its prologue forms the row terms that the dK/dV kernel reads;
   // the two kernels' partial sums share `part`, one after the other
-  hipError_t e = fused_bwd_dq_pre(d, dO, Q, K, V, O, LSE, nL, nD, Qs, dQ, st, part, ksplits);
+  hipError_t e = fused_bwd_dq_pre(d, dO, Q, K, V, O, LSE, nL, nD, dQ, st, part, ksplits);
   if (e != hipSuccess) return e;
-  return fused_bwd_dkdv(d, dO, Qs, K, V, nL, nD, dK, dV, st, part, qsplits);
+  return fused_bwd_dkdv(d, dO, Q, K, V, nL, nD, dK, dV, st, part, qsplits);
 }
 
 }  // namespace rsa

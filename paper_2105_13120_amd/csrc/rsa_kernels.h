@@ -39,13 +39,13 @@ hipError_t zero_f32(float *p, int64_t n, hipStream_t st);
 int fused_key_splits(const Dims &d);
 hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void *V, void *O,
                          float *LSE, hipStream_t st, float *part, int splits);
-// nD = -rowsum(dO o O) and nL = -LSE log2e, (B,Z,Lq) fp32; Qs = bf16(Q * scale * log2 e) (B,Z,Lq,64)
-hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, const void *Q,
-                                const float *LSE, float *nD, float *nL, void *Qs, hipStream_t st);
+// nD = -rowsum(dO o O) and nL = -LSE log2e, (B,Z,Lq) fp32
+hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, const float *LSE,
+                                float *nD, float *nL, hipStream_t st);
 // part / splits: optional split of the walk over the query rows (few keys, many rows): fp32
 // partial dV and dK, 2 * splits * B*Z*L*64 floats, added up in a fixed order; nullptr / 1: none
 int fused_bwd_dkdv_splits(const Dims &d);
-hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Qs, const void *K,
+hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Q, const void *K,
                           const void *V, const float *nL, const float *nD, void *dK, void *dV,
                           hipStream_t st, float *part = nullptr, int splits = 1);
 // part / splits: the split key walk again, fp32 partial dQ, splits * B*Z*Lq * 64 floats
@@ -54,7 +54,7 @@ hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void
                         float *part = nullptr, int splits = 1);
 hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const void *K,
                           const void *V, const void *O, const float *LSE, void *dQ, void *dK,
-                          void *dV, float *nD, float *nL, void *Qs, hipStream_t st,
+                          void *dV, float *nD, float *nL, hipStream_t st,
                           float *part = nullptr, int qsplits = 1, int ksplits = 1);
 
 // --- the linear maps around RSA (Table 2, rows Q/K/V and Linear), bf16, A = 64 ---

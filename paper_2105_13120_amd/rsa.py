@@ -74,8 +74,8 @@ def lib():
         L.rsa_dq_step.argtypes = [dp, i, i, vp, vp, vp, i, vp]
         L.rsa_dk_step.argtypes = [dp, i, i, vp, vp, vp, i, vp]
         L.rsa_store.argtypes = [dp, vp, vp, sz, vp]
-        L.rsa_bwd_preprocess.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
-        L.rsa_bwd_dkdv.argtypes = [dp] + [vp] * 7
+        L.rsa_bwd_preprocess.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        L.rsa_bwd_dkdv.argtypes = [dp] + [vp] * 8
         L.rsa_bwd_dq.argtypes = [dp] + [vp] * 7
         L.rsa_proj_workspace_bytes.argtypes = [dp, i]
         L.rsa_qkv_proj.argtypes = [dp, i] + [vp] * 6
@@ -214,14 +214,14 @@ def store(desc, src, dst):
     _check(lib().rsa_store(ctypes.byref(desc), _p(src), _p(dst), src.numel(), _stream()))
 
 
-def bwd_preprocess(desc, dO, O, Q, LSE, ws):
-    _check(lib().rsa_bwd_preprocess(ctypes.byref(desc), _p(dO), _p(O), _p(Q), _p(LSE), _p(ws),
+def bwd_preprocess(desc, dO, O, LSE, ws):
+    _check(lib().rsa_bwd_preprocess(ctypes.byref(desc), _p(dO), _p(O), _p(LSE), _p(ws),
                                     ws.numel(), _stream()))
 
 
-def bwd_dkdv(desc, dO, K, V, ws, dK, dV):
-    _check(lib().rsa_bwd_dkdv(ctypes.byref(desc), _p(dO), _p(K), _p(V), _p(ws), _p(dK), _p(dV),
-                              _stream()))
+def bwd_dkdv(desc, dO, Q, K, V, ws, dK, dV):
+    _check(lib().rsa_bwd_dkdv(ctypes.byref(desc), _p(dO), _p(Q), _p(K), _p(V), _p(ws), _p(dK),
+                              _p(dV), _stream()))
 
 
 def bwd_dq(desc, dO, Q, K, V, ws, dQ):

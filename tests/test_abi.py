@@ -77,13 +77,13 @@ def test_workspace_sizes_follow_table2():
     strip = 2 * 3 * 128 * 512
     assert rsa.workspace_bytes(d, False) >= strip * 4 + strip * 2
     assert rsa.workspace_bytes(desc(), False) == 0            # fused forward: no strip
-    assert rsa.workspace_bytes(desc(), True) == 2 * (1 * 2 * 256 * 4) + 1 * 2 * 256 * 64 * 2   # row terms and Qs
+    assert rsa.workspace_bytes(desc(), True) == 2 * (1 * 2 * 256 * 4)   # the two row terms, fp32
     assert rsa.workspace_bytes(desc(N=3), True) == 0          # invalid descriptor
     # one rank's share of a long sequence: the key walk is split, fp32 partial results per split
     d = desc(B=1, Z=2, L=4096, N=4, rank_begin=3, rank_end=4)
     rows, splits = 1 * 2 * 1024, 4
     assert rsa.workspace_bytes(d, False) == splits * rows * (64 + 2) * 4
-    assert rsa.workspace_bytes(d, True) == 2 * rows * 4 + rows * 64 * 2 + splits * rows * 64 * 4
+    assert rsa.workspace_bytes(d, True) == 2 * rows * 4 + splits * rows * 64 * 4
     for s in range(-5, 1):
         assert rsa.strerror(s)
 

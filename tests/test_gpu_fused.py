@@ -220,8 +220,8 @@ def test_backward_parts_equal_the_whole():
     dQ, dK, dV = rsa.backward(desc, dO, Q, K, V, O, LSE)
     ws = torch.empty(rsa.workspace_bytes(desc, True), dtype=torch.uint8, device="cuda")
     dQ2, dK2, dV2 = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
-    rsa.bwd_preprocess(desc, dO, O, Q, LSE, ws)
-    rsa.bwd_dkdv(desc, dO, K, V, ws, dK2, dV2)
+    rsa.bwd_preprocess(desc, dO, O, LSE, ws)
+    rsa.bwd_dkdv(desc, dO, Q, K, V, ws, dK2, dV2)
     rsa.bwd_dq(desc, dO, Q, K, V, ws, dQ2)
     torch.cuda.synchronize()
     for name, a, b in (("dQ", dQ, dQ2), ("dK", dK, dK2), ("dV", dV, dV2)):
