@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="bert_large",
                     choices=["bert_base", "bert_large", "long_32k", "rank15_64k_causal",
-                             "causal_ring_32k", "zigzag_rank0_64k_causal"])
+                             "causal_ring_32k", "zigzag_rank0_64k_causal", "wide_heads_8k"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all", action="store_true", help="(default) also time the other workloads briefly")
     ap.add_argument("--only", action="store_true", help="time the chosen workload only (no extra legs)")
@@ -305,7 +305,7 @@ def main():
     if "others" in legs:
         other = {}
         for name in ("bert_base", "bert_large", "long_32k", "rank15_64k_causal", "causal_ring_32k",
-                     "zigzag_rank0_64k_causal"):
+                     "zigzag_rank0_64k_causal", "wide_heads_8k"):
             if name == cfg.name:
                 continue
             c2 = inputs.CONFIGS[name]

@@ -18,8 +18,8 @@ int validate(const rsa_desc *d, Dims *out) {
   if (d->flags & ~(RSA_MODE_STAGED | RSA_OWN_ZIGZAG)) return RSA_ERR_UNSUPPORTED;
   const int mode = (int)(d->flags & RSA_MODE_STAGED);
   const int zigzag = (d->flags & RSA_OWN_ZIGZAG) ? 1 : 0;
-  // the fused kernels are written for bf16 heads of 64 elements
-  if (mode == RSA_MODE_FUSED && (d->dtype != RSA_BF16 || d->A != 64)) return RSA_ERR_UNSUPPORTED;
+  // the fused kernels are written for bf16 heads of 64 or 128 elements
+  if (mode == RSA_MODE_FUSED && (d->dtype != RSA_BF16 || (d->A != 64 && d->A != 128))) return RSA_ERR_UNSUPPORTED;
   const int64_t c = d->L / d->N;
   if (c % 64 != 0) return RSA_ERR_UNSUPPORTED;
   if (zigzag && (mode == RSA_MODE_STAGED || c % 128 != 0)) return RSA_ERR_UNSUPPORTED;
@@ -74,8 +74,8 @@ size_t workspace_bytes(const Dims &d, int dtype, int pass) {
   if (d.mode == RSA_MODE_STAGED) return staged_layout(d, dtype, pass).total;
   const size_t rows = (size_t)d.B * d.Z * d.Lq;
   const int ks = rsa::fused_key_splits(d);
-  if (pass == 1) return fused_bwd_base(d) + (ks > 1 ? align256(ks * rows * 64 * 4) : 0);
-  return ks > 1 ? align256(ks * rows * 66 * 4) : 0;
+  if (pass == 1) return fused_bwd_base(d) + (ks > 1 ? align256(ks * rows * d.A * 4) : 0);
+  return ks > 1 ? align256(ks * rows * (d.A + 2) * 4) : 0;
 }
 // where the split walks' partial sums start in the backward workspace
 inline float *fused_part(const Dims &d, void *ws) {
@@ -345,7 +345,7 @@ namespace {
 int proj_check(const rsa_desc *d, int32_t H, Dims *dm) {
   int rc = validate(d, dm);
   if (rc != RSA_OK) return rc;
-  if (dm->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16) return RSA_ERR_UNSUPPORTED;
+  if (dm->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16 || dm->A != 64) return RSA_ERR_UNSUPPORTED;
   if (H < 64) return RSA_ERR_SHAPE;
   if (H % 64 != 0) return RSA_ERR_UNSUPPORTED;
   // the GEMM kernel indexes rows and columns of its operands with 32 bits
@@ -409,7 +409,7 @@ namespace {
 int linformer_dims(const rsa_desc *d, int32_t Kp, Dims *own, Dims *att) {
   int rc = validate(d, own);
   if (rc != RSA_OK) return rc;
-  if (own->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16 || own->zigzag || own->causal)
+  if (own->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16 || own->A != 64 || own->zigzag || own->causal)
     return RSA_ERR_UNSUPPORTED;
   if (Kp < 64) return RSA_ERR_SHAPE;
   if (Kp % 64 != 0) return RSA_ERR_UNSUPPORTED;

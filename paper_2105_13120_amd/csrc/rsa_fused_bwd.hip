@@ -41,22 +41,24 @@ struct BwdArgs {
 };
 
 // ------------------------------------------------------------- preprocess ---
-// nD_i = -sum_a dO_ia O_ia and nL_i = -LSE_i log2e: 8 lanes x 8 elements per row.
+// nD_i = -sum_a dO_ia O_ia and nL_i = -LSE_i log2e: 8 lanes per row, 8 elements of every 64 each.
 __global__ void __launch_bounds__(256) bwd_preprocess_kernel(const uint16_t *dO, const uint16_t *O,
                                                              const float *LSE, float *nD, float *nL,
-                                                             int64_t rows) {
+                                                             int64_t rows, int A) {
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t row = gid >> 3;
   const int sub = (int)(gid & 7);
   float acc = 0.f;
   if (row < rows) {
-    const int64_t off = row * 64 + sub * 8;
-    const u32x4 x = *reinterpret_cast<const u32x4 *>(dO + off);
-    const u32x4 y = *reinterpret_cast<const u32x4 *>(O + off);
+    for (int a0 = 0; a0 < A; a0 += 64) {
+      const int64_t off = row * A + a0 + sub * 8;
+      const u32x4 x = *reinterpret_cast<const u32x4 *>(dO + off);
+      const u32x4 y = *reinterpret_cast<const u32x4 *>(O + off);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      acc = fmaf(bf16_to_f32(x[e] & 0xffffu), bf16_to_f32(y[e] & 0xffffu), acc);
-      acc = fmaf(bf16_to_f32(x[e] >> 16), bf16_to_f32(y[e] >> 16), acc);
+      for (int e = 0; e < 4; ++e) {
+        acc = fmaf(bf16_to_f32(x[e] & 0xffffu), bf16_to_f32(y[e] & 0xffffu), acc);
+        acc = fmaf(bf16_to_f32(x[e] >> 16), bf16_to_f32(y[e] >> 16), acc);
+      }
     }
   }
   acc += __shfl_xor(acc, 1);
@@ -77,14 +79,17 @@ __global__ void __launch_bounds__(256) bwd_preprocess_kernel(const uint16_t *dO,
 //   S'  = Q Ks^T - LSE log2e   (so P = exp2(S') needs no multiply or subtract)
 //   dP' = dO V^T - D           (so dS = P dP' is one multiply)
 // and dK = scale * sum_i dS_ij Q_i.
-template <int NQ, bool CAUSAL>
-__global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
+// A head of 128 is two halves of 64 (AH = 2): two LDS tiles per 64 rows, S' and dP' contract over
+// both, dV and dK have twice the accumulators, and the kernel runs one wave per SIMD.
+template <int NQ, bool CAUSAL, int AH>
+__global__ void __launch_bounds__(256, AH == 2 ? 1 : 2) fused_bwd_dkdv_kernel(BwdArgs a) {
   constexpr int KW = 32;      // keys per wave
   constexpr int BK = 4 * KW;  // keys per work-group
+  constexpr int A = 64 * AH;
   // The two stage buffers are separate objects, each addressed by name, so that the
   // compiler knows a direct load into one cannot alias the LDS reads of the other.
   struct Stage {
-    unsigned char Qt[NQ][kTileBytes], dOs[NQ][kTileBytes];
+    unsigned char Qt[NQ][AH][kTileBytes], dOs[NQ][AH][kTileBytes];
     float lse[NQ][64], d[NQ][64];
   };
   __shared__ __attribute__((aligned(16))) Stage stage0, stage1;
@@ -97,31 +102,31 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
   const int64_t key0 = (wg % a.tiles_per_head) * BK;  // first key of the work-group
   const int64_t wkey0 = key0 + wave * KW;             // first key of this wave
 
-  const uint16_t *Qh = a.Q + head * a.Lq * 64;
-  const uint16_t *dOh = a.dO + head * a.Lq * 64;
-  const uint16_t *Kh = a.K + head * a.L * 64;
-  const uint16_t *Vh = a.V + head * a.L * 64;
+  const uint16_t *Qh = a.Q + head * a.Lq * A;
+  const uint16_t *dOh = a.dO + head * a.Lq * A;
+  const uint16_t *Kh = a.K + head * a.L * A;
+  const uint16_t *Vh = a.V + head * a.L * A;
   const float *nLh = a.nL + head * a.Lq;
   const float *nDh = a.nD + head * a.Lq;
 
   // K (times scale * log2 e, rounded to bf16) and V rows of this wave as B operands:
   // lane (col, half) holds row key = wkey0 + col, elements dk*16 + half*8 .. +8.
-  bf16x8 kreg[4], vreg[4];
+  bf16x8 kreg[4 * AH], vreg[4 * AH];
   {
     int64_t key = wkey0 + col;
     if (key >= a.L) key = a.L - 1;  // ragged tail: clamped here, not stored below
 #pragma unroll
-    for (int dk = 0; dk < 4; ++dk) {
-      kreg[dk] = scale_bf16x8(*reinterpret_cast<const bf16x8 *>(Kh + key * 64 + dk * 16 + half * 8), a.cl2);
-      vreg[dk] = *reinterpret_cast<const bf16x8 *>(Vh + key * 64 + dk * 16 + half * 8);
+    for (int dk = 0; dk < 4 * AH; ++dk) {
+      kreg[dk] = scale_bf16x8(*reinterpret_cast<const bf16x8 *>(Kh + key * A + dk * 16 + half * 8), a.cl2);
+      vreg[dk] = *reinterpret_cast<const bf16x8 *>(Vh + key * A + dk * 16 + half * 8);
     }
   }
 
   const TileLanes tl(lane);
 
-  f32x16 dv[2], dk_[2];  // [db], transposed: rows = head dim, columns = keys
+  f32x16 dv[2 * AH], dk_[2 * AH];  // [db], transposed: rows = head dim, columns = keys
 #pragma unroll
-  for (int db = 0; db < 2; ++db)
+  for (int db = 0; db < 2 * AH; ++db)
 #pragma unroll
     for (int v = 0; v < 16; ++v) { dv[db][v] = 0.f; dk_[db][v] = 0.f; }
 
@@ -159,8 +164,16 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
       int qt = st * NQ + u;
       if (qt >= nqt) qt = nqt - 1;  // past the last tile: refetch it (never used)
       const int64_t r0 = (int64_t)qt * 64;
-      dma.load(Qh + r0 * 64, sn.Qt[u]);
-      dma.load(dOh + r0 * 64, sn.dOs[u]);
+#pragma unroll
+      for (int ah = 0; ah < AH; ++ah) {
+        if constexpr (AH == 1) {
+          dma.load(Qh + r0 * 64, sn.Qt[u][0]);
+          dma.load(dOh + r0 * 64, sn.dOs[u][0]);
+        } else {
+          dma.load(Qh + r0 * A + ah * 64, sn.Qt[u][ah], A);
+          dma.load(dOh + r0 * A + ah * 64, sn.dOs[u][ah], A);
+        }
+      }
       // the 64 row terms of the tile, one dword per lane: waves 0/1 fetch -LSE log2e, 2/3 fetch -D
       if ((wave & 1) == (u & 1)) {
         if (wave < 2) lds_dma4(nLh + r0 + lane, sn.lse[u]);
@@ -186,7 +199,7 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
     // stream, and an LDS read costs its full latency unless issued a phase early, so the
     // phases are fenced, every read after the tile's first is issued one phase before its
     // use, and the compiler interleaves inside a phase.
-    bf16x8 qa[2][4], ga[2][4];
+    bf16x8 qa[2][4 * AH], ga[2][4 * AH];
     f32x16 sacc[2], dpacc[2];
     const int qt0 = st_of(i) * NQ;
     auto active = [&](int u) {
@@ -203,9 +216,9 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
         for (int e = 0; e < 4; ++e) { sacc[qb][g * 4 + e] = l4[e]; dpacc[qb][g * 4 + e] = d4[e]; }
       }
 #pragma unroll
-      for (int dk = 0; dk < 4; ++dk) {
-        qa[qb][dk] = tl.read_rows(sc.Qt[u], qb * 32, dk);
-        ga[qb][dk] = tl.read_rows(sc.dOs[u], qb * 32, dk);
+      for (int dk = 0; dk < 4 * AH; ++dk) {
+        qa[qb][dk] = tl.read_rows(sc.Qt[u][dk >> 2], qb * 32, dk & 3);
+        ga[qb][dk] = tl.read_rows(sc.dOs[u][dk >> 2], qb * 32, dk & 3);
       }
     };
 #pragma unroll
@@ -216,7 +229,7 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
         bf16x8 pf[4], sf[4];  // [kk]: P and dS as B operands, k = query
         auto g12 = [&](int qb) __attribute__((always_inline)) {
 #pragma unroll
-          for (int dk = 0; dk < 4; ++dk) {
+          for (int dk = 0; dk < 4 * AH; ++dk) {
             sacc[qb] = mfma_32x32x16(qa[qb][dk], kreg[dk], sacc[qb]);
             dpacc[qb] = mfma_32x32x16(ga[qb][dk], vreg[dk], dpacc[qb]);
           }
@@ -246,21 +259,21 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
             sf[qb * 2 + w2] = __builtin_bit_cast(bf16x8, x);
           }
         };
-        bf16x8 gt[2][2][2], qt2[2][2][2];  // [qb][kk & 1][db]: dO^T and Q^T fragments
+        bf16x8 gt[2][2][2 * AH], qt2[2][2][2 * AH];  // [qb][kk & 1][db]: dO^T and Q^T fragments
         auto fetch_t = [&](int qb) __attribute__((always_inline)) {
 #pragma unroll
           for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-            for (int db = 0; db < 2; ++db) {
-              gt[qb][k2][db] = tl.read_cols(sc.dOs[u], (qb * 2 + k2) * 16, db);
-              qt2[qb][k2][db] = tl.read_cols(sc.Qt[u], (qb * 2 + k2) * 16, db);
+            for (int db = 0; db < 2 * AH; ++db) {
+              gt[qb][k2][db] = tl.read_cols(sc.dOs[u][db >> 1], (qb * 2 + k2) * 16, db & 1);
+              qt2[qb][k2][db] = tl.read_cols(sc.Qt[u][db >> 1], (qb * 2 + k2) * 16, db & 1);
             }
         };
         auto g34 = [&](int qb) __attribute__((always_inline)) {
 #pragma unroll
           for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-            for (int db = 0; db < 2; ++db) {
+            for (int db = 0; db < 2 * AH; ++db) {
               dv[db] = mfma_32x32x16(gt[qb][k2][db], pf[qb * 2 + k2], dv[db]);
               dk_[db] = mfma_32x32x16(qt2[qb][k2][db], sf[qb * 2 + k2], dk_[db]);
             }
@@ -296,11 +309,11 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
   if (gridDim.y > 1) {  // fp32 partial sums: [dV | dK][split][head][key][64]
     const int64_t heads = gridDim.x / a.tiles_per_head;
     const int64_t key = wkey0 + col;
-    float *pv = a.part + (((int64_t)blockIdx.y * heads + head) * a.L + key) * 64;
-    float *pk = pv + (int64_t)gridDim.y * heads * a.L * 64;
+    float *pv = a.part + (((int64_t)blockIdx.y * heads + head) * a.L + key) * A;
+    float *pk = pv + (int64_t)gridDim.y * heads * a.L * A;
     if (key < a.L) {
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
+      for (int db = 0; db < 2 * AH; ++db)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int off = db * 32 + g * 8 + half * 4;
@@ -316,22 +329,25 @@ __global__ void __launch_bounds__(256, 2) fused_bwd_dkdv_kernel(BwdArgs a) {
 
   // the wave's 32 x 64 blocks of dV and dK leave through its own LDS tile as whole 128-byte rows
   // (every wave is past the loop's last barrier and no load is in flight: the buffers are free)
-  unsigned char *ot = wave < 2 ? stage0.Qt[wave] : stage0.dOs[wave - 2];
-  stage_block_T(ot, 0, dv[0], dv[1], 1.0f, lane);
-  stage_block_T(ot, 32, dk_[0], dk_[1], a.scale, lane);
-  flush_rows<32>(ot, 0, a.dV + (head * a.L + wkey0) * 64, a.L - wkey0, lane);
-  flush_rows<32>(ot, 32, a.dK + (head * a.L + wkey0) * 64, a.L - wkey0, lane);
+  unsigned char *ot = wave < 2 ? stage0.Qt[wave][0] : stage0.dOs[wave - 2][0];
+#pragma unroll
+  for (int ah = 0; ah < AH; ++ah) {  // one half of the head at a time through the wave's tile
+    stage_block_T(ot, 0, dv[2 * ah], dv[2 * ah + 1], 1.0f, lane);
+    stage_block_T(ot, 32, dk_[2 * ah], dk_[2 * ah + 1], a.scale, lane);
+    flush_rows<32>(ot, 0, a.dV + (head * a.L + wkey0) * A + ah * 64, a.L - wkey0, lane, A);
+    flush_rows<32>(ot, 32, a.dK + (head * a.L + wkey0) * A + ah * 64, a.L - wkey0, lane, A);
+  }
 }
 
 // ---------------------------------------------------------------------- dQ ---
-template <int R, bool CAUSAL, bool PRE>
-__global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdArgs a) {
+template <int R, bool CAUSAL, bool PRE, int AH, int NK>  // NK: key tiles per stage (one barrier per stage)
+__global__ void __launch_bounds__(256, (R == 64 || AH == 2) ? 1 : 2) fused_bwd_dq_kernel(BwdArgs a) {
   constexpr int QB = R / 32;
   constexpr int BM = 4 * R;
-  constexpr int NK = 2;  // key tiles per stage (one barrier per stage)
+  constexpr int A = 64 * AH;  // a head of 128 is two halves of 64: two LDS tiles per 64 keys
   // two named stage buffers: see the dK/dV kernel
-  __shared__ __attribute__((aligned(16))) unsigned char Ks0[NK][kTileBytes], Ks1[NK][kTileBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char Vs0[NK][kTileBytes], Vs1[NK][kTileBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Ks0[NK][AH][kTileBytes], Ks1[NK][AH][kTileBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Vs0[NK][AH][kTileBytes], Vs1[NK][AH][kTileBytes];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -354,14 +370,14 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   const int tpc = (int)(a.c / kTileKeys);
   const int tpr = a.map.zigzag ? tpc / 2 : tpc;
 
-  const uint16_t *Qh = a.Q + head * a.Lq * 64;
-  const uint16_t *dOh = a.dO + head * a.Lq * 64;
-  const uint16_t *Kh = a.K + head * a.L * 64;
-  const uint16_t *Vh = a.V + head * a.L * 64;
+  const uint16_t *Qh = a.Q + head * a.Lq * A;
+  const uint16_t *dOh = a.dO + head * a.Lq * A;
+  const uint16_t *Kh = a.K + head * a.L * A;
+  const uint16_t *Vh = a.V + head * a.L * A;
 
   // Q (times scale * log2 e, rounded to bf16) and dO as B operands; -LSE log2e and -D of the lane's row, broadcast
   // over an accumulator, are what S'^T and dP'^T start from.
-  bf16x8 qreg[QB][4], greg[QB][4];
+  bf16x8 qreg[QB][4 * AH], greg[QB][4 * AH];
   int64_t qrow[QB];
   int64_t qtok[QB];  // global token index of the lane's row
   f32x16 negl[QB], negd[QB];
@@ -372,19 +388,19 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
     const int64_t blk = row0 + wave * R + qb * 32;  // the block of 32 rows is whole or absent
     qtok[qb] = a.map(blk < a.Lq ? blk : a.Lq - 32) + col;
 #pragma unroll
-    for (int dk = 0; dk < 4; ++dk) {
+    for (int dk = 0; dk < 4 * AH; ++dk) {
       qreg[qb][dk] = scale_bf16x8(
-          *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * 64 + dk * 16 + half * 8), a.cl2);
-      greg[qb][dk] = *reinterpret_cast<const bf16x8 *>(dOh + qrow[qb] * 64 + dk * 16 + half * 8);
+          *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * A + dk * 16 + half * 8), a.cl2);
+      greg[qb][dk] = *reinterpret_cast<const bf16x8 *>(dOh + qrow[qb] * A + dk * 16 + half * 8);
     }
     float l2, dd;
     if (PRE) {
-      // D = sum_a dO_a O_a: this lane holds 32 of the row's 64 elements, the lane 32 away the rest
+      // D = sum_a dO_a O_a: this lane holds half of the row's elements, the lane 32 away the rest
       float acc = 0.f;
 #pragma unroll
-      for (int dk = 0; dk < 4; ++dk) {
+      for (int dk = 0; dk < 4 * AH; ++dk) {
         const u32x4 x = __builtin_bit_cast(u32x4, greg[qb][dk]);
-        const u32x4 y = *reinterpret_cast<const u32x4 *>(a.O + (head * a.Lq + qrow[qb]) * 64 + dk * 16 + half * 8);
+        const u32x4 y = *reinterpret_cast<const u32x4 *>(a.O + (head * a.Lq + qrow[qb]) * A + dk * 16 + half * 8);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           acc = fmaf(bf16_to_f32(x[e] & 0xffffu), bf16_to_f32(y[e] & 0xffffu), acc);
@@ -413,9 +429,9 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
 
   const TileLanes tl(lane);
 
-  f32x16 dq[2][QB];
+  f32x16 dq[2 * AH][QB];
 #pragma unroll
-  for (int db = 0; db < 2; ++db)
+  for (int db = 0; db < 2 * AH; ++db)
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -448,8 +464,16 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
 #pragma unroll
     for (int u = 0; u < NK; ++u) {
       if (u < nk) {
-        dma.load(Kh + (k0 + u * kTileKeys) * 64, Kn[u]);
-        dma.load(Vh + (k0 + u * kTileKeys) * 64, Vn[u]);
+#pragma unroll
+        for (int ah = 0; ah < AH; ++ah) {
+          if constexpr (AH == 1) {
+            dma.load(Kh + (k0 + u * kTileKeys) * 64, Kn[u][0]);
+            dma.load(Vh + (k0 + u * kTileKeys) * 64, Vn[u][0]);
+          } else {
+            dma.load(Kh + (k0 + u * kTileKeys) * A + ah * 64, Kn[u][ah], A);
+            dma.load(Vh + (k0 + u * kTileKeys) * A + ah * 64, Vn[u][ah], A);
+          }
+        }
       }
     }
   };
@@ -477,9 +501,9 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
       for (int kb = 0; kb < 2; ++kb) {
         f32x16 s[QB], dp[QB];
 #pragma unroll
-        for (int dk = 0; dk < 4; ++dk) {
-          const bf16x8 ka = tl.read_rows(Kc[u], kb * 32, dk);
-          const bf16x8 va = tl.read_rows(Vc[u], kb * 32, dk);
+        for (int dk = 0; dk < 4 * AH; ++dk) {
+          const bf16x8 ka = tl.read_rows(Kc[u][dk >> 2], kb * 32, dk & 3);
+          const bf16x8 va = tl.read_rows(Vc[u][dk >> 2], kb * 32, dk & 3);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) {
             s[qb] = mfma_32x32x16(ka, qreg[qb][dk], dk == 0 ? negl[qb] : s[qb]);
@@ -506,10 +530,10 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
         }
       }
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
+      for (int db = 0; db < 2 * AH; ++db)
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-          const bf16x8 ka = tl.read_cols(Kc[u], kk * 16, db);
+          const bf16x8 ka = tl.read_cols(Kc[u][db >> 1], kk * 16, db & 1);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) dq[db][qb] = mfma_32x32x16(ka, sf[qb][kk], dq[db][qb]);
         }
@@ -533,9 +557,9 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
     for (int qb = 0; qb < QB; ++qb) {
       const int64_t r = row0 + wave * R + qb * 32 + col;
       if (r < a.Lq) {
-        float *po = a.part + (((int64_t)blockIdx.y * heads + head) * a.Lq + r) * 64 + half * 4;
+        float *po = a.part + (((int64_t)blockIdx.y * heads + head) * a.Lq + r) * A + half * 4;
 #pragma unroll
-        for (int db = 0; db < 2; ++db)
+        for (int db = 0; db < 2 * AH; ++db)
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
             const f32x4 w = {dq[db][qb][g * 4 + 0] * a.scale, dq[db][qb][g * 4 + 1] * a.scale,
@@ -548,11 +572,14 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   }
 
   // the wave's R x 64 block of dQ leaves through its own LDS tile as whole 128-byte rows
-  unsigned char *ot = wave == 0 ? Ks0[0] : (wave == 1 ? Ks1[0] : (wave == 2 ? Vs0[0] : Vs1[0]));
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) stage_block_T(ot, qb * 32, dq[0][qb], dq[1][qb], a.scale, lane);
+  unsigned char *ot = wave == 0 ? Ks0[0][0] : (wave == 1 ? Ks1[0][0] : (wave == 2 ? Vs0[0][0] : Vs1[0][0]));
   const int64_t wr0 = row0 + wave * R;
-  flush_rows<R>(ot, 0, a.dQ + (head * a.Lq + wr0) * 64, a.Lq - wr0, lane);
+#pragma unroll
+  for (int ah = 0; ah < AH; ++ah) {  // one half of the head at a time through the wave's tile
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) stage_block_T(ot, qb * 32, dq[2 * ah][qb], dq[2 * ah + 1][qb], a.scale, lane);
+    flush_rows<R>(ot, 0, a.dQ + (head * a.Lq + wr0) * A + ah * 64, a.Lq - wr0, lane, A);
+  }
 }
 
 // out (bf16) = sum over the splits of part[s][i], in a fixed order; n4 groups of four per split
@@ -587,7 +614,7 @@ hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, co
   const int64_t rows = (int64_t)d.B * d.Z * d.Lq;
   dim3 grid((unsigned)((rows * 8 + 255) / 256));
   hipLaunchKernelGGL(bwd_preprocess_kernel, grid, dim3(256), 0, st, (const uint16_t *)dO,
-                     (const uint16_t *)O, LSE, nD, nL, rows);
+                     (const uint16_t *)O, LSE, nD, nL, rows, d.A);
   return hipGetLastError();
 }
 
@@ -607,13 +634,19 @@ hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Q, const vo
   a.part = part;
   if (!part) splits = 1;
   dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head), (unsigned)splits);
-  if (d.causal)
-    hipLaunchKernelGGL((fused_bwd_dkdv_kernel<2, true>), grid, dim3(256), 0, st, a);
-  else
-    hipLaunchKernelGGL((fused_bwd_dkdv_kernel<2, false>), grid, dim3(256), 0, st, a);
+  if (d.A == 128) {
+    if (d.causal)
+      hipLaunchKernelGGL((fused_bwd_dkdv_kernel<2, true, 2>), grid, dim3(256), 0, st, a);
+    else
+      hipLaunchKernelGGL((fused_bwd_dkdv_kernel<2, false, 2>), grid, dim3(256), 0, st, a);
+  } else if (d.causal) {
+    hipLaunchKernelGGL((fused_bwd_dkdv_kernel<2, true, 1>), grid, dim3(256), 0, st, a);
+  } else {
+    hipLaunchKernelGGL((fused_bwd_dkdv_kernel<2, false, 1>), grid, dim3(256), 0, st, a);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || splits == 1) return e;
-  const int64_t n4 = (int64_t)d.B * d.Z * d.L * 16;
+  const int64_t n4 = (int64_t)d.B * d.Z * d.L * (d.A / 4);
   const dim3 rg((unsigned)((n4 + 255) / 256));
   hipLaunchKernelGGL(qsplit_reduce_kernel, rg, dim3(256), 0, st, part, (uint16_t *)dV, n4, splits);
   hipLaunchKernelGGL(qsplit_reduce_kernel, rg, dim3(256), 0, st, part + (int64_t)splits * n4 * 4,
@@ -621,9 +654,23 @@ hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Q, const vo
   return hipGetLastError();
 }
 
+template <bool PRE>
+static void launch_dq(const Dims &d, const BwdArgs &a, dim3 grid, hipStream_t st) {
+  if (d.A == 128) {  // one key tile (two LDS tiles) per stage
+    if (d.causal)
+      hipLaunchKernelGGL((fused_bwd_dq_kernel<32, true, PRE, 2, 1>), grid, dim3(256), 0, st, a);
+    else
+      hipLaunchKernelGGL((fused_bwd_dq_kernel<32, false, PRE, 2, 1>), grid, dim3(256), 0, st, a);
+  } else if (d.causal) {
+    hipLaunchKernelGGL((fused_bwd_dq_kernel<32, true, PRE, 1, 2>), grid, dim3(256), 0, st, a);
+  } else {
+    hipLaunchKernelGGL((fused_bwd_dq_kernel<32, false, PRE, 1, 2>), grid, dim3(256), 0, st, a);
+  }
+}
+
 // dQ = sum of the split walks' partial sums
 static hipError_t dq_reduce(const Dims &d, const float *part, void *dQ, int splits, hipStream_t st) {
-  const int64_t n4 = (int64_t)d.B * d.Z * d.Lq * 16;
+  const int64_t n4 = (int64_t)d.B * d.Z * d.Lq * (d.A / 4);
   hipLaunchKernelGGL(qsplit_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, part,
                      (uint16_t *)dQ, n4, splits);
   return hipGetLastError();
@@ -637,10 +684,7 @@ hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void
   a.part = part;
   if (!part) splits = 1;
   dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head), (unsigned)splits);
-  if (d.causal)
-    hipLaunchKernelGGL((fused_bwd_dq_kernel<32, true, false>), grid, dim3(256), 0, st, a);
-  else
-    hipLaunchKernelGGL((fused_bwd_dq_kernel<32, false, false>), grid, dim3(256), 0, st, a);
+  launch_dq<false>(d, a, grid, st);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || splits == 1) return e;
   return dq_reduce(d, part, dQ, splits, st);
@@ -656,10 +700,7 @@ hipError_t fused_bwd_dq_pre(const Dims &d, const void *dO, const void *Q, const 
   a.part = part;
   if (!part) splits = 1;
   dim3 grid((unsigned)((int64_t)d.B * d.Z * a.tiles_per_head), (unsigned)splits);
-  if (d.causal)
-    hipLaunchKernelGGL((fused_bwd_dq_kernel<32, true, true>), grid, dim3(256), 0, st, a);
-  else
-    hipLaunchKernelGGL((fused_bwd_dq_kernel<32, false, true>), grid, dim3(256), 0, st, a);
+  launch_dq<true>(d, a, grid, st);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || splits == 1) return e;
   return dq_reduce(d, part, dQ, splits, st);

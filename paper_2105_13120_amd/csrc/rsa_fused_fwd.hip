@@ -1,4 +1,4 @@
-// Fused Ring Self-Attention forward (bf16, A = 64).
+// Fused Ring Self-Attention forward (bf16, A = 64 or 128).
 //
 // One work-group owns 4*R query rows of one head and walks the K/V chunks in
 // ring order -- step t of rank n visits chunk j = (n - t) mod N, local chunk
@@ -8,6 +8,9 @@
 //
 // K/V tiles reach LDS by direct global->LDS loads, two tiles per stage, double-buffered,
 // one work-group barrier per stage.
+//
+// A head of 128 elements is handled as AH = 2 halves of 64: a 64-key tile is then two LDS tiles,
+// the S^T contraction runs over both, and O^T has twice the accumulators.
 //
 // Data flow per 64-key tile and wave (R query rows):
 //   S^T = K Q^T    A operand: K tile rows from LDS, B operand: Q^T in registers
@@ -33,16 +36,16 @@ struct FwdArgs {
   float *part_o, *part_ml;
 };
 
-template <int R, bool CAUSAL>
+template <int R, bool CAUSAL, int AH, int NK>  // NK: key tiles per stage (one barrier per stage)
 __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
   constexpr int QB = R / 32;
   constexpr int BM = 4 * R;
-  constexpr int NK = 2;  // key tiles per stage (one barrier per stage)
+  constexpr int A = 64 * AH;
   // The two stage buffers are separate objects, each addressed by name: the compiler then
   // knows that a direct load into one buffer cannot alias the LDS reads of the other and
   // does not wait for the load before them.
-  __shared__ __attribute__((aligned(16))) unsigned char Ks0[NK][kTileBytes], Ks1[NK][kTileBytes];
-  __shared__ __attribute__((aligned(16))) unsigned char Vs0[NK][kTileBytes], Vs1[NK][kTileBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Ks0[NK][AH][kTileBytes], Ks1[NK][AH][kTileBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Vs0[NK][AH][kTileBytes], Vs1[NK][AH][kTileBytes];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -67,12 +70,12 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
   const int tpc = (int)(a.c / kTileKeys);
   const int tpr = a.map.zigzag ? tpc / 2 : tpc;
 
-  const uint16_t *Qh = a.Q + head * a.Lq * 64;
-  const uint16_t *Kh = a.K + head * a.L * 64;
-  const uint16_t *Vh = a.V + head * a.L * 64;
+  const uint16_t *Qh = a.Q + head * a.Lq * A;
+  const uint16_t *Kh = a.K + head * a.L * A;
+  const uint16_t *Vh = a.V + head * a.L * A;
 
   // Q^T operand: lane (col, half) holds Q[row][dk*16 + half*8 .. +8]
-  bf16x8 qreg[QB][4];
+  bf16x8 qreg[QB][4 * AH];
   int64_t qrow[QB];  // local row (clamped to the last row for a ragged tail)
   int64_t qtok[QB];  // its global token index
 #pragma unroll
@@ -82,8 +85,8 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
     const int64_t blk = row0 + wave * R + qb * 32;  // the block of 32 rows is whole or absent
     qtok[qb] = a.map(blk < a.Lq ? blk : a.Lq - 32) + col;
 #pragma unroll
-    for (int dk = 0; dk < 4; ++dk)
-      qreg[qb][dk] = *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * 64 + dk * 16 + half * 8);
+    for (int dk = 0; dk < 4 * AH; ++dk)
+      qreg[qb][dk] = *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * A + dk * 16 + half * 8);
   }
   // first and last token of this wave's rows (R <= 64 rows inside one tile: a run of tokens)
   const int64_t wrow = row0 + wave * R < a.Lq ? row0 + wave * R : a.Lq - R;
@@ -92,13 +95,13 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
 
   const TileLanes tl(lane);
 
-  f32x16 o[2][QB];
+  f32x16 o[2 * AH][QB];
   float m[QB], mc[QB], l[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     m[qb] = -INFINITY; mc[qb] = 0.f; l[qb] = 0.f;
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+    for (int db = 0; db < 2 * AH; ++db)
 #pragma unroll
       for (int v = 0; v < 16; ++v) o[db][qb][v] = 0.f;
   }
@@ -132,8 +135,16 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
 #pragma unroll
     for (int u = 0; u < NK; ++u) {
       if (u < nk) {
-        dma.load(Kh + (k0 + u * kTileKeys) * 64, Kn[u]);
-        dma.load(Vh + (k0 + u * kTileKeys) * 64, Vn[u]);
+#pragma unroll
+        for (int ah = 0; ah < AH; ++ah) {
+          if constexpr (AH == 1) {
+            dma.load(Kh + (k0 + u * kTileKeys) * 64, Kn[u][0]);
+            dma.load(Vh + (k0 + u * kTileKeys) * 64, Vn[u][0]);
+          } else {
+            dma.load(Kh + (k0 + u * kTileKeys) * A + ah * 64, Kn[u][ah], A);
+            dma.load(Vh + (k0 + u * kTileKeys) * A + ah * 64, Vn[u][ah], A);
+          }
+        }
       }
     }
   };
@@ -159,15 +170,15 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
       f32x16 s[2][QB];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
-        bf16x8 ka[4];
+        bf16x8 ka[4 * AH];
 #pragma unroll
-        for (int dk = 0; dk < 4; ++dk) ka[dk] = tl.read_rows(Kc[u], kb * 32, dk);
+        for (int dk = 0; dk < 4 * AH; ++dk) ka[dk] = tl.read_rows(Kc[u][dk >> 2], kb * 32, dk & 3);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
           for (int v = 0; v < 16; ++v) s[kb][qb][v] = 0.f;
 #pragma unroll
-          for (int dk = 0; dk < 4; ++dk) s[kb][qb] = mfma_32x32x16(ka[dk], qreg[qb][dk], s[kb][qb]);
+          for (int dk = 0; dk < 4 * AH; ++dk) s[kb][qb] = mfma_32x32x16(ka[dk], qreg[qb][dk], s[kb][qb]);
         }
       }
       if (CAUSAL && k0 + kTileKeys - 1 > wq_first) {
@@ -208,7 +219,7 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
           mc[qb] = seen ? mn * a.cl2 : 0.f;
           l[qb] *= alpha;
 #pragma unroll
-          for (int db = 0; db < 2; ++db)
+          for (int db = 0; db < 2 * AH; ++db)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o[db][qb][v] *= alpha;
         }
@@ -237,10 +248,10 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
       }
       // ---- O^T += V^T P^T
 #pragma unroll
-      for (int db = 0; db < 2; ++db)
+      for (int db = 0; db < 2 * AH; ++db)
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-          const bf16x8 va = tl.read_cols(Vc[u], kk * 16, db);
+          const bf16x8 va = tl.read_cols(Vc[u][db >> 1], kk * 16, db & 1);
 #pragma unroll
           for (int qb = 0; qb < QB; ++qb) o[db][qb] = mfma_32x32x16(va, pf[qb][kk], o[db][qb]);
         }
@@ -266,9 +277,9 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
       const int64_t r = row0 + wave * R + qb * 32 + col;
       if (r < a.Lq) {
         const int64_t pr = ((int64_t)blockIdx.y * heads + head) * a.Lq + r;
-        float *po = a.part_o + pr * 64 + half * 4;
+        float *po = a.part_o + pr * A + half * 4;
 #pragma unroll
-        for (int db = 0; db < 2; ++db)
+        for (int db = 0; db < 2 * AH; ++db)
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
             const f32x4 w = {o[db][qb][g * 4 + 0], o[db][qb][g * 4 + 1], o[db][qb][g * 4 + 2], o[db][qb][g * 4 + 3]};
@@ -286,27 +297,34 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
   // ---- epilogue: O = O^T / l, LSE = s m + ln l.  The wave's R x 64 block of O goes through its
   // own LDS tile (every wave is past the loop's last barrier and no load is in flight, so the
   // stage buffers are free) and leaves as whole 128-byte rows.
-  unsigned char *ot = wave == 0 ? Ks0[0] : (wave == 1 ? Ks1[0] : (wave == 2 ? Vs0[0] : Vs1[0]));
+  unsigned char *ot = wave == 0 ? Ks0[0][0] : (wave == 1 ? Ks1[0][0] : (wave == 2 ? Vs0[0][0] : Vs1[0][0]));
+  float inv[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     const float lt = xhalf_sum(l[qb]);
-    const float inv = 1.0f / lt;
+    inv[qb] = 1.0f / lt;
     const int64_t r = row0 + wave * R + qb * 32 + col;
-    stage_block_T(ot, qb * 32, o[0][qb], o[1][qb], inv, lane);
     if (r < a.Lq && half == 0) a.LSE[head * a.Lq + r] = (mc[qb] + __builtin_amdgcn_logf(lt)) * kLn2;
   }
   const int64_t wr0 = row0 + wave * R;
-  flush_rows<R>(ot, 0, a.O + (head * a.Lq + wr0) * 64, a.Lq - wr0, lane);
+#pragma unroll
+  for (int ah = 0; ah < AH; ++ah) {  // one half of the head at a time through the wave's tile
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) stage_block_T(ot, qb * 32, o[2 * ah][qb], o[2 * ah + 1][qb], inv[qb], lane);
+    flush_rows<R>(ot, 0, a.O + (head * a.Lq + wr0) * A + ah * 64, a.Lq - wr0, lane, A);
+  }
 }
 
 // Merge of the split walks' partial results: with M the largest stale max of a row,
 // O = sum_s 2^(mc_s - M) o_s / sum_s 2^(mc_s - M) l_s and LSE = (M + log2 of that denominator) ln 2.
-// A split that saw no key of the row has mc = -inf and is left out.  16 lanes x 4 columns per row.
+// A split that saw no key of the row has mc = -inf and is left out.  A/4 lanes x 4 columns per row.
 __global__ void __launch_bounds__(256) fwd_combine_kernel(const float *part_o, const float *part_ml,
-                                                          uint16_t *O, float *LSE, int64_t rows, int splits) {
+                                                          uint16_t *O, float *LSE, int64_t rows, int splits,
+                                                          int A) {
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t row = gid >> 4;
-  const int sub = (int)(gid & 15);
+  const int lanes = A >> 2;
+  const int64_t row = gid / lanes;
+  const int sub = (int)(gid % lanes);
   if (row >= rows) return;
   float M = -INFINITY;
   for (int s = 0; s < splits; ++s) M = fmaxf(M, part_ml[((int64_t)s * rows + row) * 2]);
@@ -318,22 +336,22 @@ __global__ void __launch_bounds__(256) fwd_combine_kernel(const float *part_o, c
     if (mc > -INFINITY) {
       const float w = __builtin_amdgcn_exp2f(mc - M);
       lsum = fmaf(w, part_ml[pr * 2 + 1], lsum);
-      acc += *reinterpret_cast<const f32x4 *>(part_o + pr * 64 + sub * 4) * w;
+      acc += *reinterpret_cast<const f32x4 *>(part_o + pr * A + sub * 4) * w;
     }
   }
   const float inv = 1.0f / lsum;
   const u32x2 w = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv)};
-  *reinterpret_cast<u32x2 *>(O + row * 64 + sub * 4) = w;
+  *reinterpret_cast<u32x2 *>(O + row * A + sub * 4) = w;
   if (sub == 0) LSE[row] = (M + __builtin_amdgcn_logf(lsum)) * kLn2;
 }
 
-template <int R>
+template <int R, int AH, int NK>
 static hipError_t launch_fwd(const Dims &d, const FwdArgs &a, int64_t heads, int splits, hipStream_t st) {
   dim3 grid((unsigned)(heads * a.tiles_per_head), (unsigned)splits);
   if (d.causal)
-    hipLaunchKernelGGL((fused_fwd_kernel<R, true>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((fused_fwd_kernel<R, true, AH, NK>), grid, dim3(256), 0, st, a);
   else
-    hipLaunchKernelGGL((fused_fwd_kernel<R, false>), grid, dim3(256), 0, st, a);
+    hipLaunchKernelGGL((fused_fwd_kernel<R, false, AH, NK>), grid, dim3(256), 0, st, a);
   return hipGetLastError();
 }
 
@@ -364,15 +382,18 @@ hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void
   // 64 rows per wave halves the LDS traffic per flop; 32 rows per wave gives
   // twice the work-groups when the problem is too small to fill 256 CUs twice over.
   if (!part) splits = 1;
-  const bool big = (d.Lq % 256 == 0) && heads * (d.Lq / 256) * splits >= 512;
+  // (a head of 128 takes 32 rows per wave and one key tile per stage: registers and LDS)
+  const bool big = d.A == 64 && (d.Lq % 256 == 0) && heads * (d.Lq / 256) * splits >= 512;
   const int64_t rows = heads * d.Lq;
   a.part_o = part;
-  a.part_ml = part ? part + (int64_t)splits * rows * 64 : nullptr;
+  a.part_ml = part ? part + (int64_t)splits * rows * d.A : nullptr;
   a.tiles_per_head = big ? (int)(d.Lq / 256) : (int)((d.Lq + 127) / 128);
-  hipError_t e = big ? launch_fwd<64>(d, a, heads, splits, st) : launch_fwd<32>(d, a, heads, splits, st);
+  hipError_t e = d.A == 128 ? launch_fwd<32, 2, 1>(d, a, heads, splits, st)
+                 : big      ? launch_fwd<64, 1, 2>(d, a, heads, splits, st)
+                            : launch_fwd<32, 1, 2>(d, a, heads, splits, st);
   if (e != hipSuccess || splits == 1) return e;
-  hipLaunchKernelGGL(fwd_combine_kernel, dim3((unsigned)((rows * 16 + 255) / 256)), dim3(256), 0, st,
-                     a.part_o, a.part_ml, (uint16_t *)O, LSE, rows, splits);
+  hipLaunchKernelGGL(fwd_combine_kernel, dim3((unsigned)((rows * (d.A / 4) + 255) / 256)), dim3(256), 0, st,
+                     a.part_o, a.part_ml, (uint16_t *)O, LSE, rows, splits, d.A);
   return hipGetLastError();
 }
 

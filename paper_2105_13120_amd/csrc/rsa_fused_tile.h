@@ -1,5 +1,5 @@
 // LDS tile layout shared by the fused RSA kernels: a tile is 64 rows (tokens)
-// by 64 bf16 (the head dimension A), 8 KiB, with no padding.  Row r occupies
+// by 64 bf16 (the head dimension A, or one half of it when A = 128), 8 KiB, with no padding.  Row r occupies
 // bytes [128 r, 128 r + 128); inside the row the eight 16-byte chunks are
 // permuted: logical chunk cc sits at position cc ^ rot3((r >> 1) & 7), where
 // rot3 rotates a 3-bit value right by one.  With 64 four-byte banks this makes
@@ -100,17 +100,17 @@ __device__ __forceinline__ void stage_block_T(unsigned char *tile, int row_base,
     }
   }
 }
-// ... and rows [first, first + ROWS) of the tile leave for global memory (rows of 64 bf16, 128
-// bytes apart) as 16-byte pieces: one wave instruction stores 8 whole rows = 1 KiB in a row.
+// ... and rows [first, first + ROWS) of the tile leave for global memory (64 bf16 of each row,
+// rows `ld` elements apart) as 16-byte pieces: one wave instruction stores 8 rows of 128 bytes.
 // Rows at or beyond rows_valid (counted from row 0 of g) are skipped.
 template <int ROWS>
 __device__ __forceinline__ void flush_rows(const unsigned char *tile, int first, uint16_t *g,
-                                           int64_t rows_valid, int lane) {
+                                           int64_t rows_valid, int lane, int ld = 64) {
 #pragma unroll
   for (int it = 0; it < ROWS / 8; ++it) {
     const int row = it * 8 + (lane >> 3), cc = lane & 7;
     if (row < rows_valid)
-      *reinterpret_cast<u32x4 *>(g + (int64_t)row * 64 + cc * 8) =
+      *reinterpret_cast<u32x4 *>(g + (int64_t)row * ld + cc * 8) =
           *reinterpret_cast<const u32x4 *>(tile + tile_off(first + row, cc));
   }
 }

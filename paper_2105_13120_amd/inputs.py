@@ -94,6 +94,8 @@ CONFIGS = {
     "zigzag_rank0_64k_causal": RSAConfig("zigzag_rank0_64k_causal", B=1, Z=12, L=65536, A=64,
                                          N=16, dtype="bf16", causal=True,
                                          rank_begin=0, rank_end=1, zigzag=True),
+    # Heads of 128 elements: the hidden size of BERT Large (1024) cut into 8 heads instead of 16.
+    "wide_heads_8k": RSAConfig("wide_heads_8k", B=4, Z=8, L=8192, A=128, N=8, dtype="bf16"),
 }
 
 

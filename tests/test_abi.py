@@ -44,7 +44,8 @@ def test_validation_happens_before_any_launch():
     assert fwd_status(desc(L=0)) == -2
     assert fwd_status(desc(rank_begin=2, rank_end=2)) == -2
     assert fwd_status(desc(rank_end=5)) == -2
-    assert fwd_status(desc(A=128)) == -3                     # the fused kernels: heads of 64 only
+    assert fwd_status(desc(A=192)) == -3                     # the fused kernels: heads of 64 or 128
+    assert rsa.workspace_bytes(desc(A=128), True) == 2 * (1 * 2 * 256 * 4)
     assert fwd_status(desc(A=96, flags=rsa.MODE_STAGED)) == -3
     assert fwd_status(desc(A=320, flags=rsa.MODE_STAGED)) == -3
     assert rsa.workspace_bytes(desc(A=128, flags=rsa.MODE_STAGED), False) > 0

@@ -30,8 +30,8 @@ def sampled_check(cfg, x, out, head, row_blocks, cols):
     Kh, Vh = heads_view(x["K"], [head]), heads_view(x["V"], [head])
     Qh, dOh = heads_view(x["Q"], [head]), heads_view(x["dO"], [head])
     O, LSE, dQ = (download(out[k]) for k in ("O", "LSE", "dQ"))
-    O = O.reshape(-1, cfg.Lq, 64)[head]
-    dQ = dQ.reshape(-1, cfg.Lq, 64)[head]
+    O = O.reshape(-1, cfg.Lq, cfg.A)[head]
+    dQ = dQ.reshape(-1, cfg.Lq, cfg.A)[head]
     LSE = LSE.reshape(-1, cfg.Lq)[head]
     # the RMS that normalises the error is that of the whole head, from the full backward below;
     # one oracle call per run of consecutive tokens (one run unless ownership is zig-zag)
@@ -44,8 +44,8 @@ def sampled_check(cfg, x, out, head, row_blocks, cols):
         dK_ref = g[1] if dK_ref is None else dK_ref + g[1]
         dV_ref = g[2] if dV_ref is None else dV_ref + g[2]
     check("dQ", dQ[None, None], dQ_ref, cfg.dtype)
-    dK = download(out["dK"]).reshape(-1, cfg.L, 64)[head][cols]
-    dV = download(out["dV"]).reshape(-1, cfg.L, 64)[head][cols]
+    dK = download(out["dK"]).reshape(-1, cfg.L, cfg.A)[head][cols]
+    dV = download(out["dV"]).reshape(-1, cfg.L, cfg.A)[head][cols]
     check("dK", dK[None, None], dK_ref, cfg.dtype)
     check("dV", dV[None, None], dV_ref, cfg.dtype)
     for r0, nr in row_blocks:
@@ -94,3 +94,13 @@ def test_zigzag_rank0_of_64k_causal_sampled():
     cols = np.concatenate([[0, 1, 2047, 2048, 63487, 63488, 65535],
                            rng.integers(0, 2048, 100), rng.integers(0, cfg.L, 100), rng.integers(63488, cfg.L, 50)])
     sampled_check(cfg, x, out, head=7, row_blocks=[(0, 64), (1990, 58), (2048, 64), (4096 - 64, 64)], cols=cols)
+
+
+def test_wide_heads_8k_sampled():
+    """Heads of 128 elements at 8K tokens."""
+    cfg = inputs.CONFIGS["wide_heads_8k"]
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x)
+    rng = np.random.Generator(np.random.PCG64(5))
+    cols = np.concatenate([[0, 63, 64, 1023, 1024, 8191], rng.integers(0, cfg.L, 250)])
+    sampled_check(cfg, x, out, head=13, row_blocks=[(0, 64), (1000, 64), (8192 - 96, 96)], cols=cols)

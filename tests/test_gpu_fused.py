@@ -11,8 +11,8 @@ from paper_2105_13120_amd import inputs, rsa
 pytestmark = pytest.mark.gpu
 
 
-def cfg_of(B, Z, L, N, causal=False, rb=0, re=-1, seed=7, scale=1.0, zigzag=False):
-    return inputs.RSAConfig("t", B=B, Z=Z, L=L, A=64, N=N, dtype="bf16", causal=causal,
+def cfg_of(B, Z, L, N, causal=False, rb=0, re=-1, seed=7, scale=1.0, zigzag=False, A=64):
+    return inputs.RSAConfig("t", B=B, Z=Z, L=L, A=A, N=N, dtype="bf16", causal=causal,
                             rank_begin=rb, rank_end=re, seed=seed, qkv_scale=scale, zigzag=zigzag)
 
 
@@ -31,6 +31,38 @@ def test_fused_forward_backward_whole_ring(B, Z, L, N, causal):
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x)
     compare_heads(cfg, x, out, list(range(B * Z)))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("B,Z,L,N,rb,re,zigzag", [
+    (1, 1, 64, 1, 0, -1, False), (2, 3, 320, 5, 0, -1, False), (1, 2, 1024, 4, 0, -1, False),
+    (1, 2, 640, 5, 1, 4, False),     # three ranks of five: partial dK, dV
+    (1, 2, 1024, 4, 0, -1, True),    # zig-zag ownership, whole ring
+    (1, 2, 1536, 3, 1, 2, True),     # zig-zag, one rank's share
+    (1, 2, 4096, 4, 3, 4, False),    # split key walk
+    (1, 1, 4096, 2, 0, 1, True),     # split key walk under zig-zag ownership
+])
+def test_heads_of_128(B, Z, L, N, rb, re, zigzag, causal):
+    """A = 128: the fused kernels take a head as two halves of 64."""
+    cfg = cfg_of(B, Z, L, N, causal, rb=rb, re=re, seed=53, zigzag=zigzag, A=128)
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x)
+    compare_heads(cfg, x, out, list(range(B * Z)))
+
+
+def test_heads_of_128_backward_parts_equal_the_whole():
+    cfg = cfg_of(1, 2, 512, 4, causal=True, seed=59, A=128)
+    x = inputs.make_inputs(cfg)
+    Q, K, V, dO = (upload(x[k], "bf16") for k in ("Q", "K", "V", "dO"))
+    desc = rsa.make_desc(K, cfg.N, causal=True)
+    O, LSE = rsa.forward(desc, Q, K, V)
+    ws = torch.empty(rsa.workspace_bytes(desc, True), dtype=torch.uint8, device="cuda")
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    rsa.bwd_preprocess(desc, dO, O, LSE, ws)
+    rsa.bwd_dkdv(desc, dO, Q, K, V, ws, dK, dV)
+    rsa.bwd_dq(desc, dO, Q, K, V, ws, dQ)
+    torch.cuda.synchronize()
+    compare_heads(cfg, x, dict(O=O, LSE=LSE, dQ=dQ, dK=dK, dV=dV), [0, 1])
 
 
 @pytest.mark.parametrize("causal", [False, True])

@@ -20,13 +20,15 @@ def draw_case(rng):
                 causal=bool(rng.integers(0, 2)), zigzag=zigzag, seed=int(rng.integers(0, 1 << 30)))
 
 
-CASES = [draw_case(np.random.Generator(np.random.PCG64(1000 + i))) for i in range(24)]
+# 24 cases with heads of 64 elements, then 12 (other seeds) with heads of 128
+CASES = [dict(draw_case(np.random.Generator(np.random.PCG64(1000 + i))), A=64) for i in range(24)] + \
+        [dict(draw_case(np.random.Generator(np.random.PCG64(2000 + i))), A=128) for i in range(12)]
 
 
-@pytest.mark.parametrize("case", CASES, ids=lambda c: "B{B}Z{Z}L{L}N{N}r{rb}-{re}{c}{z}".format(
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "A{A}B{B}Z{Z}L{L}N{N}r{rb}-{re}{c}{z}".format(
     c="c" if c["causal"] else "", z="z" if c["zigzag"] else "", **c))
 def test_random_shape(case):
-    cfg = inputs.RSAConfig("r", B=case["B"], Z=case["Z"], L=case["L"], A=64, N=case["N"], dtype="bf16",
+    cfg = inputs.RSAConfig("r", B=case["B"], Z=case["Z"], L=case["L"], A=case["A"], N=case["N"], dtype="bf16",
                            causal=case["causal"], rank_begin=case["rb"], rank_end=case["re"],
                            seed=case["seed"], zigzag=case["zigzag"])
     x = inputs.make_inputs(cfg)
