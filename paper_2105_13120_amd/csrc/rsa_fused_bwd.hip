@@ -341,7 +341,7 @@ __global__ void __launch_bounds__(256, AH == 2 ? 1 : 2) fused_bwd_dkdv_kernel(Bw
 
 // ---------------------------------------------------------------------- dQ ---
 template <int R, bool CAUSAL, bool PRE, int AH, int NK>  // NK: key tiles per stage (one barrier per stage)
-__global__ void __launch_bounds__(256, (R == 64 || AH == 2) ? 1 : 2) fused_bwd_dq_kernel(BwdArgs a) {
+__global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdArgs a) {
   constexpr int QB = R / 32;
   constexpr int BM = 4 * R;
   constexpr int A = 64 * AH;  // a head of 128 is two halves of 64: two LDS tiles per 64 keys

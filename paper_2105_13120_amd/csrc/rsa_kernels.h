@@ -33,7 +33,7 @@ hipError_t store_rows(int dtype, const float *src, void *dst, int64_t batches,
 // p[0..n) = 0 (n a multiple of 4), by a kernel
 hipError_t zero_f32(float *p, int64_t n, hipStream_t st);
 
-// --- fused (online-softmax) path, bf16, A = 64 ---
+// --- fused (online-softmax) path, bf16, A = 64 or 128 ---
 // part / splits: optional split of the walk over the keys (few query rows, many keys), see
 // fused_key_splits: fp32 partial results, splits * B*Z*Lq * 66 floats; nullptr / 1: none
 int fused_key_splits(const Dims &d);
