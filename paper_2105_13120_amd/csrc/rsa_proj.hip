@@ -307,10 +307,12 @@ static hipError_t launch_gemm(GemmArgs &g, int splits, hipStream_t st) {
   return hipGetLastError();
 }
 
-// k splits of a weight-gradient product: enough work-groups to fill the chip twice
+// k splits of a weight-gradient product: as many as still give every CU at most one work-group
+// (the kernel runs one per CU; a second round costs more than the longer k walk of fewer splits,
+// and every split writes and re-reads a full fp32 partial result)
 int proj_wgrad_splits(int64_t Mout, int64_t Nout, int64_t K) {
   const int64_t tiles = ((Mout + kGemmBM - 1) / kGemmBM) * ((Nout + kGemmBN - 1) / kGemmBN);
-  int64_t s = (512 + tiles - 1) / tiles;
+  int64_t s = 256 / tiles;
   const int64_t slabs = K / 64;
   if (s > slabs / 4) s = slabs / 4;
   if (s < 1) s = 1;
