@@ -183,7 +183,7 @@ int staged_backward(const Dims &d, int dtype, const void *dO, const void *Q, con
 
 extern "C" {
 
-int rsa_version(void) { return 100; }
+int rsa_version(void) { return 110; }
 
 const char *rsa_strerror(int status) {
   switch (status) {

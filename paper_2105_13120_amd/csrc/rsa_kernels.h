@@ -35,7 +35,7 @@ hipError_t zero_f32(float *p, int64_t n, hipStream_t st);
 
 // --- fused (online-softmax) path, bf16, A = 64 or 128 ---
 // part / splits: optional split of the walk over the keys (few query rows, many keys), see
-// fused_key_splits: fp32 partial results, splits * B*Z*Lq * 66 floats; nullptr / 1: none
+// fused_key_splits: fp32 partial results, splits * B*Z*Lq * (A + 2) floats; nullptr / 1: none
 int fused_key_splits(const Dims &d);
 hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void *V, void *O,
                          float *LSE, hipStream_t st, float *part, int splits);
@@ -43,12 +43,12 @@ hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void
 hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, const float *LSE,
                                 float *nD, float *nL, hipStream_t st);
 // part / splits: optional split of the walk over the query rows (few keys, many rows): fp32
-// partial dV and dK, 2 * splits * B*Z*L*64 floats, added up in a fixed order; nullptr / 1: none
+// partial dV and dK, 2 * splits * B*Z*L*A floats, added up in a fixed order; nullptr / 1: none
 int fused_bwd_dkdv_splits(const Dims &d);
 hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Q, const void *K,
                           const void *V, const float *nL, const float *nD, void *dK, void *dV,
                           hipStream_t st, float *part = nullptr, int splits = 1);
-// part / splits: the split key walk again, fp32 partial dQ, splits * B*Z*Lq * 64 floats
+// part / splits: the split key walk again, fp32 partial dQ, splits * B*Z*Lq * A floats
 hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void *K, const void *V,
                         const float *nL, const float *nD, void *dQ, hipStream_t st,
                         float *part = nullptr, int splits = 1);
