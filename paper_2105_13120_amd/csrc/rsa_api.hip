@@ -345,7 +345,7 @@ namespace {
 int proj_check(const rsa_desc *d, int32_t H, Dims *dm) {
   int rc = validate(d, dm);
   if (rc != RSA_OK) return rc;
-  if (dm->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16 || dm->A != 64) return RSA_ERR_UNSUPPORTED;
+  if (dm->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16) return RSA_ERR_UNSUPPORTED;
   if (H < 64) return RSA_ERR_SHAPE;
   if (H % 64 != 0) return RSA_ERR_UNSUPPORTED;
   // the GEMM kernel indexes rows and columns of its operands with 32 bits

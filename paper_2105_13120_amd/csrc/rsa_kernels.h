@@ -57,9 +57,9 @@ hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const vo
                           void *dV, float *nD, float *nL, hipStream_t st,
                           float *part = nullptr, int qsplits = 1, int ksplits = 1);
 
-// --- the linear maps around RSA (Table 2, rows Q/K/V and Linear), bf16, A = 64 ---
-// X, dX, Y, dY: (B, Lq, H); W: (H, 3*Z*64), columns [Q | K | V] head-major; Wo: (Z*64, H);
-// Q, K, V, O and their gradients: (B, Z, Lq, 64); dW, dWo: fp32; part: k-split partial sums.
+// --- the linear maps around RSA (Table 2, rows Q/K/V and Linear), bf16, A = 64 or 128 ---
+// X, dX, Y, dY: (B, Lq, H); W: (H, 3*Z*A), columns [Q | K | V] head-major; Wo: (Z*A, H);
+// Q, K, V, O and their gradients: (B, Z, Lq, A); dW, dWo: fp32; part: k-split partial sums.
 int proj_wgrad_splits(int64_t Mout, int64_t Nout, int64_t K);
 hipError_t proj_qkv(const Dims &d, int64_t H, const void *X, const void *W, void *Q, void *K, void *V,
                     hipStream_t st);

@@ -3,8 +3,9 @@
 //   Q/K/V:  (B, rows, H) x (H, AZ) -> (B, Z, rows, A), written head-split as RSA reads it
 //   Linear: (B, Z, rows, A) x (AZ, H) -> (B, rows, H), read head-split as RSA writes it
 // One MFMA GEMM kernel serves all six products.  An operand is a "view": a matrix cut into
-// 64 x 64 tiles that are either blocks of a plain row-major matrix or the (64 rows, one head)
-// blocks of up to three (B, Z, rows, 64) tensors, so no tensor is ever re-laid out in memory.
+// 64 x 64 tiles that are either blocks of a plain row-major matrix or the (64 rows, 64 elements of
+// one head) blocks of up to three (B, Z, rows, A) tensors, A = 64 or 128, so no tensor is ever
+// re-laid out in memory.
 //
 // Work-group: 256 x 256 outputs, 8 waves of 128 x 64 (4 x 2 MFMA blocks of 32 x 32), k in slabs
 // of 64 through the swizzled LDS tiles of the attention kernels, double-buffered, one barrier
@@ -18,21 +19,12 @@ namespace rsa {
 
 // A bf16 matrix [R][C] served as 64 x 64 tiles.
 struct MatView {
-  const uint16_t *p[3];  // plain: p[0]; head-split: tensor cb / Z holds column tile cb
-  int64_t ld;            // plain: row stride in elements
+  const uint16_t *p[3];  // plain: p[0]; head-split: tensor cb / (Z * AH) holds column tile cb
+  int64_t ld;            // row stride in elements (head-split: the head size A)
   int64_t rows;          // head-split: rows per (b, z) block (a multiple of 64)
-  int Z;                 // head-split: heads = column tiles per tensor
-  int split;             // 0: plain row-major; 1: (B, Z, rows, 64) tensors, row index = b * rows + r
-  __device__ __forceinline__ const uint16_t *tile(int64_t rb, int64_t cb, int64_t &ldt) const {
-    if (!split) {
-      ldt = ld;
-      return p[0] + rb * 64 * ld + cb * 64;
-    }
-    const int which = (int)(cb / Z), z = (int)(cb % Z);
-    const int64_t m0 = rb * 64, b = m0 / rows, r0 = m0 % rows;
-    ldt = 64;
-    return p[which] + ((b * Z + z) * rows + r0) * 64;
-  }
+  int Z;                 // head-split: heads per tensor
+  int AH;                // head-split: column tiles per head (A / 64: 1 or 2), head-major order
+  int split;             // 0: plain row-major; 1: (B, Z, rows, A) tensors, row index = b * rows + r
 };
 
 // A value that is the same in every lane, moved to scalar registers (integer division leaves
@@ -46,27 +38,33 @@ __device__ __forceinline__ int64_t uniform64(int64_t x) {
 // How the tiles of one operand move along k, slab by slab, with additions only (the divisions
 // that place a head-split tile are done once, in TileCursor's constructor): `step` per slab, and
 // after `period` steps an extra jump to the next batch element (mode 1) or to the next tensor of
-// the view (mode 2: jump1 into tensor 1, jump2 into tensor 2).
+// the view (mode 2: jump1 into tensor 1, jump2 into tensor 2).  With two column tiles per head
+// (mode 3) a step is the 64 elements to the head's second half, every second step also jumps
+// (jumpA) to the next head, and after Z heads comes the jump to the next tensor.
 struct ViewWalk {
-  int64_t ld, step, jump1, jump2;
-  int period, mode;
+  int64_t ld, step, jump1, jump2, jumpA;
+  int period, mode, Z;
   // krows: k runs over the row tiles of the view; else over its column tiles
   __device__ __forceinline__ ViewWalk(const MatView &v, bool krows) {
-    jump1 = 0; jump2 = 0; period = 0x7fffffff; mode = 0;
+    jump1 = 0; jump2 = 0; jumpA = 0; period = 0x7fffffff; mode = 0; Z = v.Z;
     if (!v.split) {
       ld = v.ld;
       step = krows ? 64 * v.ld : 64;
     } else if (!krows) {  // k runs over heads, then over the tensors of the view
-      ld = 64;
-      step = v.rows * 64;
-      // after the last head of a tensor the pointer has moved Z steps; the next tensor starts over
-      jump1 = (v.p[1] - v.p[0]) - (int64_t)v.Z * step;
-      jump2 = (v.p[2] - v.p[1]) - (int64_t)v.Z * step;
-      period = v.Z; mode = 2;
+      ld = v.ld;
+      const int64_t head = v.rows * v.ld;  // elements from one head to the next
+      // after the last head of a tensor the pointer has moved Z heads; the next tensor starts over
+      jump1 = (v.p[1] - v.p[0]) - (int64_t)v.Z * head;
+      jump2 = (v.p[2] - v.p[1]) - (int64_t)v.Z * head;
+      if (v.AH == 1) {
+        step = head; period = v.Z; mode = 2;
+      } else {
+        step = 64; jumpA = head - 128; period = 2; mode = 3;
+      }
     } else {  // k runs over the rows of a batch element, then over batch elements
-      ld = 64;
-      step = 64 * 64;
-      jump1 = (int64_t)(v.Z - 1) * v.rows * 64;
+      ld = v.ld;
+      step = 64 * v.ld;
+      jump1 = (int64_t)(v.Z - 1) * v.rows * v.ld;
       period = (int)(v.rows / 64); mode = 1;
     }
   }
@@ -74,7 +72,7 @@ struct ViewWalk {
 
 struct TileCursor {
   const uint16_t *ptr;
-  int cnt, which;
+  int cnt, which;  // which: tensor of the view; in mode 3 also the head inside it, times 4
   // krows: the tile index `fixed` selects columns and k (slab ks) selects rows; else the reverse
   __device__ __forceinline__ TileCursor(const MatView &v, bool krows, int64_t fixed, int64_t ks) {
     cnt = 0; which = 0;
@@ -82,17 +80,22 @@ struct TileCursor {
       ptr = krows ? v.p[0] + ks * 64 * v.ld + fixed * 64 : v.p[0] + fixed * 64 * v.ld + ks * 64;
     } else {
       const uint32_t ct = (uint32_t)(krows ? fixed : ks), rt = (uint32_t)(krows ? ks : fixed);
-      which = (int)(ct / (uint32_t)v.Z);
-      const int64_t z = ct % (uint32_t)v.Z;
+      const uint32_t per_tensor = (uint32_t)(v.Z * v.AH);
+      which = (int)(ct / per_tensor);
+      const uint32_t rem = ct % per_tensor;
+      const int64_t z = rem / (uint32_t)v.AH;
+      const int ah = (int)(rem % (uint32_t)v.AH);
       const uint32_t m0 = rt * 64u, b = m0 / (uint32_t)v.rows, r0 = m0 % (uint32_t)v.rows;
       const uint16_t *t = which == 0 ? v.p[0] : (which == 1 ? v.p[1] : v.p[2]);
-      ptr = t + (((int64_t)b * v.Z + z) * v.rows + r0) * 64;
-      cnt = krows ? (int)(r0 / 64) : (int)z;
+      ptr = t + (((int64_t)b * v.Z + z) * v.rows + r0) * v.ld + ah * 64;
+      cnt = krows ? (int)(r0 / 64) : (v.AH == 1 ? (int)z : ah);
+      if (!krows && v.AH == 2) which |= (int)z << 2;
     }
     ptr = reinterpret_cast<const uint16_t *>(uniform64(reinterpret_cast<int64_t>(ptr)));
     cnt = __builtin_amdgcn_readfirstlane(cnt);
     which = __builtin_amdgcn_readfirstlane(which);
   }
+  template <bool WIDE>  // WIDE: some view of the product has two column tiles per head (mode 3)
   __device__ __forceinline__ void advance(const ViewWalk &w) {
     ptr += w.step;
     if (++cnt == w.period) {
@@ -100,6 +103,11 @@ struct TileCursor {
       cnt = 0;
       if (w.mode == 1) ptr += w.jump1;
       if (w.mode == 2) { ptr += which == 0 ? w.jump1 : w.jump2; ++which; }
+      if (WIDE && w.mode == 3) {
+        ptr += w.jumpA;
+        which += 4;
+        if ((which >> 2) == w.Z) { ptr += (which & 3) == 0 ? w.jump1 : w.jump2; which = (which & 3) + 1; }
+      }
     }
   }
 };
@@ -110,7 +118,7 @@ struct GemmArgs {
   int64_t kslabs;     // slabs of 64 k per split (split s takes slabs [s * kslabs, ...))
   void *out[3];       // plain: out[0] (+ split * M * out_ld elements for a k split); head-split: 3 tensors
   int64_t out_ld, out_rows;
-  int out_Z, out_split;
+  int out_Z, out_AH, out_split;  // head-split output: (B, out_Z, out_rows, 64 * out_AH) tensors
   int ntiles;         // 128-wide column tiles
 };
 
@@ -127,7 +135,8 @@ struct GemmArgs {
 // of the loop body, and two copies of a body with 128 accumulator registers do not agree on
 // where the accumulators live.)
 constexpr int kGemmBM = 256, kGemmBN = 256;
-template <bool A_KROWS, bool B_KROWS, bool OUT_F32>
+// WIDE: heads of 128 elements somewhere in the product (an operand view or the output).
+template <bool A_KROWS, bool B_KROWS, bool OUT_F32, bool WIDE>
 __global__ void __launch_bounds__(512, 1) proj_gemm_kernel(GemmArgs g) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[2][8][kTileBytes];  // [buffer][A0..A3, B0..B3]
 
@@ -165,7 +174,7 @@ __global__ void __launch_bounds__(512, 1) proj_gemm_kernel(GemmArgs g) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) stg[4 + t] = *(gvec_t)(cb[t].ptr + gb_off);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) { ca[t].advance(wa); cb[t].advance(wb); }
+    for (int t = 0; t < 4; ++t) { ca[t].template advance<WIDE>(wa); cb[t].template advance<WIDE>(wb); }
   };
   auto put = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
@@ -229,14 +238,18 @@ __global__ void __launch_bounds__(512, 1) proj_gemm_kernel(GemmArgs g) {
     unsigned char *t0 = lds[0][wave], *t1 = lds[1][wave];
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb) stage_block_T(mb < 2 ? t0 : t1, (mb & 1) * 32, acc[0][mb], acc[1][mb], 1.0f, lane);
-    const int64_t nw = n0 + wn * 64;  // the block's 64 columns: one head of a head-split output
+    const int64_t nw = n0 + wn * 64;  // the block's 64 columns: (half of) one head of a head-split output
     if (nw < g.N) {
       int which = 0;
-      int64_t zoff = 0;
+      int64_t zoff = 0, aoff = 0;
+      const int out_AH = WIDE ? g.out_AH : 1;
+      const int64_t out_A = 64 * out_AH;
       if (g.out_split) {
-        const uint32_t hb = (uint32_t)(nw / 64);
-        which = (int)(hb / (uint32_t)g.out_Z);
-        zoff = hb % (uint32_t)g.out_Z;
+        const uint32_t hb = (uint32_t)(nw / 64), per_tensor = (uint32_t)(g.out_Z * out_AH);
+        which = (int)(hb / per_tensor);
+        const uint32_t rem = hb % per_tensor;
+        zoff = rem / (uint32_t)out_AH;
+        aoff = (rem % (uint32_t)out_AH) * 64;
       }
       uint16_t *base = static_cast<uint16_t *>(which == 0 ? g.out[0] : (which == 1 ? g.out[1] : g.out[2]));
 #pragma unroll
@@ -250,7 +263,7 @@ __global__ void __launch_bounds__(512, 1) proj_gemm_kernel(GemmArgs g) {
           off = m * g.out_ld + nw + cc * 8;
         } else {
           const uint32_t b = (uint32_t)m / (uint32_t)g.out_rows, r = (uint32_t)m % (uint32_t)g.out_rows;
-          off = (((int64_t)b * g.out_Z + zoff) * g.out_rows + r) * 64 + cc * 8;
+          off = (((int64_t)b * g.out_Z + zoff) * g.out_rows + r) * out_A + aoff + cc * 8;
         }
         *reinterpret_cast<u32x4 *>(base + off) = w;
       }
@@ -287,13 +300,13 @@ __global__ void __launch_bounds__(256) ksplit_reduce_kernel(const float *part, f
 
 static MatView plain(const void *p, int64_t ld) {
   MatView v{};
-  v.p[0] = static_cast<const uint16_t *>(p); v.ld = ld; v.split = 0; v.rows = 64; v.Z = 1;
+  v.p[0] = static_cast<const uint16_t *>(p); v.ld = ld; v.split = 0; v.rows = 64; v.Z = 1; v.AH = 1;
   return v;
 }
-static MatView heads(const void *p0, const void *p1, const void *p2, int64_t rows, int Z) {
+static MatView heads(const void *p0, const void *p1, const void *p2, int64_t rows, int Z, int A = 64) {
   MatView v{};
   v.p[0] = static_cast<const uint16_t *>(p0); v.p[1] = static_cast<const uint16_t *>(p1);
-  v.p[2] = static_cast<const uint16_t *>(p2); v.ld = 64; v.rows = rows; v.Z = Z; v.split = 1;
+  v.p[2] = static_cast<const uint16_t *>(p2); v.ld = A; v.rows = rows; v.Z = Z; v.AH = A / 64; v.split = 1;
   return v;
 }
 
@@ -303,7 +316,11 @@ static hipError_t launch_gemm(GemmArgs &g, int splits, hipStream_t st) {
   const int64_t mtiles = (g.M + kGemmBM - 1) / kGemmBM;
   g.kslabs = (g.K / 64 + splits - 1) / splits;
   dim3 grid((unsigned)(mtiles * g.ntiles), (unsigned)splits);
-  hipLaunchKernelGGL((proj_gemm_kernel<A_KROWS, B_KROWS, OUT_F32>), grid, dim3(512), 0, st, g);
+  const bool wide = (g.A.split && g.A.AH == 2) || (g.B.split && g.B.AH == 2) || (g.out_split && g.out_AH == 2);
+  if (wide)
+    hipLaunchKernelGGL((proj_gemm_kernel<A_KROWS, B_KROWS, OUT_F32, true>), grid, dim3(512), 0, st, g);
+  else
+    hipLaunchKernelGGL((proj_gemm_kernel<A_KROWS, B_KROWS, OUT_F32, false>), grid, dim3(512), 0, st, g);
   return hipGetLastError();
 }
 
@@ -323,18 +340,18 @@ int proj_wgrad_splits(int64_t Mout, int64_t Nout, int64_t K) {
 hipError_t proj_qkv(const Dims &d, int64_t H, const void *X, const void *W, void *Q, void *K, void *V,
                     hipStream_t st) {
   GemmArgs g{};
-  g.M = (int64_t)d.B * d.Lq; g.N = 3LL * d.Z * 64; g.K = H;
+  g.M = (int64_t)d.B * d.Lq; g.N = 3LL * d.Z * d.A; g.K = H;
   g.A = plain(X, H);          // [M][K]
   g.B = plain(W, g.N);        // [K][N]
   g.out[0] = Q; g.out[1] = K; g.out[2] = V;
-  g.out_split = 1; g.out_rows = d.Lq; g.out_Z = d.Z;
+  g.out_split = 1; g.out_rows = d.Lq; g.out_Z = d.Z; g.out_AH = d.A / 64;
   return launch_gemm<false, true, false>(g, 1, st);
 }
 
 hipError_t proj_out(const Dims &d, int64_t H, const void *O, const void *Wo, void *Y, hipStream_t st) {
   GemmArgs g{};
-  g.M = (int64_t)d.B * d.Lq; g.N = H; g.K = (int64_t)d.Z * 64;
-  g.A = heads(O, nullptr, nullptr, d.Lq, d.Z);  // [M][K], column tile = head
+  g.M = (int64_t)d.B * d.Lq; g.N = H; g.K = (int64_t)d.Z * d.A;
+  g.A = heads(O, nullptr, nullptr, d.Lq, d.Z, d.A);  // [M][K], column tile = (half of a) head
   g.B = plain(Wo, H);                           // [K][N]
   g.out[0] = Y; g.out_split = 0; g.out_ld = H;
   return launch_gemm<false, true, false>(g, 1, st);
@@ -342,20 +359,20 @@ hipError_t proj_out(const Dims &d, int64_t H, const void *O, const void *Wo, voi
 
 hipError_t proj_out_bwd(const Dims &d, int64_t H, const void *dY, const void *O, const void *Wo,
                         void *dO, float *dWo, float *part, hipStream_t st) {
-  const int64_t M = (int64_t)d.B * d.Lq, ZA = (int64_t)d.Z * 64;
+  const int64_t M = (int64_t)d.B * d.Lq, ZA = (int64_t)d.Z * d.A;
   {  // dO = dY Wo^T, head-split
     GemmArgs g{};
     g.M = M; g.N = ZA; g.K = H;
     g.A = plain(dY, H);   // [M][K]
     g.B = plain(Wo, H);   // [N][K]
-    g.out[0] = dO; g.out_split = 1; g.out_rows = d.Lq; g.out_Z = d.Z;
+    g.out[0] = dO; g.out_split = 1; g.out_rows = d.Lq; g.out_Z = d.Z; g.out_AH = d.A / 64;
     hipError_t e = launch_gemm<false, false, false>(g, 1, st);
     if (e != hipSuccess) return e;
   }
   // dWo = O^T dY: contraction over the rows
   GemmArgs g{};
   g.M = ZA; g.N = H; g.K = M;
-  g.A = heads(O, nullptr, nullptr, d.Lq, d.Z);  // [K][M]
+  g.A = heads(O, nullptr, nullptr, d.Lq, d.Z, d.A);  // [K][M]
   g.B = plain(dY, H);                           // [K][N]
   const int splits = proj_wgrad_splits(ZA, H, M);
   g.out[0] = splits > 1 ? part : dWo; g.out_split = 0; g.out_ld = H;
@@ -370,11 +387,11 @@ hipError_t proj_out_bwd(const Dims &d, int64_t H, const void *dY, const void *O,
 hipError_t proj_qkv_bwd(const Dims &d, int64_t H, const void *dQ, const void *dK, const void *dV,
                         const void *X, const void *W, void *dX, float *dW, float *part,
                         hipStream_t st) {
-  const int64_t M = (int64_t)d.B * d.Lq, N3 = 3LL * d.Z * 64;
+  const int64_t M = (int64_t)d.B * d.Lq, N3 = 3LL * d.Z * d.A;
   {  // dX = [dQ | dK | dV] W^T
     GemmArgs g{};
     g.M = M; g.N = H; g.K = N3;
-    g.A = heads(dQ, dK, dV, d.Lq, d.Z);  // [M][K]
+    g.A = heads(dQ, dK, dV, d.Lq, d.Z, d.A);  // [M][K]
     g.B = plain(W, N3);                  // [N][K]
     g.out[0] = dX; g.out_split = 0; g.out_ld = H;
     hipError_t e = launch_gemm<false, false, false>(g, 1, st);
@@ -384,7 +401,7 @@ hipError_t proj_qkv_bwd(const Dims &d, int64_t H, const void *dQ, const void *dK
   GemmArgs g{};
   g.M = H; g.N = N3; g.K = M;
   g.A = plain(X, H);                   // [K][M]
-  g.B = heads(dQ, dK, dV, d.Lq, d.Z);  // [K][N]
+  g.B = heads(dQ, dK, dV, d.Lq, d.Z, d.A);  // [K][N]
   const int splits = proj_wgrad_splits(H, N3, M);
   g.out[0] = splits > 1 ? part : dW; g.out_split = 0; g.out_ld = N3;
   hipError_t e = launch_gemm<true, true, true>(g, splits, st);
@@ -438,7 +455,7 @@ hipError_t linformer_project_bwd(int64_t Zt, int64_t L, int64_t rows, int64_t Kp
     g.M = rows; g.N = Zt * 64; g.K = Kp;
     g.A = plain(E, Kp);                               // [M = token][K = k]
     g.B = heads(dXp, nullptr, nullptr, Kp, (int)Zt);  // [K = k][N = (head, a)]
-    g.out[0] = dX; g.out_split = 1; g.out_rows = L; g.out_Z = (int)Zt;
+    g.out[0] = dX; g.out_split = 1; g.out_rows = L; g.out_Z = (int)Zt; g.out_AH = 1;
     hipError_t e = launch_gemm<false, true, false>(g, 1, st);
     if (e != hipSuccess) return e;
   }

@@ -26,19 +26,23 @@ def check_f32(name, got, ref):
     assert err <= 2e-4 * rms, f"{name}: max abs err {err:.3e} vs rms {rms:.3e}"
 
 
-# (B, Z, L, N, rank range, H): several 128-tiles, ragged 64-edges in M, N and K, one rank's share
+# (B, Z, L, N, rank range, H, A): several 128-tiles, ragged 64-edges in M, N and K, one rank's share;
+# heads of 64 and of 128 elements
 CASES = [
-    (1, 1, 64, 1, (0, 1), 64),
-    (2, 2, 128, 2, (0, 2), 192),
-    (1, 3, 320, 5, (0, 5), 320),
-    (2, 4, 512, 4, (1, 3), 256),
-    (1, 16, 2048, 8, (0, 8), 1024),
+    (1, 1, 64, 1, (0, 1), 64, 64),
+    (2, 2, 128, 2, (0, 2), 192, 64),
+    (1, 3, 320, 5, (0, 5), 320, 64),
+    (2, 4, 512, 4, (1, 3), 256, 64),
+    (1, 16, 2048, 8, (0, 8), 1024, 64),
+    (1, 1, 64, 1, (0, 1), 64, 128),
+    (2, 3, 320, 5, (1, 4), 192, 128),
+    (2, 5, 512, 4, (0, 4), 320, 128),     # 15 column tiles per output: work-groups straddle Q | K | V
+    (1, 8, 2048, 8, (0, 8), 1024, 128),
 ]
 
 
-@pytest.mark.parametrize("B,Z,L,N,ranks,H", CASES)
-def test_projections_forward_and_backward(B, Z, L, N, ranks, H):
-    A = 64
+@pytest.mark.parametrize("B,Z,L,N,ranks,H,A", CASES)
+def test_projections_forward_and_backward(B, Z, L, N, ranks, H, A):
     rows = (ranks[1] - ranks[0]) * (L // N)
     X = draw((B, rows, H), 1)
     W = draw((H, 3 * Z * A), 2, H ** -0.5)
@@ -87,10 +91,11 @@ def test_projection_outputs_feed_rsa_without_relayout():
     check("Y", download(Y), oracle.proj.out_proj(download(O), Wo), "bf16")
 
 
-def test_attention_block_backward_chain():
+@pytest.mark.parametrize("Z,A", [(4, 64), (2, 128)])
+def test_attention_block_backward_chain(Z, A):
     """dY -> Linear backward -> RSA backward -> Q/K/V projection backward: the whole block's
     gradients, each stage against the oracle on the rounded tensors that stage received."""
-    B, Z, L, N, H, A = 2, 4, 512, 4, 256, 64
+    B, L, N, H = 2, 512, 4, 256
     X = draw((B, L, H), 21)
     W = draw((H, 3 * Z * A), 22, H ** -0.5)
     Wo = draw((Z * A, H), 23, (Z * A) ** -0.5)
