@@ -190,7 +190,9 @@ const char *rsa_strerror(int status) {
     case RSA_OK: return "ok";
     case RSA_ERR_NULL: return "a required pointer is NULL";
     case RSA_ERR_SHAPE: return "bad shape: sizes must be positive, L divisible by N, ranks within [0, N)";
-    case RSA_ERR_UNSUPPORTED: return "unsupported: need A = 64, L/N divisible by 64, 16-byte aligned pointers, bf16 for the fused mode";
+    case RSA_ERR_UNSUPPORTED:
+      return "unsupported: need a head size of 64 or 128 (staged mode: a multiple of 64 up to 256), L/N "
+             "divisible by 64, 16-byte aligned pointers, bf16 for the fused mode";
     case RSA_ERR_WORKSPACE: return "workspace missing or too small";
     case RSA_ERR_HIP: return "a HIP call failed";
     default: return "unknown status";
