@@ -711,8 +711,17 @@ hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const vo
                           void *dV, float *nD, float *nL, hipStream_t st, float *part,
                           int qsplits, int ksplits) {
   // the dQ kernel first: its prologue forms the row terms that the dK/dV kernel reads;
-  // the two kernels' partial sums share `part`, one after the other
-  hipError_t e = fused_bwd_dq_pre(d, dO, Q, K, V, O, LSE, nL, nD, dQ, st, part, ksplits);
+  // the two kernels' partial sums share `part`, one after the other.  (With heads of 128 the
+  // prologue costs the dQ kernel more registers than it has: there the row terms come from
+  // the preprocess kernel.)
+  hipError_t e;
+  if (d.A == 128) {
+    e = fused_bwd_preprocess(d, dO, O, LSE, nD, nL, st);
+    if (e != hipSuccess) return e;
+    e = fused_bwd_dq(d, dO, Q, K, V, nL, nD, dQ, st, part, ksplits);
+  } else {
+    e = fused_bwd_dq_pre(d, dO, Q, K, V, O, LSE, nL, nD, dQ, st, part, ksplits);
+  }
   if (e != hipSuccess) return e;
   return fused_bwd_dkdv(d, dO, Q, K, V, nL, nD, dK, dV, st, part, qsplits);
 }
