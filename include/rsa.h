@@ -27,7 +27,7 @@
  *    round-to-nearest-even per stored element.  dtype RSA_F32: fp32
  *    throughout (staged mode only).
  *  - Supported: A = 64 or 128 in fused mode, any multiple of 64 up to 256 in
- *    staged mode (the Linformer entry points: A = 64); L divisible by N (section 4.2: the sequence length must be
+ *    staged mode; L divisible by N (section 4.2: the sequence length must be
  *    divisible by the sequence-parallel size); c divisible by 64.
  */
 #ifndef RSA_H

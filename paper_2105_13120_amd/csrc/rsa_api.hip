@@ -411,12 +411,12 @@ namespace {
 int linformer_dims(const rsa_desc *d, int32_t Kp, Dims *own, Dims *att) {
   int rc = validate(d, own);
   if (rc != RSA_OK) return rc;
-  if (own->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16 || own->A != 64 || own->zigzag || own->causal)
+  if (own->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16 || own->zigzag || own->causal)
     return RSA_ERR_UNSUPPORTED;
   if (Kp < 64) return RSA_ERR_SHAPE;
   if (Kp % 64 != 0) return RSA_ERR_UNSUPPORTED;
   // the GEMM kernel indexes rows and columns of its operands with 32 bits
-  if (own->L >= (1LL << 31) || (int64_t)own->B * own->Z * 64 >= (1LL << 31)) return RSA_ERR_UNSUPPORTED;
+  if (own->L >= (1LL << 31) || (int64_t)own->B * own->Z * own->A >= (1LL << 31)) return RSA_ERR_UNSUPPORTED;
   *att = *own;
   att->N = 1; att->rank_begin = 0; att->rank_end = 1;
   att->L = Kp; att->c = Kp;  // Lq stays: the ranks' rows
@@ -424,11 +424,11 @@ int linformer_dims(const rsa_desc *d, int32_t Kp, Dims *own, Dims *att) {
 }
 size_t linformer_ws(const Dims &own, const Dims &att, int64_t Kp) {
   const int64_t Zt = (int64_t)own.B * own.Z;
-  const size_t part = (size_t)rsa::linformer_splits(Kp, Zt, own.Lq) * Kp * Zt * 64 * 4;
+  const size_t part = (size_t)rsa::linformer_splits(Kp, Zt, own.Lq, own.A) * Kp * Zt * own.A * 4;
   // backward: row terms, then the fp32 partial dV, dK of the split query walk
   const int qs = rsa::fused_bwd_dkdv_splits(att);
   const size_t bwd = fused_bwd_base(att) +
-                     (qs > 1 ? (size_t)2 * qs * Zt * Kp * 64 * 4 : 0);
+                     (qs > 1 ? (size_t)2 * qs * Zt * Kp * own.A * 4 : 0);
   return align256(part > bwd ? part : bwd);
 }
 }  // namespace
@@ -456,7 +456,7 @@ int rsa_linformer_project(const rsa_desc *d, int32_t Kp, const void *X, const vo
   if (ws_bytes < linformer_ws(own, att, Kp)) return RSA_ERR_WORKSPACE;
   const char *Xr = static_cast<const char *>(X) + row0 * own.A * 2;
   const char *Er = static_cast<const char *>(E) + row0 * Kp * 2;
-  return hip_status(rsa::linformer_project(Zt, own.L, own.Lq, Kp, Xr, Er, Xp, static_cast<float *>(ws), st));
+  return hip_status(rsa::linformer_project(Zt, own.L, own.Lq, Kp, own.A, Xr, Er, Xp, static_cast<float *>(ws), st));
 }
 
 int rsa_linformer_forward(const rsa_desc *d, int32_t Kp, const void *Q, const void *Kp_, const void *Vp_,
@@ -484,7 +484,7 @@ int rsa_linformer_project_bwd(const rsa_desc *d, int32_t Kp, const void *dXp, co
   const char *Er = static_cast<const char *>(E) + row0 * Kp * 2;
   char *dXr = static_cast<char *>(dX) + row0 * own.A * 2;
   float *dEr = dE + row0 * Kp;
-  return hip_status(rsa::linformer_project_bwd(Zt, own.L, own.Lq, Kp, dXp, Xr, Er, dXr, dEr, st));
+  return hip_status(rsa::linformer_project_bwd(Zt, own.L, own.Lq, Kp, own.A, dXp, Xr, Er, dXr, dEr, st));
 }
 
 }  // extern "C"

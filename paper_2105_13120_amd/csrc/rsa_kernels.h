@@ -70,13 +70,13 @@ hipError_t proj_qkv_bwd(const Dims &d, int64_t H, const void *dQ, const void *dK
                         const void *X, const void *W, void *dX, float *dW, float *part,
                         hipStream_t st);
 
-// --- Linformer projections along the sequence (Table 3, row Projection), bf16, A = 64 ---
-// Zt = B*Z heads; X, dX: (Zt, L, 64), used from a first token on for `rows` tokens (the pointers
-// passed are those of that first token); E: (rows, Kp); Xp, dXp: (Zt, Kp, 64); dE fp32 (rows, Kp).
-int linformer_splits(int64_t Kp, int64_t Zt, int64_t rows);
-hipError_t linformer_project(int64_t Zt, int64_t L, int64_t rows, int64_t Kp, const void *X,
+// --- Linformer projections along the sequence (Table 3, row Projection), bf16, A = 64 or 128 ---
+// Zt = B*Z heads; X, dX: (Zt, L, A), used from a first token on for `rows` tokens (the pointers
+// passed are those of that first token); E: (rows, Kp); Xp, dXp: (Zt, Kp, A); dE fp32 (rows, Kp).
+int linformer_splits(int64_t Kp, int64_t Zt, int64_t rows, int A);
+hipError_t linformer_project(int64_t Zt, int64_t L, int64_t rows, int64_t Kp, int A, const void *X,
                              const void *E, void *Xp, float *part, hipStream_t st);
-hipError_t linformer_project_bwd(int64_t Zt, int64_t L, int64_t rows, int64_t Kp, const void *dXp,
+hipError_t linformer_project_bwd(int64_t Zt, int64_t L, int64_t rows, int64_t Kp, int A, const void *dXp,
                                  const void *X, const void *E, void *dX, float *dE, hipStream_t st);
 
 }  // namespace rsa

@@ -413,56 +413,56 @@ hipError_t proj_qkv_bwd(const Dims &d, int64_t H, const void *dQ, const void *dK
 }
 
 // ---- Linformer projections along the sequence (Table 3, row Projection) ----
-// out (Zt, Kp, 64) bf16 = sum over the k splits of part[s][k][zt*64 + a], in a fixed order
+// out (Zt, Kp, A) bf16 = sum over the k splits of part[s][k][zt*A + a], in a fixed order
 __global__ void __launch_bounds__(256) ksplit_reduce_heads_kernel(const float *part, uint16_t *out,
-                                                                  int64_t Kp, int64_t Zt, int splits) {
+                                                                  int64_t Kp, int64_t Zt, int splits, int A) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;  // one group of 4 columns
-  const int64_t n4 = Zt * 16, total = Kp * n4;
+  const int64_t n4 = Zt * (A / 4), total = Kp * n4;
   if (i >= total) return;
   const int64_t k = i / n4, c = (i % n4) * 4;
   f32x4 s = reinterpret_cast<const f32x4 *>(part)[i];
   for (int j = 1; j < splits; ++j) s += reinterpret_cast<const f32x4 *>(part)[(int64_t)j * total + i];
   const u32x2 w = {pack_bf16(s[0], s[1]), pack_bf16(s[2], s[3])};
-  *reinterpret_cast<u32x2 *>(out + ((c / 64) * Kp + k) * 64 + (c & 63)) = w;
+  *reinterpret_cast<u32x2 *>(out + ((c / A) * Kp + k) * A + (c % A)) = w;
 }
 
-int linformer_splits(int64_t Kp, int64_t Zt, int64_t rows) {
-  return proj_wgrad_splits(Kp, Zt * 64, rows);
+int linformer_splits(int64_t Kp, int64_t Zt, int64_t rows, int A) {
+  return proj_wgrad_splits(Kp, Zt * A, rows);
 }
 
-// Xp (Zt, Kp, 64) = E^T X over `rows` tokens: X (Zt, L, 64) from token row0 on, E (rows, Kp) from row0 on
-hipError_t linformer_project(int64_t Zt, int64_t L, int64_t rows, int64_t Kp, const void *X,
+// Xp (Zt, Kp, A) = E^T X over `rows` tokens: X (Zt, L, A) from token row0 on, E (rows, Kp) from row0 on
+hipError_t linformer_project(int64_t Zt, int64_t L, int64_t rows, int64_t Kp, int A, const void *X,
                              const void *E, void *Xp, float *part, hipStream_t st) {
   GemmArgs g{};
-  g.M = Kp; g.N = Zt * 64; g.K = rows;
-  g.A = plain(E, Kp);                          // [K = token][M = k]
-  g.B = heads(X, nullptr, nullptr, L, (int)Zt);  // [K = token][N = (head, a)]; one "batch" of Zt heads
-  const int splits = linformer_splits(Kp, Zt, rows);
+  g.M = Kp; g.N = Zt * A; g.K = rows;
+  g.A = plain(E, Kp);                               // [K = token][M = k]
+  g.B = heads(X, nullptr, nullptr, L, (int)Zt, A);  // [K = token][N = (head, a)]; one "batch" of Zt heads
+  const int splits = linformer_splits(Kp, Zt, rows, A);
   g.out[0] = part; g.out_split = 0; g.out_ld = g.N;
   hipError_t e = launch_gemm<true, true, true>(g, splits, st);
   if (e != hipSuccess) return e;
-  const int64_t total = Kp * Zt * 16;
+  const int64_t total = Kp * Zt * (A / 4);
   hipLaunchKernelGGL(ksplit_reduce_heads_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                     part, static_cast<uint16_t *>(Xp), Kp, Zt, splits);
+                     part, static_cast<uint16_t *>(Xp), Kp, Zt, splits, A);
   return hipGetLastError();
 }
 
-// dX rows (Zt, L, 64) from row0 on = E dXp, and dE (rows, Kp) fp32 = sum over heads of X dXp^T
-hipError_t linformer_project_bwd(int64_t Zt, int64_t L, int64_t rows, int64_t Kp, const void *dXp,
+// dX rows (Zt, L, A) from row0 on = E dXp, and dE (rows, Kp) fp32 = sum over heads of X dXp^T
+hipError_t linformer_project_bwd(int64_t Zt, int64_t L, int64_t rows, int64_t Kp, int A, const void *dXp,
                                  const void *X, const void *E, void *dX, float *dE, hipStream_t st) {
   {
     GemmArgs g{};
-    g.M = rows; g.N = Zt * 64; g.K = Kp;
-    g.A = plain(E, Kp);                               // [M = token][K = k]
-    g.B = heads(dXp, nullptr, nullptr, Kp, (int)Zt);  // [K = k][N = (head, a)]
-    g.out[0] = dX; g.out_split = 1; g.out_rows = L; g.out_Z = (int)Zt; g.out_AH = 1;
+    g.M = rows; g.N = Zt * A; g.K = Kp;
+    g.A = plain(E, Kp);                                  // [M = token][K = k]
+    g.B = heads(dXp, nullptr, nullptr, Kp, (int)Zt, A);  // [K = k][N = (head, a)]
+    g.out[0] = dX; g.out_split = 1; g.out_rows = L; g.out_Z = (int)Zt; g.out_AH = A / 64;
     hipError_t e = launch_gemm<false, true, false>(g, 1, st);
     if (e != hipSuccess) return e;
   }
   GemmArgs g{};
-  g.M = rows; g.N = Kp; g.K = Zt * 64;
-  g.A = heads(X, nullptr, nullptr, L, (int)Zt);     // [M = token][K = (head, a)]
-  g.B = heads(dXp, nullptr, nullptr, Kp, (int)Zt);  // [N = k][K = (head, a)]
+  g.M = rows; g.N = Kp; g.K = Zt * A;
+  g.A = heads(X, nullptr, nullptr, L, (int)Zt, A);     // [M = token][K = (head, a)]
+  g.B = heads(dXp, nullptr, nullptr, Kp, (int)Zt, A);  // [N = k][K = (head, a)]
   g.out[0] = dE; g.out_split = 0; g.out_ld = Kp;
   return launch_gemm<false, false, true>(g, 1, st);
 }

@@ -23,19 +23,21 @@ def check_f32(name, got, ref):
     assert err <= 2e-4 * rms, f"{name}: max abs err {err:.3e} vs rms {rms:.3e}"
 
 
-# (B, Z, L, N, ranks, Kp)
+# (B, Z, L, N, ranks, Kp, A)
 CASES = [
-    (1, 1, 64, 1, (0, 1), 64),
-    (2, 2, 256, 2, (0, 2), 64),
-    (1, 3, 640, 5, (0, 5), 128),
-    (1, 2, 1024, 4, (1, 3), 192),      # two ranks' share: partial projections and gradients
-    (2, 4, 4096, 8, (0, 8), 256),
+    (1, 1, 64, 1, (0, 1), 64, 64),
+    (2, 2, 256, 2, (0, 2), 64, 64),
+    (1, 3, 640, 5, (0, 5), 128, 64),
+    (1, 2, 1024, 4, (1, 3), 192, 64),      # two ranks' share: partial projections and gradients
+    (2, 4, 4096, 8, (0, 8), 256, 64),
+    (1, 1, 64, 1, (0, 1), 64, 128),        # heads of 128 elements
+    (1, 3, 640, 5, (1, 4), 128, 128),
+    (2, 2, 2048, 8, (0, 8), 256, 128),
 ]
 
 
-@pytest.mark.parametrize("B,Z,L,N,ranks,Kp", CASES)
-def test_linformer_chain(B, Z, L, N, ranks, Kp):
-    A = 64
+@pytest.mark.parametrize("B,Z,L,N,ranks,Kp,A", CASES)
+def test_linformer_chain(B, Z, L, N, ranks, Kp, A):
     c = L // N
     r0, rows = ranks[0] * c, (ranks[1] - ranks[0]) * c
     K, V = draw((B, Z, L, A), 1), draw((B, Z, L, A), 2)
