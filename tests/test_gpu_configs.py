@@ -104,3 +104,16 @@ def test_wide_heads_8k_sampled():
     rng = np.random.Generator(np.random.PCG64(5))
     cols = np.concatenate([[0, 63, 64, 1023, 1024, 8191], rng.integers(0, cfg.L, 250)])
     sampled_check(cfg, x, out, head=13, row_blocks=[(0, 64), (1000, 64), (8192 - 96, 96)], cols=cols)
+
+
+def test_last_rank_of_a_256_rank_ring_sampled():
+    """Edge of the index ranges: 262144 tokens in 256 chunks, the last rank's 1024 rows under the
+    causal mask (token indices beyond 2^16, 256 ring steps, the key walk split over work-groups)."""
+    cfg = inputs.RSAConfig("edge", B=1, Z=2, L=262144, A=64, N=256, dtype="bf16", causal=True,
+                           rank_begin=255, rank_end=256, seed=3)
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x)
+    rng = np.random.Generator(np.random.PCG64(6))
+    cols = np.concatenate([[0, 1023, 1024, 131071, 131072, 261119, 261120, 262143],
+                           rng.integers(0, cfg.L, 120), rng.integers(261120, cfg.L, 60)])
+    sampled_check(cfg, x, out, head=1, row_blocks=[(0, 64), (500, 70), (1024 - 64, 64)], cols=cols)
