@@ -73,9 +73,14 @@ size_t fused_bwd_base(const Dims &d) {
 size_t workspace_bytes(const Dims &d, int dtype, int pass) {
   if (d.mode == RSA_MODE_STAGED) return staged_layout(d, dtype, pass).total;
   const size_t rows = (size_t)d.B * d.Z * d.Lq;
-  const int ks = rsa::fused_key_splits(d);
-  if (pass == 1) return fused_bwd_base(d) + (ks > 1 ? align256(ks * rows * d.A * 4) : 0);
-  return ks > 1 ? align256(ks * rows * (d.A + 2) * 4) : 0;
+  if (pass == 1) {
+    const int ks = rsa::fused_key_splits(d);
+    return fused_bwd_base(d) + (ks > 1 ? align256(ks * rows * d.A * 4) : 0);
+  }
+  bool big;
+  int fs;
+  rsa::fused_fwd_plan(d, &big, &fs);
+  return fs > 1 ? align256(fs * rows * (d.A + 2) * 4) : 0;
 }
 // where the split walks' partial sums start in the backward workspace
 inline float *fused_part(const Dims &d, void *ws) {
@@ -218,8 +223,7 @@ int rsa_forward(const rsa_desc *d, const void *Q, const void *K, const void *V, 
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (dm.mode == RSA_MODE_STAGED)
     return staged_forward(dm, d->dtype, Q, K, V, O, LSE, static_cast<char *>(ws), st);
-  return hip_status(rsa::fused_forward(dm, Q, K, V, O, LSE, st, static_cast<float *>(ws),
-                                       rsa::fused_key_splits(dm)));
+  return hip_status(rsa::fused_forward(dm, Q, K, V, O, LSE, st, static_cast<float *>(ws)));
 }
 
 int rsa_backward(const rsa_desc *d, const void *dO, const void *Q, const void *K, const void *V,
@@ -462,7 +466,7 @@ int rsa_linformer_project(const rsa_desc *d, int32_t Kp, const void *X, const vo
 int rsa_linformer_forward(const rsa_desc *d, int32_t Kp, const void *Q, const void *Kp_, const void *Vp_,
                           void *O, float *LSE, void *stream) {
   RSA_LINF_PROLOGUE(Q && Kp_ && Vp_ && O && LSE, Q, Kp_, Vp_, O, LSE);
-  return hip_status(rsa::fused_forward(att, Q, Kp_, Vp_, O, LSE, st, nullptr, 1));
+  return hip_status(rsa::fused_forward(att, Q, Kp_, Vp_, O, LSE, st, nullptr));
 }
 
 int rsa_linformer_backward(const rsa_desc *d, int32_t Kp, const void *dO, const void *Q, const void *Kp_,

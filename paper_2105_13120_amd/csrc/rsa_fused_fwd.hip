@@ -355,23 +355,49 @@ static hipError_t launch_fwd(const Dims &d, const FwdArgs &a, int64_t heads, int
   return hipGetLastError();
 }
 
-// Splits of the key walk for the forward and dQ kernels (both own 128 query rows per
-// work-group when the problem is small): 1 when the rows alone fill the chip.  A split
-// keeps at least 8 stages of 128 keys.  Under the causal mask the walks differ in length,
-// so more, shorter work-groups are wanted.
-int fused_key_splits(const Dims &d) {
-  const int64_t wgs = (int64_t)d.B * d.Z * ((d.Lq + 127) / 128);
-  const int64_t stages = d.L / 128;
-  const int64_t want = d.causal ? 3072 : 1536;
+// Splits of the key walk for a kernel whose work-groups own `rows_per_wg` query rows (two
+// work-groups per CU make 512 slots): 1 when the rows alone fill the chip.  Otherwise the smallest count whose work-groups fill whole rounds of the 512 slots
+// to 95 % -- a round that is half empty costs as much as a full one -- with at least 16 stages
+// of 128 keys left per split (shorter walks lose more to their prologue and to the merge than
+// the better fill gains).  Under the causal mask walks differ in length, so at least three
+// rounds are wanted; under zig-zag ownership half of the row tiles see almost no keys and do
+// not count.  When no count qualifies, the largest one allowed.
+static int key_splits_for(const Dims &d, int rows_per_wg) {
+  int64_t wgs = (int64_t)d.B * d.Z * ((d.Lq + rows_per_wg - 1) / rows_per_wg);
   if (wgs >= 1024) return 1;
-  int64_t s = (want + wgs - 1) / wgs;
-  if (s > stages / 8) s = stages / 8;
-  if (s > 32) s = 32;
-  return s < 2 ? 1 : (int)s;
+  int64_t stages = d.L / 128;  // the longest walk of a row tile
+  if (d.causal && !d.zigzag && (int64_t)d.rank_end * d.c / 128 < stages) stages = (int64_t)d.rank_end * d.c / 128;
+  const int64_t smax = stages / 16 < 32 ? stages / 16 : 32;
+  if (smax < 2) return 1;
+  if (d.causal && d.zigzag) wgs = (wgs + 1) / 2;
+  const int64_t min_rounds = d.causal ? 3 : 1;
+  for (int64_t s = 1; s <= smax; ++s) {
+    const int64_t n = s * wgs, rounds = (n + 511) / 512;
+    if (rounds >= min_rounds && n * 20 >= rounds * 512 * 19) return (int)s;
+  }
+  return (int)smax;
+}
+
+// the dQ kernel: 128 rows per work-group
+int fused_key_splits(const Dims &d) { return key_splits_for(d, 128); }
+
+// The forward: 64 rows per wave (256 per work-group) halve the LDS traffic per flop and are
+// taken when their work-groups, times their splits, fill the 512 slots at least once; else 32
+// rows per wave, which give twice the work-groups.  (A head of 128 elements takes 32 rows per
+// wave and one key tile per stage: registers and LDS.)
+void fused_fwd_plan(const Dims &d, bool *big, int *splits) {
+  if (d.A == 64 && d.Lq % 256 == 0) {
+    const int s = key_splits_for(d, 256);
+    if ((int64_t)d.B * d.Z * (d.Lq / 256) * s >= 512) {
+      *big = true; *splits = s;
+      return;
+    }
+  }
+  *big = false; *splits = key_splits_for(d, 128);
 }
 
 hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void *V, void *O,
-                         float *LSE, hipStream_t st, float *part, int splits) {
+                         float *LSE, hipStream_t st, float *part) {
   FwdArgs a;
   a.Q = (const uint16_t *)Q; a.K = (const uint16_t *)K; a.V = (const uint16_t *)V;
   a.O = (uint16_t *)O; a.LSE = LSE;
@@ -379,11 +405,10 @@ hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void
   a.N = d.N;
   a.cl2 = d.scale * kLog2e;
   const int64_t heads = (int64_t)d.B * d.Z;
-  // 64 rows per wave halves the LDS traffic per flop; 32 rows per wave gives
-  // twice the work-groups when the problem is too small to fill 256 CUs twice over.
+  bool big;
+  int splits;
+  fused_fwd_plan(d, &big, &splits);
   if (!part) splits = 1;
-  // (a head of 128 takes 32 rows per wave and one key tile per stage: registers and LDS)
-  const bool big = d.A == 64 && (d.Lq % 256 == 0) && heads * (d.Lq / 256) * splits >= 512;
   const int64_t rows = heads * d.Lq;
   a.part_o = part;
   a.part_ml = part ? part + (int64_t)splits * rows * d.A : nullptr;

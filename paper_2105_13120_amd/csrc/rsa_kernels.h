@@ -34,11 +34,13 @@ hipError_t store_rows(int dtype, const float *src, void *dst, int64_t batches,
 hipError_t zero_f32(float *p, int64_t n, hipStream_t st);
 
 // --- fused (online-softmax) path, bf16, A = 64 or 128 ---
-// part / splits: optional split of the walk over the keys (few query rows, many keys), see
-// fused_key_splits: fp32 partial results, splits * B*Z*Lq * (A + 2) floats; nullptr / 1: none
+// Split of the walk over the keys (few query rows, many keys).  fused_fwd_plan: the forward's
+// rows per work-group (big: 256, else 128) and its split count; part: its fp32 partial results,
+// splits * B*Z*Lq * (A + 2) floats, or nullptr for no split.  fused_key_splits: the dQ kernel's count.
+void fused_fwd_plan(const Dims &d, bool *big, int *splits);
 int fused_key_splits(const Dims &d);
 hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void *V, void *O,
-                         float *LSE, hipStream_t st, float *part, int splits);
+                         float *LSE, hipStream_t st, float *part);
 // nD = -rowsum(dO o O) and nL = -LSE log2e, (B,Z,Lq) fp32
 hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, const float *LSE,
                                 float *nD, float *nL, hipStream_t st);

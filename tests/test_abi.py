@@ -82,7 +82,7 @@ def test_workspace_sizes_follow_table2():
     assert rsa.workspace_bytes(desc(N=3), True) == 0          # invalid descriptor
     # one rank's share of a long sequence: the key walk is split, fp32 partial results per split
     d = desc(B=1, Z=2, L=4096, N=4, rank_begin=3, rank_end=4)
-    rows, splits = 1 * 2 * 1024, 4
+    rows, splits = 1 * 2 * 1024, 2          # 32 stages of 128 keys: at most 2 splits of 16
     assert rsa.workspace_bytes(d, False) == splits * rows * (64 + 2) * 4
     assert rsa.workspace_bytes(d, True) == 2 * rows * 4 + splits * rows * 64 * 4
     for s in range(-5, 1):

@@ -77,12 +77,13 @@ def test_fused_rank_subrange_gives_partial_sums(causal, rb, re):
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("B,Z,L,N,rb,re,zigzag", [
     (1, 2, 4096, 4, 3, 4, False),    # last rank of four: every split of the key walk has work
-    (1, 2, 4096, 4, 0, 1, False),    # first rank: under the mask only its own chunk is visible
-    (1, 1, 4096, 8, 2, 5, False),    # three ranks, ring walks that wrap around
+    (1, 2, 8192, 8, 0, 2, False),    # first ranks: under the mask only their own chunks are visible (no split)
+    (1, 1, 8192, 16, 4, 10, False),  # six ranks, ring walks that wrap around
     (1, 2, 4096, 2, 0, 1, True),     # zig-zag share: its first half sees few keys, its second all
-    (1, 1, 6144, 3, 1, 2, True),     # odd ring size, 6 splits
-    (1, 1, 2304, 9, 8, 9, False),    # 18 stages in 2 splits: the boundary falls inside a chunk
-    (1, 1, 2112, 11, 10, 11, False), # chunks of 3 tiles: one tile per stage
+    (1, 1, 6144, 3, 1, 2, True),     # odd ring size, 3 splits
+    (1, 1, 4608, 9, 8, 9, False),    # 36 stages in 2 splits: the boundary falls inside a chunk
+    (1, 1, 4224, 11, 10, 11, False), # chunks of 6 tiles
+    (1, 1, 6336, 33, 32, 33, False), # chunks of 3 tiles: one tile per stage, 49 stages in 3 splits
 ])
 def test_split_key_walk(B, Z, L, N, rb, re, zigzag, causal):
     """Few query rows against many keys: the forward and dQ kernels divide the walk over the keys
@@ -90,17 +91,19 @@ def test_split_key_walk(B, Z, L, N, rb, re, zigzag, causal):
     cfg = cfg_of(B, Z, L, N, causal, rb=rb, re=re, seed=43, zigzag=zigzag)
     desc = rsa.make_desc(torch.empty(B, Z, L, 64, dtype=torch.bfloat16), N, causal=causal,
                          rank_begin=rb, rank_end=re, zigzag=zigzag)
-    assert rsa.workspace_bytes(desc, False) > 0     # the split is on for this shape
+    # the split is on for these shapes, except where the mask hides most of the keys
+    assert (rsa.workspace_bytes(desc, False) > 0) == (not (causal and rb == 0 and not zigzag))
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x)
     compare_heads(cfg, x, out, list(range(B * Z)))
 
 
 @pytest.mark.parametrize("causal", [False, True])
-@pytest.mark.parametrize("rb,zigzag", [(7, False), (0, True), (3, True)])
+@pytest.mark.parametrize("rb,zigzag", [(15, False), (0, True), (3, True)])
 def test_split_key_walk_with_256_row_tiles(rb, zigzag, causal):
-    """Enough heads that the split forward takes its 256-row work-groups."""
-    cfg = cfg_of(2, 8, 8192, 8, causal, rb=rb, re=rb + 1, seed=47, zigzag=zigzag)
+    """Enough heads and keys that the split forward takes its 256-row work-groups
+    (16 heads x 4 row tiles x 8 splits = 512 work-groups)."""
+    cfg = cfg_of(2, 8, 16384, 16, causal, rb=rb, re=rb + 1, seed=47, zigzag=zigzag)
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x)
     compare_heads(cfg, x, out, [0, 6, 15])
