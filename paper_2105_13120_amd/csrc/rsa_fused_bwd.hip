@@ -510,17 +510,21 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
             dp[qb] = mfma_32x32x16(va, greg[qb][dk], dk == 0 ? negd[qb] : dp[qb]);
           }
         }
+        if (domask) {  // uniform over the wave: only tiles on the diagonal pay for the mask
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb) {
+            // last visible key of the lane's row, relative to the block of 32 keys (32-bit compare)
+            const int64_t d64 = qtok[qb] - k0 - kb * 32 - half * 4;
+            const int dlast = d64 > 64 ? 64 : (int)d64;
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+              if ((v >> 2) * 8 + (v & 3) > dlast) s[qb][v] = -INFINITY;
+          }
+        }
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-          // last visible key of the lane's row, relative to the block of 32 keys (32-bit compare)
-          const int64_t d64 = qtok[qb] - k0 - kb * 32 - half * 4;
-          const int dlast = d64 > 64 ? 64 : (int)d64;
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            float x = s[qb][v];
-            if (domask && (v >> 2) * 8 + (v & 3) > dlast) x = -INFINITY;
-            dp[qb][v] *= __builtin_amdgcn_exp2f(x);
-          }
+          for (int v = 0; v < 16; ++v) dp[qb][v] *= __builtin_amdgcn_exp2f(s[qb][v]);
 #pragma unroll
           for (int u = 0; u < 2; ++u) {
             u32x4 w = {pack_bf16(dp[qb][u * 8 + 0], dp[qb][u * 8 + 1]), pack_bf16(dp[qb][u * 8 + 2], dp[qb][u * 8 + 3]),
