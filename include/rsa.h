@@ -20,7 +20,8 @@
  *    the ring's all-reduce of section 3.2.2 would add up).  dQ, dK, dV are
  *    overwritten, not accumulated into.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    Work is enqueued asynchronously; no call synchronises.
+ *    Work is enqueued asynchronously; no call synchronises, allocates or
+ *    records a memset, so a sequence of calls can be captured in a HIP graph.
  *  - Every call returns an rsa_status.  Arguments are validated on the host
  *    before anything is launched; on error nothing has been enqueued.
  *  - dtype RSA_BF16: bf16 storage, fp32 accumulation and fp32 softmax, one

@@ -1,0 +1,59 @@
+"""The library allocates nothing and records no memset: its launch sequences can be captured in a
+HIP graph.  Every replay is checked against the eager result, with eager work in between."""
+import pytest
+import torch
+
+from helpers import upload
+from paper_2105_13120_amd import inputs, rsa
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("mode,kw", [
+    (rsa.MODE_FUSED, dict(B=2, Z=2, L=512, N=4, causal=True)),
+    (rsa.MODE_FUSED, dict(B=1, Z=2, L=4096, N=4, causal=False, rank_begin=3, rank_end=4)),   # split key walk
+    (rsa.MODE_FUSED, dict(B=1, Z=2, L=1024, N=4, causal=True, zigzag=True, A=128)),
+    (rsa.MODE_STAGED, dict(B=1, Z=2, L=256, N=2, causal=False)),
+])
+def test_forward_backward_under_graph_capture(mode, kw):
+    kw = dict(kw)
+    A = kw.pop("A", 64)
+    cfg = inputs.RSAConfig("g", A=A, dtype="bf16", seed=61, **kw)
+    x = inputs.make_inputs(cfg)
+    Q, K, V, dO = (upload(x[k], "bf16") for k in ("Q", "K", "V", "dO"))
+    rb, re = cfg.ranks
+    desc = rsa.make_desc(K, cfg.N, causal=cfg.causal, rank_begin=rb, rank_end=re, mode=mode, zigzag=cfg.zigzag)
+    wf = torch.empty(max(rsa.workspace_bytes(desc, False), 16), dtype=torch.uint8, device="cuda")
+    wb = torch.empty(max(rsa.workspace_bytes(desc, True), 16), dtype=torch.uint8, device="cuda")
+
+    def buffers():
+        return dict(O=torch.empty_like(Q), LSE=torch.empty(Q.shape[:3], dtype=torch.float32, device="cuda"),
+                    dQ=torch.empty_like(Q), dK=torch.empty_like(K), dV=torch.empty_like(V))
+
+    def run(b):
+        rsa.forward(desc, Q, K, V, O=b["O"], LSE=b["LSE"], ws=wf)
+        rsa.backward(desc, dO, Q, K, V, b["O"], b["LSE"], dQ=b["dQ"], dK=b["dK"], dV=b["dV"], ws=wb)
+
+    eager = buffers()
+    run(eager)
+    torch.cuda.synchronize()
+    ref = {k: v.clone() for k, v in eager.items()}
+
+    g = buffers()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(g)                                  # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run(g)
+    for replay in range(3):
+        for v in g.values():
+            v.fill_(float("nan")) if v.dtype != torch.float32 else v.fill_(-1.0)
+        wf.fill_(0xFF); wb.fill_(0xFF)          # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in ref:
+            assert torch.equal(g[k], ref[k]), f"replay {replay}: {k} differs from the eager result"
