@@ -65,6 +65,28 @@ def event_ms(fn, iters, torch):
     return s.elapsed_time(e) / iters
 
 
+def event_stats(fns, iters, torch):
+    """Median and minimum over `iters` single passes of every function in fns (run one after the
+    other inside each pass), each pass bracketed by its own HIP events: {name: (median, min)} in ms,
+    plus "step" for the whole pass."""
+    names = list(fns)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(iters)]
+    torch.cuda.synchronize()
+    for it in range(iters):
+        ev[it][0].record()
+        for j, n in enumerate(names):
+            fns[n]()
+            ev[it][j + 1].record()
+    torch.cuda.synchronize()
+    out = {}
+    for j, n in enumerate(names):
+        t = sorted(ev[it][j].elapsed_time(ev[it][j + 1]) for it in range(iters))
+        out[n] = (t[len(t) // 2], t[0])
+    t = sorted(ev[it][0].elapsed_time(ev[it][-1]) for it in range(iters))
+    out["step"] = (t[len(t) // 2], t[0])
+    return out
+
+
 def setup(cfg, torch, rsa, inputs):
     x = inputs.make_inputs(cfg)
     dt = torch.bfloat16
@@ -120,6 +142,8 @@ def time_workload(cfg, steps, warmup, torch, rsa, inputs, per_kernel=True):
                                it, torch),
         }
         res["kernel_ms"] = k
+        st = event_stats({"fwd": fwd, "bwd": bwd}, max(5, min(steps, 200)), torch)
+        res["pass_ms"] = {n: {"median": round(v[0], 4), "min": round(v[1], 4)} for n, v in st.items()}
     return res, x
 
 
@@ -296,6 +320,7 @@ def main():
         "frac_of_bf16_peak": round(res["tflops"] / PEAK_BF16_TFLOPS, 4),
         "tokens_per_s": round(res["tokens_per_s"], 1),
         "kernel_ms": {n: round(v, 4) for n, v in k.items()},
+        "pass_ms": res["pass_ms"],
         "roofline": {"bound": "mfma", "kernel": "fused_bwd_dkdv_kernel", "achieved": round(achieved, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
