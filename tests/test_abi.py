@@ -89,6 +89,24 @@ def test_workspace_sizes_follow_table2():
         assert rsa.strerror(s)
 
 
+def test_split_plan_of_the_key_walk():
+    """Host logic behind rsa_workspace_bytes in fused mode: how many work-groups share a row
+    tile's walk over the keys (forward: (A + 2) floats per row and split; dQ: A floats)."""
+    def splits(d):
+        rows = d.B * d.Z * (d.rank_end - d.rank_begin) * (d.L // d.N)
+        f = rsa.workspace_bytes(d, False) // (rows * (d.A + 2) * 4)
+        b = (rsa.workspace_bytes(d, True) - 2 * rows * 4) // (rows * d.A * 4)
+        return max(f, 1), max(b, 1)
+    big = dict(B=1, Z=12, L=65536, N=16, causal=1)
+    assert splits(desc(B=8, Z=16, L=2048, N=8, rank_end=8)) == (1, 1)          # whole ring: rows fill the chip
+    assert splits(desc(B=8, Z=16, L=2048, N=8, rank_begin=3, rank_end=4)) == (1, 1)   # 16 stages: too short to split
+    assert splits(desc(rank_begin=15, rank_end=16, **big)) == (8, 4)          # 192 x 8 and 384 x 4 = 3 full rounds
+    assert splits(desc(rank_begin=0, rank_end=1, **big)) == (2, 2)            # first rank under the mask sees 32 stages: 2 x 16
+    assert splits(desc(rank_begin=0, rank_end=1, flags=rsa.OWN_ZIGZAG, **big)) == (16, 8)   # half the tiles are long
+    assert splits(desc(B=2, Z=16, L=16384, N=32, rank_begin=9, rank_end=10)) == (8, 4)     # 64 x 8 (256-row tiles) and 128 x 4: one round
+    assert splits(desc(B=4, Z=8, A=128, L=8192, N=8, rank_begin=2, rank_end=3)) == (2, 2)
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(rsa, "_lib", None)
     monkeypatch.setattr(rsa, "LIB_PATH", "/nonexistent/librsa_hip.so")
