@@ -248,6 +248,15 @@ def staged_report(cfg, torch, rsa, inputs):
         "av_step": event_ms(lambda: rsa.av_step(desc, n, 1 % N, P, t["V"], Oacc, 0), 10, torch),
         "softmax_bwd": event_ms(lambda: rsa.softmax_bwd(desc, n, P, S, D, dS), 10, torch),
     }
+    # the whole ring in this layout: every rank's two passes, forward and backward
+    del S, P, dS, Oacc
+    O = torch.empty_like(t["Q"])
+    dQ, dK, dV = torch.empty_like(t["Q"]), torch.empty_like(t["K"]), torch.empty_like(t["V"])
+    wf = torch.empty(max(rsa.workspace_bytes(desc, False), 16), dtype=torch.uint8, device=dev)
+    wb = torch.empty(max(rsa.workspace_bytes(desc, True), 16), dtype=torch.uint8, device=dev)
+    ms["ring_forward"] = event_ms(lambda: rsa.forward(desc, t["Q"], t["K"], t["V"], O=O, LSE=LSE, ws=wf), 3, torch)
+    ms["ring_backward"] = event_ms(lambda: rsa.backward(desc, t["dO"], t["Q"], t["K"], t["V"], O, LSE, dQ=dQ,
+                                                        dK=dK, dV=dV, ws=wb), 3, torch)
     gbs = lambda nbytes, m: nbytes / (m * 1e-3) / 1e9
     # algorithmic bytes: softmax reads 4 B and writes 2 B per score; softmax backward reads
     # P (2 B) and dP (4 B) and writes dS (2 B); a qk step writes 4 B per score of its block
@@ -258,6 +267,7 @@ def staged_report(cfg, torch, rsa, inputs):
         "qk_step_write_GBps": round(gbs(4 * scores / N, ms["qk_step"]), 1),
         "hbm_peak_GBps": PEAK_HBM_GBS,
         "strip_bytes_forward_all_ranks": (4 + 4 + 2 + 2) * scores * N,
+        "ring_tflops": round(cfg.flops() / ((ms["ring_forward"] + ms["ring_backward"]) * 1e-3) / 1e12, 1),
     }
 
 
