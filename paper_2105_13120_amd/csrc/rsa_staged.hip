@@ -353,6 +353,61 @@ __global__ void __launch_bounds__(256) row_softmax_reg_kernel(const float *S, Ou
   }
 }
 
+// Longer rows, L = 1024 nv with nv <= 32: one work-group per row, 4 nv values per thread in
+// registers, the maximum and the sum merged across the four waves through LDS.
+template <typename OutT>
+__global__ void __launch_bounds__(256) row_softmax_wg_kernel(const float *S, OutT *P, float *LSE, int nv,
+                                                             int64_t c, int64_t Lq, int64_t row_off) {
+  constexpr int NVMAX = 32;
+  __shared__ float red[8];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t row = blockIdx.x, L = 1024 * (int64_t)nv;
+  const float *s = S + row * L;
+  f32x4 x[NVMAX];
+  float m = -INFINITY;
+#pragma unroll
+  for (int v = 0; v < NVMAX; ++v)
+    if (v < nv) {
+      x[v] = *reinterpret_cast<const f32x4 *>(s + v * 1024 + tid * 4);
+      m = fmaxf(m, fmaxf(fmaxf(x[v][0], x[v][1]), fmaxf(x[v][2], x[v][3])));
+    }
+  m = wave_max(m);
+  if (lane == 0) red[wave] = m;
+  __syncthreads();
+  const float M = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));  // finite: some score is unmasked
+  const float mc = M * kLog2e;
+  float l = 0.f;
+#pragma unroll
+  for (int v = 0; v < NVMAX; ++v)
+    if (v < nv) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        x[v][k] = exp2f(fmaf(x[v][k], kLog2e, -mc));
+        l += x[v][k];
+      }
+    }
+  l = wave_sum(l);
+  if (lane == 0) red[4 + wave] = l;
+  __syncthreads();
+  const float lsum = (red[4] + red[5]) + (red[6] + red[7]);
+  const float inv = 1.0f / lsum;
+  OutT *p = P + row * L;
+#pragma unroll
+  for (int v = 0; v < NVMAX; ++v)
+    if (v < nv) {
+      if constexpr (sizeof(OutT) == 2) {
+        u32x2 o = {pack_bf16(x[v][0] * inv, x[v][1] * inv), pack_bf16(x[v][2] * inv, x[v][3] * inv)};
+        *reinterpret_cast<u32x2 *>(p + v * 1024 + tid * 4) = o;
+      } else {
+        *reinterpret_cast<f32x4 *>(p + v * 1024 + tid * 4) = x[v] * inv;
+      }
+    }
+  if (tid == 0) {
+    const int64_t head = row / c, r = row % c;
+    LSE[head * Lq + row_off + r] = M + logf(lsum);
+  }
+}
+
 template <typename OutT>
 static bool launch_row_softmax_reg(const float *S, OutT *P, float *LSE, int64_t rows, int64_t L, int64_t c,
                                    int64_t Lq, int64_t row_off, hipStream_t st) {
@@ -365,6 +420,11 @@ static bool launch_row_softmax_reg(const float *S, OutT *P, float *LSE, int64_t 
   }
   RSA_ROWSM(1) RSA_ROWSM(2) RSA_ROWSM(4) RSA_ROWSM(8) RSA_ROWSM(16)
 #undef RSA_ROWSM
+  if (L % 1024 == 0 && L <= 32768 && rows < (1LL << 31)) {
+    hipLaunchKernelGGL((row_softmax_wg_kernel<OutT>), dim3((unsigned)rows), dim3(256), 0, st, S, P, LSE,
+                       (int)(L / 1024), c, Lq, row_off);
+    return true;
+  }
   return false;
 }
 

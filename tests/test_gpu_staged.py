@@ -125,3 +125,13 @@ def test_staged_heads_wider_than_64(dtype, A, causal, rb, re):
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED)
     compare_heads(cfg, x, out, [0, 1])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,N,causal", [(5120, 5, False), (8192, 4, True)])
+def test_staged_forward_with_long_rows(dtype, L, N, causal):
+    """Rows of more than 4096 scores: the softmax keeps a row in the registers of one work-group."""
+    cfg = small_cfg(dtype, causal, B=1, Z=1, L=L, N=N, rb=N - 1, re=N, seed=31)
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED, backward=False)
+    compare_heads(cfg, x, out, [0], backward=False)
