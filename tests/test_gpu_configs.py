@@ -117,3 +117,11 @@ def test_last_rank_of_a_256_rank_ring_sampled():
     cols = np.concatenate([[0, 1023, 1024, 131071, 131072, 261119, 261120, 262143],
                            rng.integers(0, cfg.L, 120), rng.integers(261120, cfg.L, 60)])
     sampled_check(cfg, x, out, head=1, row_blocks=[(0, 64), (500, 70), (1024 - 64, 64)], cols=cols)
+
+
+def test_bert_large_staged_layout_sampled_heads():
+    """The paper's two-pass layout at config 3's full size (strip of 67 M scores per rank)."""
+    cfg = inputs.CONFIGS["bert_large"]
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED)
+    print(compare_heads(cfg, x, out, [0, 77, 127]))
