@@ -120,7 +120,7 @@ def test_last_rank_of_a_256_rank_ring_sampled():
 
 
 def test_bert_large_staged_layout_sampled_heads():
-    """The paper's two-pass layout at config 3's full size (strip of 67 M scores per rank)."""
+    """The paper's two-pass layout at the full size of the bert_large workload (strip of 67 M scores per rank)."""
     cfg = inputs.CONFIGS["bert_large"]
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED)

@@ -100,7 +100,7 @@ def test_each_step_against_the_oracle(dtype, causal):
 
 
 def test_config_tiny_f32_forward():
-    """BASELINE config 1: B1 Z2 L256 N4 fp32, forward only, max abs err <= 1e-4."""
+    """The small fp32 workload (tiny_f32: B1 Z2 L256 N4), forward only, max abs err <= 1e-4."""
     cfg = inputs.CONFIGS["tiny_f32"]
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED, backward=False)
