@@ -22,6 +22,7 @@ def test_bert_large_sampled_heads():
     cfg = inputs.CONFIGS["bert_large"]
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x)
+    check_sum_rules(cfg, x, out)
     print(compare_heads(cfg, x, out, [0, 15, 64, 127]))
 
 
@@ -56,10 +57,26 @@ def sampled_check(cfg, x, out, head, row_blocks, cols):
         assert np.abs(LSE[r0:r0 + nr] - LSE_ref[0, 0]).max() <= LSE_ATOL
 
 
+def check_sum_rules(cfg, x, out):
+    """Properties of the backward that hold at any size, on every head: rows of P sum to 1, so
+    sum_j dV_j = sum_i dO_i; rows of dS sum to 0, so sum_j dK_j = 0.  The stored gradients carry
+    one bf16 rounding per element (2^-9 relative, independent), so a sum over L keys may be off by
+    about sqrt(L) 2^-9 rms; the bound is 8 times that."""
+    dV, dK = download(out["dV"]), download(out["dK"])
+    dO = x["dO"].astype(np.float64)
+    L = cfg.L
+    for name, got, want in (("dV", dV.sum(axis=2), dO.sum(axis=2)), ("dK", dK.sum(axis=2), 0.0)):
+        g = dV if name == "dV" else dK
+        rms = np.sqrt(np.mean(g.astype(np.float64) ** 2, axis=(2, 3), keepdims=False))[..., None]
+        bound = 8.0 * np.sqrt(L) * 2.0 ** -9 * rms
+        assert (np.abs(got - want) <= bound).all(), f"sum rule for {name}"
+
+
 def test_long_32k_sampled():
     cfg = inputs.CONFIGS["long_32k"]
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x)
+    check_sum_rules(cfg, x, out)
     rng = np.random.Generator(np.random.PCG64(1))
     cols = np.concatenate([[0, 63, 64, 2047, 2048, 32767], rng.integers(0, cfg.L, 250)])
     sampled_check(cfg, x, out, head=5, row_blocks=[(0, 64), (2016, 64), (32768 - 96, 96)], cols=cols)
@@ -80,6 +97,7 @@ def test_causal_ring_32k_sampled():
     cfg = inputs.CONFIGS["causal_ring_32k"]
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x)
+    check_sum_rules(cfg, x, out)
     rng = np.random.Generator(np.random.PCG64(3))
     cols = np.concatenate([[0, 63, 64, 2047, 2048, 32767], rng.integers(0, cfg.L, 250)])
     sampled_check(cfg, x, out, head=9, row_blocks=[(0, 64), (2016, 64), (20000, 64), (32768 - 96, 96)], cols=cols)
