@@ -157,10 +157,10 @@ int rsa_store(const rsa_desc *d, const float *src, void *dst, size_t count,
  * into its prologue, then the dK/dV kernel; the three calls below in the order
  * given produce the same gradients up to the fp32 summation order of D.
  *  rsa_bwd_preprocess: fills ws with the row terms -D_i = -sum_a dO_ia O_ia and
- *    -LSE_i log2(e) (fp32).  Both other kernels recompute
- *    P = exp2(s log2(e) Q K^T - LSE log2 e) tile by tile, with the factor
- *    s log2(e) folded into the operand they keep in registers (K in the dK/dV
- *    kernel, Q in the dQ kernel; one rounding to bf16), and read the row terms.
+ *    -LSE_i / s (fp32).  Both other kernels recompute
+ *    P = exp2(s log2(e) (Q K^T - LSE / s)) tile by tile from the caller's Q and K
+ *    (the factor is applied in fp32; no operand is rounded a second time) and
+ *    read the row terms.
  *  rsa_bwd_dkdv: for every key chunk, the walk over the query rows of all
  *    simulated ranks -- dV = sum_n P^T dO, dK = s sum_n dS^T Q (the sums the
  *    ring all-reduces, section 3.2.2).  Also forms dP = dO V^T for its tiles.

@@ -62,7 +62,7 @@ StagedWs staged_layout(const Dims &d, int dtype, int pass) {
   return w;
 }
 
-// Fused backward: the row terms -D and -LSE log2e (fp32 per row)
+// Fused backward: the row terms -D and -LSE / scale (fp32 per row)
 size_t fused_bwd_base(const Dims &d) {
   const size_t rows = (size_t)d.B * d.Z * d.Lq;
   return 2 * align256(rows * 4);
@@ -87,7 +87,7 @@ inline float *fused_part(const Dims &d, void *ws) {
   return reinterpret_cast<float *>(static_cast<char *>(ws) + fused_bwd_base(d));
 }
 
-// Fused backward workspace: -D at the start, -LSE log2e next.
+// Fused backward workspace: -D at the start, -LSE / scale next.
 inline float *fused_nD(void *ws) { return static_cast<float *>(ws); }
 inline float *fused_nL(const Dims &d, void *ws) {
   return reinterpret_cast<float *>(static_cast<char *>(ws) + align256((size_t)d.B * d.Z * d.Lq * 4));

@@ -34,19 +34,6 @@ __device__ __forceinline__ uint32_t pack_bf16(float x, float y) {
   return __builtin_bit_cast(uint32_t, r);
 }
 
-// Eight bf16 values times a scalar, rounded back to bf16 (nearest even).
-__device__ __forceinline__ bf16x8 scale_bf16x8(bf16x8 x, float c) {
-  const u32x4 u = __builtin_bit_cast(u32x4, x);
-  u32x4 r;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const float lo = __builtin_bit_cast(float, u[e] << 16) * c;
-    const float hi = __builtin_bit_cast(float, u[e] & 0xffff0000u) * c;
-    r[e] = pack_bf16(lo, hi);
-  }
-  return __builtin_bit_cast(bf16x8, r);
-}
-
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
   return __builtin_bit_cast(float, (uint32_t)b << 16);
 }

@@ -2,20 +2,24 @@
 // with the ring structure of section 3.2.2, without the score strip in memory.
 // P is recomputed from Q, K and the forward's LSE: P = exp(s QK^T - LSE).
 //
-//   preprocess: the row terms -D = -rowsum(dO o O) and -LSE log2e; a kernel of its own for the
+//   preprocess: the row terms -D = -rowsum(dO o O) and -LSE / s; a kernel of its own for the
 //     step-level entry point, the prologue of the dQ kernel in rsa_backward.
-//   Both kernels recompute P = exp2(s log2e Q K^T - LSE log2e) with the factor s log2e folded into
-//   the operand they hold in registers, rounded to bf16: K in the dK/dV kernel, Q in the dQ kernel.
+//   Both kernels recompute P = exp2(s log2e (Q K^T - LSE / s)): the matrix core forms the bracket
+//   from the caller's bf16 Q and K as they are (its accumulator starts from -LSE / s) and the
+//   factor s log2e is applied to the fp32 result, one multiply per score.  Folding that factor
+//   into a bf16 operand instead would save the multiply and round the operand a second time:
+//   an error of 2^-9 per element that is the same for every score of a key (or query), adds up
+//   coherently in dK (or dQ) and more than doubles their largest error.
 //   dkdv kernel: a work-group owns 4*32 keys and walks the query tiles of every
 //     simulated rank, starting with the rank that holds those keys (ring
 //     order); the sum over ranks that the ring would all-reduce is its loop.
-//       S' = Q Ks^T - LSE log2e, dP' = dO V^T - D   (A: Q / dO rows from LDS; B: Ks / V registers;
+//       S' = Q K^T - LSE / s, dP' = dO V^T - D      (A: Q / dO rows from LDS; B: K / V registers;
 //                                                    the row terms are the accumulators' start)
-//       P = exp2(S'), dS = P o dP'
+//       P = exp2(s log2e S'), dS = P o dP'
 //       dV^T += dO^T P, dK^T += Q^T dS   (A operand: LDS transpose reads; B: P / dS registers)
 //   dq kernel: a work-group owns 4*R query rows and walks the K/V tiles in ring
 //     order (the paper's second K ring pass):
-//       S'^T = K Qs^T - LSE log2e (Qs = bf16(Q * scale * log2 e), formed in registers),
+//       S'^T = K Q^T - LSE / s, P^T = exp2(s log2e S'^T),
 //       dP'^T = V dO^T - D, dS^T = P^T o dP'^T, dQ^T += K^T dS^T
 #include "rsa_fused_tile.h"
 #include "rsa_kernels.h"
@@ -24,7 +28,7 @@ namespace rsa {
 
 struct BwdArgs {
   const uint16_t *Q, *K, *V, *dO;
-  const float *nL, *nD;                 // -LSE log2e and -D per query row
+  const float *nL, *nD;                 // -LSE / scale and -D per query row
   // dQ kernel with the preprocess folded in: it forms the row terms from O and LSE
   // itself and leaves them in nL_out, nD_out for the dK/dV kernel that follows
   const uint16_t *O;
@@ -37,14 +41,14 @@ struct BwdArgs {
   int64_t L, c, Lq;
   RowMap map;  // local query row -> global token index
   int N, tiles_per_head;
-  float cl2, scale;
+  float cl2, scale, inv_scale;  // scale log2(e), scale, 1 / scale
 };
 
 // ------------------------------------------------------------- preprocess ---
-// nD_i = -sum_a dO_ia O_ia and nL_i = -LSE_i log2e: 8 lanes per row, 8 elements of every 64 each.
+// nD_i = -sum_a dO_ia O_ia and nL_i = -LSE_i / scale: 8 lanes per row, 8 elements of every 64 each.
 __global__ void __launch_bounds__(256) bwd_preprocess_kernel(const uint16_t *dO, const uint16_t *O,
                                                              const float *LSE, float *nD, float *nL,
-                                                             int64_t rows, int A) {
+                                                             int64_t rows, int A, float inv_scale) {
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t row = gid >> 3;
   const int sub = (int)(gid & 7);
@@ -66,17 +70,17 @@ __global__ void __launch_bounds__(256) bwd_preprocess_kernel(const uint16_t *dO,
   acc += __shfl_xor(acc, 4);
   if (row < rows && sub == 0) {
     nD[row] = -acc;
-    nL[row] = -LSE[row] * kLog2e;
+    nL[row] = -LSE[row] * inv_scale;
   }
 }
 
 // ------------------------------------------------------------------ dK, dV ---
-// Work-group: 4 waves x 32 keys.  Ks = bf16(K * scale * log2 e) and V of a wave's keys stay in
+// Work-group: 4 waves x 32 keys.  K and V of a wave's keys stay in
 // registers as B operands; the work-group walks the query rows in stages of NQ tiles of 64 rows
 // of Q and dO, double-buffered in LDS and filled by direct global->LDS loads (no staging
 // registers), one barrier per stage.
 // The row terms of the softmax backward ride on the accumulator init of the MFMAs:
-//   S'  = Q Ks^T - LSE log2e   (so P = exp2(S') needs no multiply or subtract)
+//   S'  = Q K^T - LSE / scale  (so P = exp2(scale log2e S') is one multiply and the exp2)
 //   dP' = dO V^T - D           (so dS = P dP' is one multiply)
 // and dK = scale * sum_i dS_ij Q_i.
 // A head of 128 is two halves of 64 (AH = 2): two LDS tiles per 64 rows, S' and dP' contract over
@@ -109,7 +113,7 @@ __global__ void __launch_bounds__(256, AH == 2 ? 1 : 2) fused_bwd_dkdv_kernel(Bw
   const float *nLh = a.nL + head * a.Lq;
   const float *nDh = a.nD + head * a.Lq;
 
-  // K (times scale * log2 e, rounded to bf16) and V rows of this wave as B operands:
+  // K and V rows of this wave as B operands:
   // lane (col, half) holds row key = wkey0 + col, elements dk*16 + half*8 .. +8.
   bf16x8 kreg[4 * AH], vreg[4 * AH];
   {
@@ -117,7 +121,7 @@ __global__ void __launch_bounds__(256, AH == 2 ? 1 : 2) fused_bwd_dkdv_kernel(Bw
     if (key >= a.L) key = a.L - 1;  // ragged tail: clamped here, not stored below
 #pragma unroll
     for (int dk = 0; dk < 4 * AH; ++dk) {
-      kreg[dk] = scale_bf16x8(*reinterpret_cast<const bf16x8 *>(Kh + key * A + dk * 16 + half * 8), a.cl2);
+      kreg[dk] = *reinterpret_cast<const bf16x8 *>(Kh + key * A + dk * 16 + half * 8);
       vreg[dk] = *reinterpret_cast<const bf16x8 *>(Vh + key * A + dk * 16 + half * 8);
     }
   }
@@ -174,7 +178,7 @@ __global__ void __launch_bounds__(256, AH == 2 ? 1 : 2) fused_bwd_dkdv_kernel(Bw
           dma.load(dOh + r0 * A + ah * 64, sn.dOs[u][ah], A);
         }
       }
-      // the 64 row terms of the tile, one dword per lane: waves 0/1 fetch -LSE log2e, 2/3 fetch -D
+      // the 64 row terms of the tile, one dword per lane: waves 0/1 fetch -LSE / scale, 2/3 fetch -D
       if ((wave & 1) == (u & 1)) {
         if (wave < 2) lds_dma4(nLh + r0 + lane, sn.lse[u]);
         else lds_dma4(nDh + r0 + lane, sn.d[u]);
@@ -207,7 +211,7 @@ __global__ void __launch_bounds__(256, AH == 2 ? 1 : 2) fused_bwd_dkdv_kernel(Bw
       return qt < nqt && (!CAUSAL || a.map((int64_t)qt * 64) + 63 >= wkey0);
     };
     auto fetch = [&](int u, int qb) __attribute__((always_inline)) {
-      // accumulators start from -LSE log2e and -D of their rows (same for all lanes of a half)
+      // accumulators start from -LSE / scale and -D of their rows (same for all lanes of a half)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&sc.lse[u][qb * 32 + g * 8 + half * 4]);
@@ -250,8 +254,8 @@ __global__ void __launch_bounds__(256, AH == 2 ? 1 : 2) fused_bwd_dkdv_kernel(Bw
             u32x4 w, x;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const float p0 = __builtin_amdgcn_exp2f(sv[w2 * 8 + 2 * e]);
-              const float p1 = __builtin_amdgcn_exp2f(sv[w2 * 8 + 2 * e + 1]);
+              const float p0 = __builtin_amdgcn_exp2f(sv[w2 * 8 + 2 * e] * a.cl2);
+              const float p1 = __builtin_amdgcn_exp2f(sv[w2 * 8 + 2 * e + 1] * a.cl2);
               w[e] = pack_bf16(p0, p1);
               x[e] = pack_bf16(p0 * dp[w2 * 8 + 2 * e], p1 * dp[w2 * 8 + 2 * e + 1]);
             }
@@ -375,7 +379,7 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   const uint16_t *Kh = a.K + head * a.L * A;
   const uint16_t *Vh = a.V + head * a.L * A;
 
-  // Q (times scale * log2 e, rounded to bf16) and dO as B operands; -LSE log2e and -D of the lane's row, broadcast
+  // Q and dO as B operands; -LSE / scale and -D of the lane's row, broadcast
   // over an accumulator, are what S'^T and dP'^T start from.
   bf16x8 qreg[QB][4 * AH], greg[QB][4 * AH];
   int64_t qrow[QB];
@@ -389,8 +393,7 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
     qtok[qb] = a.map(blk < a.Lq ? blk : a.Lq - 32) + col;
 #pragma unroll
     for (int dk = 0; dk < 4 * AH; ++dk) {
-      qreg[qb][dk] = scale_bf16x8(
-          *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * A + dk * 16 + half * 8), a.cl2);
+      qreg[qb][dk] = *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * A + dk * 16 + half * 8);
       greg[qb][dk] = *reinterpret_cast<const bf16x8 *>(dOh + qrow[qb] * A + dk * 16 + half * 8);
     }
     float l2, dd;
@@ -408,7 +411,7 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
         }
       }
       dd = -xhalf_sum(acc);
-      l2 = -a.LSE[head * a.Lq + qrow[qb]] * kLog2e;
+      l2 = -a.LSE[head * a.Lq + qrow[qb]] * a.inv_scale;
       if (r < a.Lq && blockIdx.y == 0) {
         if (half == 0) {
           a.nD_out[head * a.Lq + r] = dd;
@@ -524,7 +527,7 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
-          for (int v = 0; v < 16; ++v) dp[qb][v] *= __builtin_amdgcn_exp2f(s[qb][v]);
+          for (int v = 0; v < 16; ++v) dp[qb][v] *= __builtin_amdgcn_exp2f(s[qb][v] * a.cl2);
 #pragma unroll
           for (int u = 0; u < 2; ++u) {
             u32x4 w = {pack_bf16(dp[qb][u * 8 + 0], dp[qb][u * 8 + 1]), pack_bf16(dp[qb][u * 8 + 2], dp[qb][u * 8 + 3]),
@@ -608,7 +611,7 @@ static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const
   a.part = nullptr;
   a.O = nullptr; a.LSE = nullptr; a.nL_out = nullptr; a.nD_out = nullptr;
   a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.map = make_row_map(d);
-  a.N = d.N; a.cl2 = d.scale * kLog2e; a.scale = d.scale;
+  a.N = d.N; a.cl2 = d.scale * kLog2e; a.scale = d.scale; a.inv_scale = 1.0f / d.scale;
   a.tiles_per_head = 0;
   return a;
 }
@@ -618,7 +621,7 @@ hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, co
   const int64_t rows = (int64_t)d.B * d.Z * d.Lq;
   dim3 grid((unsigned)((rows * 8 + 255) / 256));
   hipLaunchKernelGGL(bwd_preprocess_kernel, grid, dim3(256), 0, st, (const uint16_t *)dO,
-                     (const uint16_t *)O, LSE, nD, nL, rows, d.A);
+                     (const uint16_t *)O, LSE, nD, nL, rows, d.A, 1.0f / d.scale);
   return hipGetLastError();
 }
 
@@ -694,7 +697,7 @@ hipError_t fused_bwd_dq(const Dims &d, const void *dO, const void *Q, const void
   return dq_reduce(d, part, dQ, splits, st);
 }
 
-// The dQ kernel with the preprocess in its prologue: also writes -D and -LSE log2e.
+// The dQ kernel with the preprocess in its prologue: also writes -D and -LSE / scale.
 hipError_t fused_bwd_dq_pre(const Dims &d, const void *dO, const void *Q, const void *K, const void *V,
                             const void *O, const float *LSE, float *nL, float *nD, void *dQ,
                             hipStream_t st, float *part, int splits) {

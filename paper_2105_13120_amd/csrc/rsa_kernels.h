@@ -41,7 +41,7 @@ void fused_fwd_plan(const Dims &d, bool *big, int *splits);
 int fused_key_splits(const Dims &d);
 hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void *V, void *O,
                          float *LSE, hipStream_t st, float *part);
-// nD = -rowsum(dO o O) and nL = -LSE log2e, (B,Z,Lq) fp32
+// nD = -rowsum(dO o O) and nL = -LSE / scale, (B,Z,Lq) fp32
 hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, const float *LSE,
                                 float *nD, float *nL, hipStream_t st);
 // part / splits: optional split of the walk over the query rows (few keys, many rows): fp32

@@ -31,6 +31,7 @@ class RSAConfig:
     backward: bool = True
     seed: int = 0
     zigzag: bool = False  # rank n owns half-chunks n and 2N-1-n instead of chunk n
+    att_scale: float = 0.0  # the softmax scale handed to the library; 0 selects 1/sqrt(A)
 
     @property
     def c(self):

@@ -3,43 +3,46 @@ import numpy as np
 import torch
 
 import oracle
+from bf16_model import ideal_bf16_pipeline
 from paper_2105_13120_amd import inputs, rsa
 
 # Tolerances of the comparison with the fp64 oracle.
-#  fp32 path: max abs error <= 1e-4.
-#  bf16 path, per output tensor x with oracle value r:
-#    |x_ia - r_ia| <= 2e-2 * rms(r) + 2^-6 * max_a |r_ia|   for every element, and
-#    rms(x - r) <= 5e-3 * rms(r).
-#  2e-2 of the RMS is the stated bar.  Taken alone as a bound on the maximum
-#  error it cannot be met by any path that feeds bf16 operands to the matrix
-#  cores and stores bf16: O, dQ, dK and dV are heavy-tailed on these inputs (the
-#  largest element is 6 to 15 times the RMS) and both the operand rounding of P
-#  and dS and the final store are errors relative to the element, so an otherwise
-#  exact fp64 pipeline with those roundings is already 2e-2 to 3.5e-2 of the RMS
-#  off at its largest elements (tests/test_tolerance_model.py reproduces this on
-#  the CPU).  The operand noise of a token's vector scales with that token's
-#  probability / dS mass, i.e. with the whole row i of the output, so the bound
-#  grows by two bf16 ulps (2^-6) of the row's largest element: the roundings of P
-#  (forward, entering O and through it D), of dS, of the pre-scaled Q and of the
-#  store each cost up to half an ulp, and dS = P (dP - D) amplifies the error of D
-#  on the first rows of a causal mask, where a row has few keys (the ideal
-#  pipeline reaches 1.2e-2 of such an element).  The RMS criterion keeps the whole
-#  tensor tight (the ideal pipeline sits at 2.4e-3 to 3.5e-3).
-#  dQ carries one more term.  Every bf16 backward forms D_i = sum_a dO_ia O_ia from the
-#  *stored* O, whose rounding (|dO_ia| 2^-9 |O_ia| per term, independent signs) leaves an error
-#  delta_i in D_i with standard deviation 2^-9 / sqrt(3) * sqrt(sum_a dO_ia^2 O_ia^2).  It enters
-#  dS_ij = P_ij (dP_ij - D_i) for every key of the row with the same sign, so
-#  dQ_i = s sum_j dS_ij K_j moves by s * delta_i * (sum_j P_ij K_j): the row's attention-weighted
-#  mean key.  For rows that see many keys O_i is small and the term vanishes; on the first rows
-#  of a causal mask (one or two keys, O_i of the size of a value vector) it is the largest error
-#  in the tensor: the ideal pipeline of tests/test_tolerance_model.py is 1.34 times the bound
-#  above on such an element.  The dQ bound is therefore widened by four standard deviations of
-#  that term, computed from the oracle's own O and P (dq_extra below).
+#  fp32 path: max abs error <= 1e-4.  LSE (fp32 on both paths): 1e-4 absolute.
+#  bf16 path.  The stated bar is "max abs err <= 2e-2 relative to the output RMS".  Read as a bound
+#  on the largest error of a tensor it cannot be met by anything that stores bf16: O, dQ, dK, dV are
+#  heavy-tailed on these inputs (largest element 10 to 12 times the RMS) and the store rounds
+#  relative to the element (unit roundoff 2^-8), so the EXACT result rounded to bf16 is already
+#  2.6e-2 of the RMS off at its largest element (bert_base and bert_large, all heads; the CPU test
+#  tests/test_tolerance_model.py shows it).  What is asserted instead, per output tensor x with
+#  oracle value r:
+#   (1) every element:  |x_ia - r_ia| <= 2e-2 rms(r) + 2^-7 max_a |r_ia|   (+ dq_extra for dQ)
+#       -- the stated bar plus two unit roundoffs of the row's largest element: one for the store,
+#       one for the noise that the bf16 rounding of the matrix-core operands P and dS of that row
+#       leaves (it scales with the row).  The ideal bf16 pipeline of tests/bf16_model.py reaches
+#       0.33 to 0.89 of this bound on the shapes of tests/test_tolerance_model.py.
+#   (2) the whole tensor:  rms(x - r) <= 3e-3 rms(r)   (the ideal pipeline: 2.0e-3 to 2.5e-3).
+#   (3) against the ideal pipeline on the same inputs (wherever a test computes it: every dense
+#       comparison): max|x - r| <= 1.5 max|ideal - r| and rms(x - r) <= 1.15 rms(ideal - r).
+#       The ideal pipeline is exact arithmetic with only the roundings a bf16 matrix-core path
+#       cannot avoid, which are also exactly the roundings the fused kernels make; (3) is what
+#       rejects avoidable error: a second rounding of a scaled operand (the planted mistake of
+#       tests/test_tolerance_model.py) passes (1) and fails (3) at 1.27 of the ideal RMS error.
+#  dQ carries one more term in (1).  Every bf16 backward forms D_i = sum_a dO_ia O_ia from the
+#  *stored* O, whose rounding leaves an error delta_i in D_i with standard deviation
+#  2^-9 / sqrt(3) * sqrt(sum_a dO_ia^2 O_ia^2).  It enters dS_ij = P_ij (dP_ij - D_i) for every key
+#  of the row with the same sign, so dQ_i = s sum_j dS_ij K_j moves by s delta_i (sum_j P_ij K_j):
+#  the row's attention-weighted mean key.  For rows that see many keys O_i is small and the term
+#  vanishes; on the first rows of a causal mask (one or two keys, O_i of the size of a value vector)
+#  it is the largest error in the tensor, so the dQ bound is widened by four standard deviations of
+#  that term, computed from the oracle's own O and P (dq_extra below; the ideal pipeline reaches
+#  0.8 to 0.9 of the widened bound on such rows).
 F32_ATOL = 1e-4
 BF16_REL_RMS = 2e-2
-BF16_RTOL = 2.0 ** -6
-BF16_REL_RMS_MEAN = 5e-3
-LSE_ATOL = 1e-3
+BF16_RTOL = 2.0 ** -7
+BF16_REL_RMS_MEAN = 3e-3
+IDEAL_MAX_RATIO = 1.5
+IDEAL_RMS_RATIO = 1.15
+LSE_ATOL = 1e-4
 
 
 def torch_dtype(name):
@@ -75,16 +78,33 @@ def dq_extra(Q, K, V, dO, O_ref, q0, causal, scale=None):
     return 4.0 * sigma * s * np.abs(PK)
 
 
-def check(name, got, ref, dtype, extra=None):
-    """Assert the tolerance for one output tensor; returns max abs err (f32) or
-    max abs err / rms (bf16).  extra: per-element addition to the bf16 bound."""
+class Err(float):
+    """max abs err / rms (bf16) or max abs err (f32), with the other figures as attributes:
+    rms_rel = rms(err) / rms; vs_ideal_max, vs_ideal_rms = the ratios of criterion (3) or None."""
+    rms_rel = None
+    vs_ideal_max = None
+    vs_ideal_rms = None
+
+    def describe(self):
+        t = f"{float(self):.2e}"
+        if self.rms_rel is not None:
+            t += f" (rms {self.rms_rel:.2e}"
+            if self.vs_ideal_max is not None:
+                t += f"; x{self.vs_ideal_max:.2f} max, x{self.vs_ideal_rms:.2f} rms of ideal"
+            t += ")"
+        return t
+
+
+def check(name, got, ref, dtype, extra=None, ideal=None):
+    """Assert the tolerance for one output tensor; returns an Err.  extra: per-element addition
+    to the bf16 bound; ideal: the same tensor from the ideal bf16 pipeline (criterion (3))."""
     assert got.shape == ref.shape, (name, got.shape, ref.shape)
     assert np.isfinite(got).all(), f"{name}: non-finite values"
     diff = np.abs(got - ref)
     if dtype == "f32":
         err = float(diff.max())
         assert err <= F32_ATOL, f"{name}: max abs err {err:.3e} > {F32_ATOL}"
-        return err
+        return Err(err)
     rms = max(float(np.sqrt(np.mean(np.square(ref)))), 1e-30)
     bound = BF16_REL_RMS * rms + BF16_RTOL * np.abs(ref).max(axis=-1, keepdims=True)
     if extra is not None:
@@ -92,9 +112,19 @@ def check(name, got, ref, dtype, extra=None):
     worst = float((diff / bound).max())
     assert worst <= 1.0, (f"{name}: error is {worst:.3f} of the bound "
                           f"(max abs err / rms = {diff.max() / rms:.3e})")
-    mean = float(np.sqrt(np.mean(np.square(diff)))) / rms
-    assert mean <= BF16_REL_RMS_MEAN, f"{name}: rms err / rms {mean:.3e} > {BF16_REL_RMS_MEAN}"
-    return float(diff.max()) / rms
+    mean = float(np.sqrt(np.mean(np.square(diff))))
+    assert mean <= BF16_REL_RMS_MEAN * rms, f"{name}: rms err / rms {mean / rms:.3e} > {BF16_REL_RMS_MEAN}"
+    e = Err(float(diff.max()) / rms)
+    e.rms_rel = mean / rms
+    if ideal is not None:
+        di = np.abs(ideal - ref)
+        e.vs_ideal_max = float(diff.max()) / max(float(di.max()), 1e-30)
+        e.vs_ideal_rms = mean / max(float(np.sqrt(np.mean(np.square(di)))), 1e-30)
+        assert e.vs_ideal_max <= IDEAL_MAX_RATIO, (f"{name}: max err is {e.vs_ideal_max:.2f} times the ideal "
+                                                   f"bf16 pipeline's ({diff.max() / rms:.3e} of the rms)")
+        assert e.vs_ideal_rms <= IDEAL_RMS_RATIO, (f"{name}: rms err is {e.vs_ideal_rms:.2f} times the ideal "
+                                                   f"bf16 pipeline's ({mean / rms:.3e} of the rms)")
+    return e
 
 
 def gpu_forward_backward(cfg, x, mode=rsa.MODE_FUSED, backward=True):
@@ -102,7 +132,7 @@ def gpu_forward_backward(cfg, x, mode=rsa.MODE_FUSED, backward=True):
     Q, K, V = (upload(x[k], cfg.dtype) for k in ("Q", "K", "V"))
     rb, re = cfg.ranks
     desc = rsa.make_desc(K, cfg.N, causal=cfg.causal, rank_begin=rb, rank_end=re, mode=mode,
-                         zigzag=cfg.zigzag)
+                         zigzag=cfg.zigzag, scale=cfg.att_scale)
     O, LSE = rsa.forward(desc, Q, K, V)
     out = {"O": O, "LSE": LSE}
     if backward:
@@ -111,6 +141,16 @@ def gpu_forward_backward(cfg, x, mode=rsa.MODE_FUSED, backward=True):
         out.update(dQ=dQ, dK=dK, dV=dV)
     torch.cuda.synchronize()
     return out
+
+
+def att_scale(cfg):
+    """The softmax scale as the oracle takes it (None: 1/sqrt(A))."""
+    return cfg.att_scale if cfg.att_scale > 0 else None
+
+
+def row_tokens(cfg):
+    """Global token index of every local query row."""
+    return np.concatenate([np.arange(t0, t0 + n) for _, t0, n in cfg.segments()])
 
 
 def oracle_on_segments(cfg, Qh, Kh, Vh, dOh=None):
@@ -122,32 +162,50 @@ def oracle_on_segments(cfg, Qh, Kh, Vh, dOh=None):
     dQ = np.empty_like(Qh) if dOh is not None else None
     extra = np.empty_like(Qh) if dOh is not None else None
     dK = dV = None
+    sc = att_scale(cfg)
     for r0, t0, n in cfg.segments():
         Qs = np.ascontiguousarray(Qh[:, :, r0:r0 + n])
-        O[:, :, r0:r0 + n], LSE[:, :, r0:r0 + n] = oracle.forward(Qs, Kh, Vh, q0=t0, causal=cfg.causal)
+        O[:, :, r0:r0 + n], LSE[:, :, r0:r0 + n] = oracle.forward(Qs, Kh, Vh, q0=t0, causal=cfg.causal, scale=sc)
         if dOh is not None:
             dOs = np.ascontiguousarray(dOh[:, :, r0:r0 + n])
-            g = oracle.backward(Qs, Kh, Vh, dOs, q0=t0, causal=cfg.causal)
+            g = oracle.backward(Qs, Kh, Vh, dOs, q0=t0, causal=cfg.causal, scale=sc)
             dQ[:, :, r0:r0 + n] = g[0]
             dK = g[1] if dK is None else dK + g[1]
             dV = g[2] if dV is None else dV + g[2]
-            extra[:, :, r0:r0 + n] = dq_extra(Qs, Kh, Vh, dOs, O[:, :, r0:r0 + n], t0, cfg.causal)
+            extra[:, :, r0:r0 + n] = dq_extra(Qs, Kh, Vh, dOs, O[:, :, r0:r0 + n], t0, cfg.causal, scale=sc)
     return O, LSE, dQ, dK, dV, extra
 
 
-def compare_heads(cfg, x, out, heads, backward=True):
-    """Full comparison with the oracle on the listed flat head indices."""
+def compare_heads(cfg, x, out, heads, backward=True, ideal=True, ideal_heads=16):
+    """Full comparison with the oracle on the listed flat head indices.  ideal: also hold the bf16
+    outputs to the stated multiples of the ideal bf16 pipeline's error (criterion (3) on top), on
+    the first `ideal_heads` of the listed heads."""
     Qh, Kh, Vh = (heads_view(x[k], heads) for k in ("Q", "K", "V"))
     dOh = heads_view(x["dO"], heads) if backward else None
     O_ref, LSE_ref, dQ_ref, dK_ref, dV_ref, dq_x = oracle_on_segments(cfg, Qh, Kh, Vh, dOh)
+    got = {k: heads_view(download(out[k]), heads) for k in (("O", "dQ", "dK", "dV") if backward else ("O",))}
+    refs = dict(O=O_ref, dQ=dQ_ref, dK=dK_ref, dV=dV_ref)
     errs = {}
-    errs["O"] = check("O", heads_view(download(out["O"]), heads), O_ref, cfg.dtype)
+    for name in got:
+        errs[name] = check(name, got[name], refs[name], cfg.dtype,
+                           extra=dq_x if name == "dQ" and cfg.dtype == "bf16" else None)
     lse = download(out["LSE"]).reshape(-1, cfg.Lq)[heads][None]
     err = float(np.abs(lse - LSE_ref).max())
     assert err <= LSE_ATOL, f"LSE: max abs err {err:.3e}"
-    errs["LSE"] = err
-    if backward:
-        for name, ref in (("dQ", dQ_ref), ("dK", dK_ref), ("dV", dV_ref)):
-            errs[name] = check(name, heads_view(download(out[name]), heads), ref, cfg.dtype,
-                               extra=dq_x if name == "dQ" and cfg.dtype == "bf16" else None)
+    errs["LSE"] = Err(err)
+    if ideal and cfg.dtype == "bf16":
+        n = min(ideal_heads, len(heads))
+        cut = lambda a: None if a is None else a[:, :n]
+        m = ideal_bf16_pipeline(cut(Qh), cut(Kh), cut(Vh), cut(dOh), scale=att_scale(cfg),
+                                qtok=row_tokens(cfg), causal=cfg.causal)
+        model = dict(O=m[0])
+        if backward:
+            model.update(dQ=m[2], dK=m[3], dV=m[4])
+        for name in got:
+            errs[name] = check(name, cut(got[name]), cut(refs[name]), cfg.dtype, ideal=model[name],
+                               extra=cut(dq_x) if name == "dQ" else None)
     return errs
+
+
+def describe(errs):
+    return ", ".join(f"{k} {v.describe()}" for k, v in errs.items())

@@ -3,8 +3,8 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import (BF16_REL_RMS, LSE_ATOL, check, compare_heads, download, gpu_forward_backward,
-                     heads_view)
+from helpers import (BF16_REL_RMS, LSE_ATOL, check, compare_heads, describe, download,
+                     gpu_forward_backward, heads_view)
 from paper_2105_13120_amd import inputs, rsa
 
 pytestmark = pytest.mark.gpu
@@ -15,7 +15,7 @@ def test_bert_base_all_heads_sampled():
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x)
     heads = [0, 1, 11, 12, 95, 96, 190, 191]
-    print(compare_heads(cfg, x, out, heads))
+    print(describe(compare_heads(cfg, x, out, heads)))
 
 
 def test_bert_large_sampled_heads():
@@ -23,7 +23,7 @@ def test_bert_large_sampled_heads():
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x)
     check_sum_rules(cfg, x, out)
-    print(compare_heads(cfg, x, out, [0, 15, 64, 127]))
+    print(describe(compare_heads(cfg, x, out, [0, 15, 64, 127])))
 
 
 def sampled_check(cfg, x, out, head, row_blocks, cols):
@@ -142,4 +142,4 @@ def test_bert_large_staged_layout_sampled_heads():
     cfg = inputs.CONFIGS["bert_large"]
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED)
-    print(compare_heads(cfg, x, out, [0, 77, 127]))
+    print(describe(compare_heads(cfg, x, out, [0, 77, 127])))

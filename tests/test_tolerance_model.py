@@ -1,88 +1,105 @@
 """Where the bf16 tolerance comes from (CPU only).
 
-An otherwise exact fp64 pipeline that rounds only what any bf16 matrix-core
-path must round -- P and dS as MFMA operands, O before it enters D, and the
-stored outputs -- is compared with the oracle.  Its largest error exceeds
-2e-2 of the RMS (the tensors are heavy-tailed and these roundings are relative
-to the element), stays inside the mixed bound the GPU tests use, and its RMS
-error is a few 1e-3 of the RMS.  The emulation below is test-only arithmetic
-written from the oracle's step list; it is not the GPU path and not the oracle.
+tests/bf16_model.py holds an otherwise exact fp64 pipeline that rounds only what any bf16
+matrix-core path must round -- P and dS as MFMA operands, O before it enters D, and the stored
+outputs.  Here it is compared with the oracle: the stated bar read literally (largest error <=
+2e-2 of the RMS) fails already for the exact result rounded once to bf16; the pipeline sits at
+a stated fraction of the bounds the GPU tests use; and a pipeline with one avoidable rounding
+more (the planted mistake) is rejected by the comparison with the ideal pipeline.
 """
 import numpy as np
+import pytest
 
 import oracle
-from helpers import BF16_REL_RMS, BF16_REL_RMS_MEAN, BF16_RTOL, check, dq_extra
+from bf16_model import folded_scale_pipeline, ideal_bf16_pipeline, r
+from helpers import (BF16_REL_RMS, BF16_REL_RMS_MEAN, BF16_RTOL, IDEAL_RMS_RATIO, check, dq_extra)
 from paper_2105_13120_amd import inputs
 
-
-def r(a):
-    return inputs.round_to_bf16(np.asarray(a, dtype=np.float32)).astype(np.float64)
+NAMES = ("O", "dQ", "dK", "dV")
 
 
-def ideal_bf16_pipeline(Q, K, V, dO, s):
-    S = s * Q @ K.transpose(0, 1, 3, 2)
-    m = S.max(-1, keepdims=True)
-    p = np.exp(S - m)
-    l = p.sum(-1, keepdims=True)
-    O = r((r(p) @ V) / l)
-    P = p / l
-    dP = dO @ V.transpose(0, 1, 3, 2)
-    D = (dO * O).sum(-1, keepdims=True)
-    dS = r(P * (dP - D))
-    dQ = r(s * dS @ K)
-    dK = r(s * dS.transpose(0, 1, 3, 2) @ Q)
-    dV = r(r(P).transpose(0, 1, 3, 2) @ dO)
-    return O, dQ, dK, dV
-
-
-def test_ideal_bf16_pipeline_breaks_max_over_rms_but_meets_the_mixed_bound():
-    cfg = inputs.RSAConfig("t", B=2, Z=4, L=512, A=64, N=1, dtype="bf16", seed=0)
+def case(causal=False, L=512, Z=4, A=64, seed=0, qkv_scale=1.0):
+    cfg = inputs.RSAConfig("t", B=1, Z=Z, L=L, A=A, N=1, dtype="bf16", seed=seed, causal=causal,
+                           qkv_scale=qkv_scale)
     x = inputs.make_inputs(cfg)
     Q, K, V, dO = (x[k].astype(np.float64) for k in ("Q", "K", "V", "dO"))
-    O_ref, _ = oracle.forward(Q, K, V)
-    refs = (O_ref,) + oracle.backward(Q, K, V, dO)
-    got = ideal_bf16_pipeline(Q, K, V, dO, 0.125)
-    over = 0
-    for name, g, ref in zip(("O", "dQ", "dK", "dV"), got, refs):
+    O_ref, _ = oracle.forward(Q, K, V, causal=causal)
+    refs = (O_ref,) + oracle.backward(Q, K, V, dO, causal=causal)
+    return Q, K, V, dO, refs
+
+
+def pick(m):
+    return (m[0],) + tuple(m[2:])
+
+
+def test_the_exact_result_rounded_to_bf16_breaks_the_literal_bar():
+    """16 heads of 512 tokens: the largest element of O is more than 6 times the RMS, and rounding
+    it to bf16 (unit roundoff 2^-8) alone leaves an error above 2e-2 of the RMS."""
+    Q, K, V, dO, refs = case(Z=16)
+    O = refs[0]
+    rms = np.sqrt(np.mean(O ** 2))
+    assert np.abs(O).max() / rms > 6.0
+    assert np.abs(r(O) - O).max() / rms > BF16_REL_RMS
+
+
+@pytest.mark.parametrize("causal,L,A,qkv_scale", [(False, 512, 64, 1.0), (True, 512, 64, 1.0),
+                                                  (False, 1024, 64, 0.5), (True, 768, 128, 1.0)])
+def test_ideal_pipeline_sits_at_a_stated_fraction_of_the_bounds(causal, L, A, qkv_scale):
+    Q, K, V, dO, refs = case(causal, L, A=A, qkv_scale=qkv_scale)
+    got = pick(ideal_bf16_pipeline(Q, K, V, dO, causal=causal))
+    extra = dq_extra(Q, K, V, dO, refs[0], 0, causal)
+    for name, g, ref in zip(NAMES, got, refs):
         rms = np.sqrt(np.mean(ref ** 2))
-        assert np.abs(ref).max() / rms > 6.0                 # heavy tails
-        over += np.abs(g - ref).max() / rms > BF16_REL_RMS
+        bound = BF16_REL_RMS * rms + BF16_RTOL * np.abs(ref).max(-1, keepdims=True)
+        if name == "dQ":
+            bound = bound + extra
+        worst = (np.abs(g - ref) / bound).max()
+        assert 0.25 <= worst <= 0.92, (name, worst)          # criterion (1): headroom between 1.1 and 4
         mean = np.sqrt(np.mean((g - ref) ** 2)) / rms
-        assert mean < BF16_REL_RMS_MEAN / 1.5
-        check(name, g, ref, "bf16")                          # the bound the GPU tests use
-    assert over >= 3       # the plain max/rms reading fails for most tensors even here
+        assert 1.8e-3 <= mean <= 2.7e-3, (name, mean)        # criterion (2) allows 3e-3
+        check(name, g, ref, "bf16", extra=extra if name == "dQ" else None, ideal=g)
+
+
+def test_a_second_rounding_of_a_scaled_operand_is_rejected():
+    """The planted mistake: scores recomputed from bf16(K s log2e) / bf16(Q s log2e).  It stays
+    inside the per-element bound (1) and is thrown out by the comparison with the ideal pipeline:
+    its RMS error is 1.2 to 1.3 times the ideal's (at or just over the 3e-3 of criterion (2)) and
+    its largest dQ, dK errors 2 to 3 times."""
+    Q, K, V, dO, refs = case(Z=2)
+    good = pick(ideal_bf16_pipeline(Q, K, V, dO))
+    bad = pick(folded_scale_pipeline(Q, K, V, dO))
+    assert np.array_equal(good[0], bad[0])                   # the forward is the same
+    for name, g, b, ref in zip(NAMES[1:], good[1:], bad[1:], refs[1:]):
+        rms = np.sqrt(np.mean(ref ** 2))
+        bound = BF16_REL_RMS * rms + BF16_RTOL * np.abs(ref).max(-1, keepdims=True)
+        assert (np.abs(b - ref) <= bound).all()              # criterion (1) alone accepts it
+        ratio = np.sqrt(np.mean((b - ref) ** 2)) / np.sqrt(np.mean((g - ref) ** 2))
+        assert ratio > IDEAL_RMS_RATIO + 0.05, (name, ratio)
+        with pytest.raises(AssertionError, match="times the ideal|rms err / rms"):
+            check(name, b, ref, "bf16", ideal=g)
+    for name, i in (("dQ", 1), ("dK", 2)):
+        assert np.abs(bad[i] - refs[i]).max() > 2.0 * np.abs(good[i] - refs[i]).max(), name
 
 
 def test_check_rejects_small_systematic_errors():
     ref = np.random.Generator(np.random.PCG64(1)).standard_normal((1, 1, 256, 64))
     check("ok", r(ref), ref, "bf16")
-    for bad in (ref * 1.02, ref + 0.03, np.where(np.abs(ref) < 0.5, ref * 1.05, ref)):
-        try:
+    for bad in (ref * 1.01, ref + 0.025, np.where(np.abs(ref) < 0.5, ref * 1.03, ref)):
+        with pytest.raises(AssertionError):
             check("bad", bad, ref, "bf16")
-        except AssertionError:
-            continue
-        raise AssertionError("check accepted a wrong tensor")
 
 
 def test_rounding_of_the_stored_O_inside_D_needs_its_own_term_on_the_first_causal_rows():
     """Token 1 of a causal sequence sees two keys; D_1 = dO_1 . O_1 is formed from the bf16 O_1 and
-    its error enters dS_10 and dS_11 with one sign.  On this input (found by the seeded random-shape
-    GPU tests) the ideal pipeline is 1.3 times the mixed bound at that row and meets the bound
-    widened by dq_extra; no later row comes near."""
+    its error enters dS_10 and dS_11 with one sign.  On this input (a seeded random shape) the ideal
+    pipeline is well over the per-element bound at that row and meets the bound widened by dq_extra;
+    no later row comes near."""
     cfg = inputs.RSAConfig("r", B=1, Z=3, L=4096, A=64, N=8, dtype="bf16", causal=True, seed=193410553,
                            rank_begin=0, rank_end=5, zigzag=True)
     x = inputs.make_inputs(cfg)
     n = 256   # rank 0's first half-chunk: tokens 0..255, which see only themselves
     Q, K, V, dO = (x[k][:, :1, :n].astype(np.float64) for k in ("Q", "K", "V", "dO"))
-    s = 0.125
-    S = s * Q @ K.transpose(0, 1, 3, 2)
-    S[..., np.triu(np.ones((n, n), bool), 1)] = -np.inf
-    p = np.exp(S - S.max(-1, keepdims=True))
-    l = p.sum(-1, keepdims=True)
-    O = r((r(p) @ V) / l)
-    P = p / l
-    D = (dO * O).sum(-1, keepdims=True)
-    dQ = r(s * r(P * (dO @ V.transpose(0, 1, 3, 2) - D)) @ K)
+    dQ = ideal_bf16_pipeline(Q, K, V, dO, causal=True)[2]
     O_ref, _ = oracle.forward(Q, K, V, causal=True)
     dQ_ref = oracle.backward(Q, K, V, dO, causal=True)[0]
     # the RMS that normalises the bound is that of the whole head (2560 rows, most of them late)
@@ -95,8 +112,8 @@ def test_rounding_of_the_stored_O_inside_D_needs_its_own_term_on_the_first_causa
     rms = np.sqrt(sq / (cfg.Lq * 64))
     plain = BF16_REL_RMS * rms + BF16_RTOL * np.abs(dQ_ref).max(-1, keepdims=True)
     ratio = np.abs(dQ - dQ_ref) / plain
-    assert ratio[0, 0, 1].max() > 1.2 and ratio[0, 0, 8:].max() < 0.8
-    check("dQ", dQ, dQ_ref, "bf16", extra=dq_extra(Q, K, V, dO, O_ref, 0, True))
-    # the term is negligible where a row sees many keys
+    assert ratio[0, 0, 1].max() > 1.5 and ratio[0, 0, 8:].max() < 1.0
     x_ = dq_extra(Q, K, V, dO, O_ref, 0, True)
-    assert (x_[0, 0, 128:] < 0.25 * plain[0, 0, 128:]).all()
+    assert (np.abs(dQ - dQ_ref) <= plain + x_).all()
+    # the term is negligible where a row sees many keys
+    assert (x_[0, 0, 128:] < 0.3 * plain[0, 0, 128:]).all()
