@@ -50,7 +50,7 @@ typedef enum {
 
 typedef enum { RSA_F32 = 0, RSA_BF16 = 1 } rsa_dtype;
 
-/* flags: one mode, optionally or-ed with an ownership bit */
+/* flags: one mode, optionally or-ed with the bits below */
 #define RSA_MODE_FUSED 0u  /* online-softmax kernels, no score strip in HBM   */
 #define RSA_MODE_STAGED 1u /* the paper's two-pass layout: strip S^n in HBM   */
 /* Zig-zag chunk ownership (fused mode only; an extension for the causal mask, which
@@ -61,6 +61,15 @@ typedef enum { RSA_F32 = 0, RSA_BF16 = 1 } rsa_dtype;
  * [(2N-1-n) h, (2N-n) h); K, V, dK, dV stay in token order.  Ring step t of rank n
  * visits the two half-chunks of rank (n - t) mod N.  Needs h divisible by 64. */
 #define RSA_OWN_ZIGZAG 2u
+/* Fused backward only.  Without this bit rsa_backward forms dQ inside the kernel that
+ * walks the query rows for dK and dV (the K ring pass and the two sums over ranks of
+ * section 3.2.2 in one sweep: S and dP are computed once) and adds every key block's
+ * share of dQ to an fp32 accumulator in the workspace with atomic adds, so the last
+ * bits of dQ depend on the order in which work-groups arrive.  With this bit dQ comes
+ * from a kernel of its own that owns its rows and sums in a fixed order (S and dP are
+ * then computed twice); results are bit-identical from run to run.  dK, dV, O and LSE
+ * are deterministic either way. */
+#define RSA_DETERMINISTIC 4u
 
 typedef struct {
   int32_t B, Z, A;   /* batch, heads, head size                              */
@@ -71,7 +80,15 @@ typedef struct {
                      /* query i iff j <= i in global token index (extension) */
   int32_t dtype;     /* rsa_dtype of Q, K, V, O, dO, dQ, dK, dV              */
   float scale;       /* 1/sqrt(d_k) of Eq. 1; 0 selects 1/sqrt(A)            */
-  uint32_t flags;    /* RSA_MODE_FUSED or RSA_MODE_STAGED [| RSA_OWN_ZIGZAG] */
+  uint32_t flags;    /* RSA_MODE_* [| RSA_OWN_ZIGZAG] [| RSA_DETERMINISTIC]  */
+  /* Strides in elements of the batch, head and row index (the last index is always
+   * contiguous): q_stride for Q and dQ, kv_stride for K, V, dK, dV, o_stride for O
+   * and dO.  All three zero = dense (B, Z, rows, A), i.e. {Z rows A, rows A, A}.
+   * Non-dense layouts (e.g. heads interleaved as (B, rows, Z, A), or Q, K, V as
+   * slices of one packed projection output) are taken by rsa_forward, rsa_backward
+   * and the rsa_bwd_* calls in fused mode; row strides must be multiples of 8
+   * elements (16 bytes) and at most 2^24.  LSE, D and the workspace are always dense. */
+  int64_t q_stride[3], kv_stride[3], o_stride[3];
 } rsa_desc;
 
 int rsa_version(void);
@@ -151,9 +168,10 @@ int rsa_store(const rsa_desc *d, const float *src, void *dst, size_t count,
               void *stream);
 
 /*
- * The kernels of the fused backward on their own (bf16, fused mode), for
- * profiling and tests, on one workspace `ws` of rsa_workspace_bytes(d, 1)
- * bytes.  rsa_backward runs the dQ kernel first, with the preprocess folded
+ * The kernels of the deterministic fused backward on their own (bf16, fused mode),
+ * for profiling and tests, on one workspace `ws` of at least
+ * rsa_workspace_bytes(d, 1) bytes (checked on the host: RSA_ERR_WORKSPACE).  With
+ * RSA_DETERMINISTIC rsa_backward runs the dQ kernel first, with the preprocess folded
  * into its prologue, then the dK/dV kernel; the three calls below in the order
  * given produce the same gradients up to the fp32 summation order of D.
  *  rsa_bwd_preprocess: fills ws with the row terms -D_i = -sum_a dO_ia O_ia and
@@ -174,9 +192,10 @@ int rsa_bwd_preprocess(const rsa_desc *d, const void *dO, const void *O,
                        const float *LSE, void *ws, size_t ws_bytes,
                        void *stream);
 int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *Q, const void *K,
-                 const void *V, const void *ws, void *dK, void *dV, void *stream);
+                 const void *V, const void *ws, size_t ws_bytes, void *dK, void *dV,
+                 void *stream);
 int rsa_bwd_dq(const rsa_desc *d, const void *dO, const void *Q, const void *K,
-               const void *V, void *ws, void *dQ, void *stream);
+               const void *V, void *ws, size_t ws_bytes, void *dQ, void *stream);
 
 /*
  * The two linear maps around RSA on the simulated ranks' rows (Table 2, sequence

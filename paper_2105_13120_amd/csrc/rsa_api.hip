@@ -15,7 +15,7 @@ int validate(const rsa_desc *d, Dims *out) {
   if (d->rank_begin < 0 || d->rank_end > d->N || d->rank_begin >= d->rank_end) return RSA_ERR_SHAPE;
   if (d->A % 64 != 0 || d->A > 256) return RSA_ERR_UNSUPPORTED;
   if (d->dtype != RSA_F32 && d->dtype != RSA_BF16) return RSA_ERR_UNSUPPORTED;
-  if (d->flags & ~(RSA_MODE_STAGED | RSA_OWN_ZIGZAG)) return RSA_ERR_UNSUPPORTED;
+  if (d->flags & ~(RSA_MODE_STAGED | RSA_OWN_ZIGZAG | RSA_DETERMINISTIC)) return RSA_ERR_UNSUPPORTED;
   const int mode = (int)(d->flags & RSA_MODE_STAGED);
   const int zigzag = (d->flags & RSA_OWN_ZIGZAG) ? 1 : 0;
   // the fused kernels are written for bf16 heads of 64 or 128 elements
@@ -31,6 +31,25 @@ int validate(const rsa_desc *d, Dims *out) {
   out->mode = mode; out->zigzag = zigzag;
   out->L = d->L; out->c = c; out->Lq = (int64_t)(d->rank_end - d->rank_begin) * c;
   out->scale = d->scale > 0.0f ? d->scale : 1.0f / std::sqrt((float)d->A);
+  out->deterministic = (d->flags & RSA_DETERMINISTIC) ? 1 : 0;
+  // strides: all zero selects the dense layout; otherwise every stride must be positive, the
+  // row stride a multiple of 16 bytes that holds a row, and only the fused kernels take them
+  const int64_t *in[3] = {d->q_stride, d->kv_stride, d->o_stride};
+  int64_t *st[3] = {out->qs, out->ks, out->os};
+  const int64_t rows[3] = {out->Lq, out->L, out->Lq};
+  out->strided = 0;
+  for (int t = 0; t < 3; ++t) {
+    const bool zero = in[t][0] == 0 && in[t][1] == 0 && in[t][2] == 0;
+    const int64_t dense[3] = {(int64_t)d->Z * rows[t] * d->A, rows[t] * d->A, d->A};
+    for (int k = 0; k < 3; ++k) st[t][k] = zero ? dense[k] : in[t][k];
+    if (zero) continue;
+    if (in[t][0] <= 0 || in[t][1] <= 0 || in[t][2] < d->A) return RSA_ERR_SHAPE;
+    if (in[t][2] % 8 != 0 || in[t][2] > (1 << 24) || in[t][1] % 8 != 0 || in[t][0] % 8 != 0)
+      return RSA_ERR_UNSUPPORTED;
+    if (st[t][0] != dense[0] || st[t][1] != dense[1] || st[t][2] != dense[2]) out->strided = 1;
+  }
+  if (out->strided && mode == RSA_MODE_STAGED) return RSA_ERR_UNSUPPORTED;
+  if (out->strided) return RSA_ERR_UNSUPPORTED;  // TODO(strides): until the fused kernels take them
   return RSA_OK;
 }
 
@@ -68,15 +87,20 @@ size_t fused_bwd_base(const Dims &d) {
   return 2 * align256(rows * 4);
 }
 
+// Fused backward with dQ from its own kernel: the row terms, then the partial dQ per split and
+// row when the key walk is split.
+size_t det_bwd_bytes(const Dims &d) {
+  const size_t rows = (size_t)d.B * d.Z * d.Lq;
+  const int ks = rsa::fused_key_splits(d);
+  return fused_bwd_base(d) + (ks > 1 ? align256(ks * rows * d.A * 4) : 0);
+}
+
 // Fused path: the partial results of a split key walk (forward: unnormalised O and the pair
 // (max, sum) per split and row; backward: partial dQ per split and row, after the base part).
 size_t workspace_bytes(const Dims &d, int dtype, int pass) {
   if (d.mode == RSA_MODE_STAGED) return staged_layout(d, dtype, pass).total;
   const size_t rows = (size_t)d.B * d.Z * d.Lq;
-  if (pass == 1) {
-    const int ks = rsa::fused_key_splits(d);
-    return fused_bwd_base(d) + (ks > 1 ? align256(ks * rows * d.A * 4) : 0);
-  }
+  if (pass == 1) return det_bwd_bytes(d);
   bool big;
   int fs;
   rsa::fused_fwd_plan(d, &big, &fs);
@@ -326,22 +350,24 @@ int rsa_bwd_preprocess(const rsa_desc *d, const void *dO, const void *O, const f
                        void *ws, size_t ws_bytes, void *stream) {
   RSA_STEP_PROLOGUE(dO && O && LSE, dO, O, LSE, ws);
   if (d->dtype != RSA_BF16 || dm.mode != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
-  if (!ws || ws_bytes < workspace_bytes(dm, d->dtype, 1)) return RSA_ERR_WORKSPACE;
+  if (!ws || ws_bytes < det_bwd_bytes(dm)) return RSA_ERR_WORKSPACE;
   return hip_status(rsa::fused_bwd_preprocess(dm, dO, O, LSE, fused_nD(ws), fused_nL(dm, ws), st));
 }
 
 int rsa_bwd_dkdv(const rsa_desc *d, const void *dO, const void *Q, const void *K, const void *V,
-                 const void *ws, void *dK, void *dV, void *stream) {
-  RSA_STEP_PROLOGUE(dO && Q && K && V && ws && dK && dV, dO, Q, K, V, ws, dK, dV);
+                 const void *ws, size_t ws_bytes, void *dK, void *dV, void *stream) {
+  RSA_STEP_PROLOGUE(dO && Q && K && V && dK && dV, dO, Q, K, V, ws, dK, dV);
   if (d->dtype != RSA_BF16 || dm.mode != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < det_bwd_bytes(dm)) return RSA_ERR_WORKSPACE;
   void *w = const_cast<void *>(ws);
   return hip_status(rsa::fused_bwd_dkdv(dm, dO, Q, K, V, fused_nL(dm, w), fused_nD(w), dK, dV, st));
 }
 
 int rsa_bwd_dq(const rsa_desc *d, const void *dO, const void *Q, const void *K, const void *V,
-               void *ws, void *dQ, void *stream) {
-  RSA_STEP_PROLOGUE(dO && Q && K && V && ws && dQ, dO, Q, K, V, ws, dQ);
+               void *ws, size_t ws_bytes, void *dQ, void *stream) {
+  RSA_STEP_PROLOGUE(dO && Q && K && V && dQ, dO, Q, K, V, ws, dQ);
   if (d->dtype != RSA_BF16 || dm.mode != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;
+  if (!ws || ws_bytes < det_bwd_bytes(dm)) return RSA_ERR_WORKSPACE;
   return hip_status(rsa::fused_bwd_dq(dm, dO, Q, K, V, fused_nL(dm, ws), fused_nD(ws), dQ, st,
                                       fused_part(dm, ws), rsa::fused_key_splits(dm)));
 }
@@ -351,7 +377,7 @@ namespace {
 int proj_check(const rsa_desc *d, int32_t H, Dims *dm) {
   int rc = validate(d, dm);
   if (rc != RSA_OK) return rc;
-  if (dm->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16) return RSA_ERR_UNSUPPORTED;
+  if (dm->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16 || dm->strided) return RSA_ERR_UNSUPPORTED;
   if (H < 64) return RSA_ERR_SHAPE;
   if (H % 64 != 0) return RSA_ERR_UNSUPPORTED;
   // the GEMM kernel indexes rows and columns of its operands with 32 bits
@@ -415,7 +441,7 @@ namespace {
 int linformer_dims(const rsa_desc *d, int32_t Kp, Dims *own, Dims *att) {
   int rc = validate(d, own);
   if (rc != RSA_OK) return rc;
-  if (own->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16 || own->zigzag || own->causal)
+  if (own->mode != RSA_MODE_FUSED || d->dtype != RSA_BF16 || own->zigzag || own->causal || own->strided)
     return RSA_ERR_UNSUPPORTED;
   if (Kp < 64) return RSA_ERR_SHAPE;
   if (Kp % 64 != 0) return RSA_ERR_UNSUPPORTED;
@@ -424,6 +450,7 @@ int linformer_dims(const rsa_desc *d, int32_t Kp, Dims *own, Dims *att) {
   *att = *own;
   att->N = 1; att->rank_begin = 0; att->rank_end = 1;
   att->L = Kp; att->c = Kp;  // Lq stays: the ranks' rows
+  att->ks[0] = (int64_t)own->Z * Kp * own->A; att->ks[1] = (int64_t)Kp * own->A; att->ks[2] = own->A;
   return RSA_OK;
 }
 size_t linformer_ws(const Dims &own, const Dims &att, int64_t Kp) {

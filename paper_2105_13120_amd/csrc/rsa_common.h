@@ -126,6 +126,10 @@ struct Dims {
   int zigzag;  // 1: rank n owns half-chunks n and 2N-1-n (RSA_OWN_ZIGZAG)
   int64_t L, c, Lq;
   float scale;
+  int deterministic;  // RSA_DETERMINISTIC: dQ from its own kernel, no atomics
+  // element strides of (batch, head, row) for Q/dQ, K/V/dK/dV and O/dO; strided = any not dense
+  int64_t qs[3], ks[3], os[3];
+  int strided;
 };
 
 // Which global token a local query row is.  Contiguous ownership (the paper, section 3.1):

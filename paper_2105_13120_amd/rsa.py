@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_PKG, "librsa_hip.so")
 RSA_F32, RSA_BF16 = 0, 1
 MODE_FUSED, MODE_STAGED = 0, 1
 OWN_ZIGZAG = 2   # flag bit: rank n owns half-chunks n and 2N-1-n
+DETERMINISTIC = 4   # flag bit: dQ from a kernel of its own (fixed summation order, no atomics)
 
 EXPORTS = (
     "rsa_version", "rsa_strerror", "rsa_workspace_bytes", "rsa_forward", "rsa_backward",
@@ -34,6 +35,8 @@ class RSADesc(ctypes.Structure):
         ("rank_begin", ctypes.c_int32), ("rank_end", ctypes.c_int32),
         ("causal", ctypes.c_int32), ("dtype", ctypes.c_int32),
         ("scale", ctypes.c_float), ("flags", ctypes.c_uint32),
+        ("q_stride", ctypes.c_int64 * 3), ("kv_stride", ctypes.c_int64 * 3),
+        ("o_stride", ctypes.c_int64 * 3),
     ]
 
 
@@ -75,8 +78,8 @@ def lib():
         L.rsa_dk_step.argtypes = [dp, i, i, vp, vp, vp, i, vp]
         L.rsa_store.argtypes = [dp, vp, vp, sz, vp]
         L.rsa_bwd_preprocess.argtypes = [dp, vp, vp, vp, vp, sz, vp]
-        L.rsa_bwd_dkdv.argtypes = [dp] + [vp] * 8
-        L.rsa_bwd_dq.argtypes = [dp] + [vp] * 7
+        L.rsa_bwd_dkdv.argtypes = [dp] + [vp] * 5 + [sz] + [vp] * 3
+        L.rsa_bwd_dq.argtypes = [dp] + [vp] * 5 + [sz] + [vp] * 2
         L.rsa_proj_workspace_bytes.argtypes = [dp, i]
         L.rsa_qkv_proj.argtypes = [dp, i] + [vp] * 6
         L.rsa_out_proj.argtypes = [dp, i] + [vp] * 4
@@ -120,13 +123,28 @@ def _dtype_code(t):
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
+def _strides(t):
+    """(batch, head, row) element strides of a (B, Z, rows, A) tensor whose last index is contiguous."""
+    assert t.dim() == 4 and (t.shape[3] == 1 or t.stride(3) == 1), "the last index must be contiguous"
+    return (ctypes.c_int64 * 3)(t.stride(0), t.stride(1), t.stride(2))
+
+
 def make_desc(K, N, causal=False, rank_begin=0, rank_end=None, mode=MODE_FUSED, scale=0.0,
-              zigzag=False):
-    """Descriptor for K of shape (B, Z, L, A).  zigzag: rank n owns half-chunks n and 2N-1-n."""
+              zigzag=False, deterministic=False, Q=None, O=None):
+    """Descriptor for K of shape (B, Z, L, A).  zigzag: rank n owns half-chunks n and 2N-1-n.
+    deterministic: RSA_DETERMINISTIC.  K's strides are taken when it is not contiguous (V, dK, dV
+    must then share them); Q and O, when given, supply the strides of Q/dQ and O/dO likewise."""
     B, Z, L, A = K.shape
-    return RSADesc(B, Z, A, L, N, rank_begin, N if rank_end is None else rank_end,
-                   int(bool(causal)), _dtype_code(K), float(scale),
-                   int(mode) | (OWN_ZIGZAG if zigzag else 0))
+    d = RSADesc(B, Z, A, L, N, rank_begin, N if rank_end is None else rank_end,
+                int(bool(causal)), _dtype_code(K), float(scale),
+                int(mode) | (OWN_ZIGZAG if zigzag else 0) | (DETERMINISTIC if deterministic else 0))
+    if not K.is_contiguous():
+        d.kv_stride = _strides(K)
+    if Q is not None and not Q.is_contiguous():
+        d.q_stride = _strides(Q)
+    if O is not None and not O.is_contiguous():
+        d.o_stride = _strides(O)
+    return d
 
 
 def workspace_bytes(desc, backward):
@@ -142,7 +160,7 @@ def _workspace(desc, backward, device):
 def forward(desc, Q, K, V, O=None, LSE=None, ws=None):
     """rsa_forward.  Q: (B,Z,Lq,A); K, V: (B,Z,L,A).  Returns (O, LSE)."""
     for t in (Q, K, V):
-        assert t.is_cuda and t.is_contiguous()
+        assert t.is_cuda and t.stride(-1) == 1   # other strides travel in the descriptor
     if O is None:
         O = torch.empty_like(Q)
     if LSE is None:
@@ -159,7 +177,7 @@ def forward(desc, Q, K, V, O=None, LSE=None, ws=None):
 def backward(desc, dO, Q, K, V, O, LSE, dQ=None, dK=None, dV=None, ws=None):
     """rsa_backward.  Returns (dQ, dK, dV)."""
     for t in (dO, Q, K, V, O, LSE):
-        assert t.is_cuda and t.is_contiguous()
+        assert t.is_cuda and t.stride(-1) == 1
     dQ = torch.empty_like(Q) if dQ is None else dQ
     dK = torch.empty_like(K) if dK is None else dK
     dV = torch.empty_like(V) if dV is None else dV
@@ -220,13 +238,13 @@ def bwd_preprocess(desc, dO, O, LSE, ws):
 
 
 def bwd_dkdv(desc, dO, Q, K, V, ws, dK, dV):
-    _check(lib().rsa_bwd_dkdv(ctypes.byref(desc), _p(dO), _p(Q), _p(K), _p(V), _p(ws), _p(dK),
-                              _p(dV), _stream()))
+    _check(lib().rsa_bwd_dkdv(ctypes.byref(desc), _p(dO), _p(Q), _p(K), _p(V), _p(ws), ws.numel(),
+                              _p(dK), _p(dV), _stream()))
 
 
 def bwd_dq(desc, dO, Q, K, V, ws, dQ):
-    _check(lib().rsa_bwd_dq(ctypes.byref(desc), _p(dO), _p(Q), _p(K), _p(V), _p(ws), _p(dQ),
-                            _stream()))
+    _check(lib().rsa_bwd_dq(ctypes.byref(desc), _p(dO), _p(Q), _p(K), _p(V), _p(ws), ws.numel(),
+                            _p(dQ), _stream()))
 
 
 # ---- the linear maps around RSA (Table 2, rows Q/K/V and Linear) ----

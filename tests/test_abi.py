@@ -30,6 +30,9 @@ def desc(**kw):
     d = dict(B=1, Z=2, A=64, L=256, N=4, rank_begin=0, rank_end=4, causal=0,
              dtype=rsa.RSA_BF16, scale=0.0, flags=rsa.MODE_FUSED)
     d.update(kw)
+    for k in ("q_stride", "kv_stride", "o_stride"):
+        if k in d:
+            d[k] = (ctypes.c_int64 * 3)(*d[k])
     return rsa.RSADesc(**d)
 
 
@@ -66,6 +69,17 @@ def test_validation_happens_before_any_launch():
     p = ctypes.c_void_p(0x1000)
     bwd = rsa.lib().rsa_backward(ctypes.byref(desc()), p, p, p, p, p, p, p, p, p, None, 0, None)
     assert bwd == -4                                          # backward always needs D
+    # the kernels of the backward on their own check their workspace on the host too
+    L = rsa.lib()
+    need = rsa.workspace_bytes(desc(flags=rsa.DETERMINISTIC), True)
+    assert need == 2 * (1 * 2 * 256 * 4)
+    assert L.rsa_bwd_dkdv(ctypes.byref(desc()), p, p, p, p, p, need - 1, p, p, None) == -4
+    assert L.rsa_bwd_dkdv(ctypes.byref(desc()), p, p, p, p, None, need, p, p, None) == -4
+    assert L.rsa_bwd_dq(ctypes.byref(desc()), p, p, p, p, p, need - 1, p, None) == -4
+    assert L.rsa_bwd_dq(ctypes.byref(desc()), p, p, p, p, None, 1 << 30, p, None) == -4
+    assert L.rsa_bwd_preprocess(ctypes.byref(desc()), p, p, p, p, need - 1, None) == -4
+    split = desc(B=1, Z=2, L=4096, N=4, rank_begin=3, rank_end=4)   # split key walk: partial dQ behind the row terms
+    assert L.rsa_bwd_dq(ctypes.byref(split), p, p, p, p, p, 2 * 2048 * 4, p, None) == -4
     step = rsa.lib().rsa_qk_step(ctypes.byref(staged), 4, 0, p, p, p, None)
     assert step == -2                                         # rank outside [begin, end)
     step = rsa.lib().rsa_qk_step(ctypes.byref(staged), 0, 7, p, p, p, None)
