@@ -6,8 +6,21 @@ with bf16 matrix-core operands and bf16 storage must make:
     the stored O (which then enters D = rowsum(dO o O)), and the stored dQ, dK, dV.
 The fused HIP kernels make exactly these roundings and no others (their scores, softmax
 statistics, products with the row terms and accumulations are fp32), so this model is
-also the model of the kernels; the GPU tests hold the kernels to a stated multiple of
-its error on the same inputs.
+also the model of the kernels; the GPU tests hold the kernels to stated multiples of
+its error on the same inputs.  Two details of how P is rounded in the forward:
+  reference="true_max":    P = bf16(exp(S - max_j S)): a two-pass softmax.  The row's largest
+                           probability is then exactly 1 and carries no rounding error.
+  reference="running_max": an online softmax rounds exp(S - m) for whatever m its running
+                           maximum held when the key went by, so where in its binade a
+                           probability sits (which decides its rounding error) is arbitrary,
+                           the largest one included.  Modelled by a seeded per-row offset
+                           u in [0, 1): P = 2^u bf16(2^-u exp(S - max_j S)).
+The two differ only on rows that one key dominates (a sharp softmax: that key's rounding is
+most of the row's error); the fused forward is an online softmax and is compared with the second.
+
+`strip_bf16_pipeline` is the model of the paper's two-pass layout with the score strip stored
+in bf16: the normalised P is rounded once, when it is written, and both O = P V and
+dS = P o (dP - D) are formed from that rounded P (dS is then rounded again as an operand).
 
 `folded_scale_pipeline` adds the one rounding an earlier version of the backward kernels
 made on top: the factor s log2(e) folded into a bf16 operand (K for dK/dV, Q for dQ).
@@ -26,7 +39,7 @@ def r(a):
     return inputs.round_to_bf16(np.asarray(a, dtype=np.float32)).astype(np.float64)
 
 
-def _head(Q, K, V, dO, s, qtok, causal, fold):
+def _head(Q, K, V, dO, s, qtok, causal, fold=False, strip=False, rng=None):
     """One head: Q, dO (Lq, A) are the query rows of tokens qtok; K, V (L, A)."""
     L = K.shape[0]
     log2e = 1.4426950408889634
@@ -38,7 +51,17 @@ def _head(Q, K, V, dO, s, qtok, causal, fold):
     m = S.max(-1, keepdims=True)
     p = np.exp(S - m)
     l = p.sum(-1, keepdims=True)
-    O = r((r(p) @ V) / l)
+    P = p / l
+    if strip:
+        Pr = r(P)
+        O = r(Pr @ V)
+    else:
+        if rng is None:
+            pr = r(p)
+        else:
+            u = np.exp2(rng.random((Q.shape[0], 1)))
+            pr = r(p / u) * u
+        O = r((pr @ V) / l)
     out = [O, m[:, 0] + np.log(l[:, 0])]
     if dO is None:
         return out
@@ -52,8 +75,10 @@ def _head(Q, K, V, dO, s, qtok, causal, fold):
             Sk[mask] = -np.inf
             Sq[mask] = -np.inf
         Pk, Pq = np.exp2(Sk - lse * log2e), np.exp2(Sq - lse * log2e)
+    elif strip:
+        Pk = Pq = Pr
     else:
-        Pk = Pq = p / l
+        Pk = Pq = P
     dP = dO @ V.T
     D = (dO * O).sum(-1, keepdims=True)
     dV = r(r(Pk).T @ dO)
@@ -62,7 +87,7 @@ def _head(Q, K, V, dO, s, qtok, causal, fold):
     return out + [dQ, dK, dV]
 
 
-def _pipeline(Q, K, V, dO, scale, qtok, causal, fold):
+def _pipeline(Q, K, V, dO, scale, qtok, causal, **kw):
     B, Z, Lq, A = Q.shape
     s = 1.0 / np.sqrt(A) if scale is None else scale
     qtok = np.arange(Lq) if qtok is None else np.asarray(qtok, dtype=np.int64)
@@ -70,7 +95,7 @@ def _pipeline(Q, K, V, dO, scale, qtok, causal, fold):
     res = None
     for b in range(B):
         for z in range(Z):
-            h = _head(Q[b, z], K[b, z], V[b, z], None if dO is None else dO[b, z], s, qtok, causal, fold)
+            h = _head(Q[b, z], K[b, z], V[b, z], None if dO is None else dO[b, z], s, qtok, causal, **kw)
             if res is None:
                 res = [np.empty((B, Z) + x.shape) for x in h]
             for dst, x in zip(res, h):
@@ -78,13 +103,20 @@ def _pipeline(Q, K, V, dO, scale, qtok, causal, fold):
     return tuple(res)
 
 
-def ideal_bf16_pipeline(Q, K, V, dO=None, scale=None, qtok=None, causal=False):
+def ideal_bf16_pipeline(Q, K, V, dO=None, scale=None, qtok=None, causal=False, reference="true_max"):
     """(O, LSE) or (O, LSE, dQ, dK, dV) of the ideal bf16 pipeline; arrays (B, Z, rows, A) float64
     holding bf16-representable inputs.  Row i of Q, dO is token qtok[i] of the sequence (default:
-    token i); dK, dV are those rows' partial sums."""
-    return _pipeline(Q, K, V, dO, scale, qtok, causal, fold=False)
+    token i); dK, dV are those rows' partial sums.  reference: see the top of the file."""
+    assert reference in ("true_max", "running_max")
+    rng = np.random.Generator(np.random.PCG64(20210525)) if reference == "running_max" else None
+    return _pipeline(Q, K, V, dO, scale, qtok, causal, rng=rng)
+
+
+def strip_bf16_pipeline(Q, K, V, dO=None, scale=None, qtok=None, causal=False):
+    """The same for the two-pass layout whose probability strip is stored in bf16."""
+    return _pipeline(Q, K, V, dO, scale, qtok, causal, strip=True)
 
 
 def folded_scale_pipeline(Q, K, V, dO, scale=None, qtok=None, causal=False):
-    """The same with s log2(e) folded into a bf16 operand of the recomputed scores."""
+    """The ideal pipeline with s log2(e) folded into a bf16 operand of the recomputed scores."""
     return _pipeline(Q, K, V, dO, scale, qtok, causal, fold=True)

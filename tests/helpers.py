@@ -3,7 +3,7 @@ import numpy as np
 import torch
 
 import oracle
-from bf16_model import ideal_bf16_pipeline
+from bf16_model import ideal_bf16_pipeline, strip_bf16_pipeline
 from paper_2105_13120_amd import inputs, rsa
 
 # Tolerances of the comparison with the fp64 oracle.
@@ -22,11 +22,19 @@ from paper_2105_13120_amd import inputs, rsa
 #       0.33 to 0.89 of this bound on the shapes of tests/test_tolerance_model.py.
 #   (2) the whole tensor:  rms(x - r) <= 3e-3 rms(r)   (the ideal pipeline: 2.0e-3 to 2.5e-3).
 #   (3) against the ideal pipeline on the same inputs (wherever a test computes it: every dense
-#       comparison): max|x - r| <= 1.5 max|ideal - r| and rms(x - r) <= 1.15 rms(ideal - r).
+#       comparison): rms(x - r) <= 1.15 rms(ideal - r), the 99.9th percentile of |x - r| <= 1.25
+#       times that of |ideal - r|, and max|x - r| <= 2.5 max|ideal - r|.
 #       The ideal pipeline is exact arithmetic with only the roundings a bf16 matrix-core path
 #       cannot avoid, which are also exactly the roundings the fused kernels make; (3) is what
 #       rejects avoidable error: a second rounding of a scaled operand (the planted mistake of
 #       tests/test_tolerance_model.py) passes (1) and fails (3) at 1.27 of the ideal RMS error.
+#       The largest error of a tensor is one draw from the few elements of its top binade (their
+#       store alone errs by up to half an ulp, and the P-rounding noise under it, a quarter ulp,
+#       decides which way they round): two correct pipelines differ by a factor of up to about 2
+#       there (the forward keeps P relative to a running maximum, the model to the true one, so
+#       their rounding draws differ), hence the loose factor on the maximum and the tight ones on
+#       the tail percentile and the RMS.  dK and dV, whose P both sides form from the same LSE,
+#       agree with the model to the last digit of the largest error.
 #  dQ carries one more term in (1).  Every bf16 backward forms D_i = sum_a dO_ia O_ia from the
 #  *stored* O, whose rounding leaves an error delta_i in D_i with standard deviation
 #  2^-9 / sqrt(3) * sqrt(sum_a dO_ia^2 O_ia^2).  It enters dS_ij = P_ij (dP_ij - D_i) for every key
@@ -40,7 +48,8 @@ F32_ATOL = 1e-4
 BF16_REL_RMS = 2e-2
 BF16_RTOL = 2.0 ** -7
 BF16_REL_RMS_MEAN = 3e-3
-IDEAL_MAX_RATIO = 1.5
+IDEAL_MAX_RATIO = 2.5
+IDEAL_P999_RATIO = 1.25
 IDEAL_RMS_RATIO = 1.15
 LSE_ATOL = 1e-4
 
@@ -80,9 +89,11 @@ def dq_extra(Q, K, V, dO, O_ref, q0, causal, scale=None):
 
 class Err(float):
     """max abs err / rms (bf16) or max abs err (f32), with the other figures as attributes:
-    rms_rel = rms(err) / rms; vs_ideal_max, vs_ideal_rms = the ratios of criterion (3) or None."""
+    rms_rel = rms(err) / rms; vs_ideal_max, vs_ideal_p999, vs_ideal_rms = the ratios of criterion (3)
+    or None."""
     rms_rel = None
     vs_ideal_max = None
+    vs_ideal_p999 = None
     vs_ideal_rms = None
 
     def describe(self):
@@ -90,14 +101,19 @@ class Err(float):
         if self.rms_rel is not None:
             t += f" (rms {self.rms_rel:.2e}"
             if self.vs_ideal_max is not None:
-                t += f"; x{self.vs_ideal_max:.2f} max, x{self.vs_ideal_rms:.2f} rms of ideal"
+                t += (f"; x{self.vs_ideal_max:.2f} max, x{self.vs_ideal_p999:.2f} p99.9, "
+                      f"x{self.vs_ideal_rms:.2f} rms of ideal")
             t += ")"
         return t
 
 
-def check(name, got, ref, dtype, extra=None, ideal=None):
+def check(name, got, ref, dtype, extra=None, ideal=None, both_rounded=False, strip=False):
     """Assert the tolerance for one output tensor; returns an Err.  extra: per-element addition
-    to the bf16 bound; ideal: the same tensor from the ideal bf16 pipeline (criterion (3))."""
+    to the bf16 bound; ideal: the same tensor from the ideal bf16 pipeline (criterion (3));
+    both_rounded: ref is itself a bf16 result of the HIP path (two layouts or ring sizes compared
+    with each other), so the difference carries both sides' noise: bounds times sqrt(2).
+    strip: a result of the two-pass layout, whose bf16 probability strip rounds P once more on the
+    way into dS (RMS error of dQ, dK sqrt(1.5) times the ideal pipeline's): criterion (2) times 1.25."""
     assert got.shape == ref.shape, (name, got.shape, ref.shape)
     assert np.isfinite(got).all(), f"{name}: non-finite values"
     diff = np.abs(got - ref)
@@ -106,20 +122,25 @@ def check(name, got, ref, dtype, extra=None, ideal=None):
         assert err <= F32_ATOL, f"{name}: max abs err {err:.3e} > {F32_ATOL}"
         return Err(err)
     rms = max(float(np.sqrt(np.mean(np.square(ref)))), 1e-30)
-    bound = BF16_REL_RMS * rms + BF16_RTOL * np.abs(ref).max(axis=-1, keepdims=True)
+    widen = np.sqrt(2.0) if both_rounded else 1.0
+    bound = widen * (BF16_REL_RMS * rms + BF16_RTOL * np.abs(ref).max(axis=-1, keepdims=True))
     if extra is not None:
         bound = bound + extra
     worst = float((diff / bound).max())
     assert worst <= 1.0, (f"{name}: error is {worst:.3f} of the bound "
                           f"(max abs err / rms = {diff.max() / rms:.3e})")
     mean = float(np.sqrt(np.mean(np.square(diff))))
-    assert mean <= BF16_REL_RMS_MEAN * rms, f"{name}: rms err / rms {mean / rms:.3e} > {BF16_REL_RMS_MEAN}"
+    rms_bar = widen * (1.25 if strip else 1.0) * BF16_REL_RMS_MEAN
+    assert mean <= rms_bar * rms, f"{name}: rms err / rms {mean / rms:.3e} > {rms_bar:.2e}"
     e = Err(float(diff.max()) / rms)
     e.rms_rel = mean / rms
     if ideal is not None:
         di = np.abs(ideal - ref)
         e.vs_ideal_max = float(diff.max()) / max(float(di.max()), 1e-30)
         e.vs_ideal_rms = mean / max(float(np.sqrt(np.mean(np.square(di)))), 1e-30)
+        e.vs_ideal_p999 = float(np.quantile(diff, 0.999)) / max(float(np.quantile(di, 0.999)), 1e-30)
+        assert e.vs_ideal_p999 <= IDEAL_P999_RATIO, (f"{name}: the 99.9th percentile of the error is "
+                                                    f"{e.vs_ideal_p999:.2f} times the ideal bf16 pipeline's")
         assert e.vs_ideal_max <= IDEAL_MAX_RATIO, (f"{name}: max err is {e.vs_ideal_max:.2f} times the ideal "
                                                    f"bf16 pipeline's ({diff.max() / rms:.3e} of the rms)")
         assert e.vs_ideal_rms <= IDEAL_RMS_RATIO, (f"{name}: rms err is {e.vs_ideal_rms:.2f} times the ideal "
@@ -176,10 +197,11 @@ def oracle_on_segments(cfg, Qh, Kh, Vh, dOh=None):
     return O, LSE, dQ, dK, dV, extra
 
 
-def compare_heads(cfg, x, out, heads, backward=True, ideal=True, ideal_heads=16):
+def compare_heads(cfg, x, out, heads, backward=True, ideal=True, ideal_heads=16, mode=rsa.MODE_FUSED):
     """Full comparison with the oracle on the listed flat head indices.  ideal: also hold the bf16
-    outputs to the stated multiples of the ideal bf16 pipeline's error (criterion (3) on top), on
-    the first `ideal_heads` of the listed heads."""
+    outputs to the stated multiples of the error of the CPU model of their pipeline (criterion (3)
+    on top), on the first `ideal_heads` of the listed heads: the ideal bf16 pipeline with P relative
+    to a running maximum for the fused kernels, the bf16-strip pipeline for the two-pass layout."""
     Qh, Kh, Vh = (heads_view(x[k], heads) for k in ("Q", "K", "V"))
     dOh = heads_view(x["dO"], heads) if backward else None
     O_ref, LSE_ref, dQ_ref, dK_ref, dV_ref, dq_x = oracle_on_segments(cfg, Qh, Kh, Vh, dOh)
@@ -187,7 +209,7 @@ def compare_heads(cfg, x, out, heads, backward=True, ideal=True, ideal_heads=16)
     refs = dict(O=O_ref, dQ=dQ_ref, dK=dK_ref, dV=dV_ref)
     errs = {}
     for name in got:
-        errs[name] = check(name, got[name], refs[name], cfg.dtype,
+        errs[name] = check(name, got[name], refs[name], cfg.dtype, strip=mode == rsa.MODE_STAGED,
                            extra=dq_x if name == "dQ" and cfg.dtype == "bf16" else None)
     lse = download(out["LSE"]).reshape(-1, cfg.Lq)[heads][None]
     err = float(np.abs(lse - LSE_ref).max())
@@ -196,14 +218,18 @@ def compare_heads(cfg, x, out, heads, backward=True, ideal=True, ideal_heads=16)
     if ideal and cfg.dtype == "bf16":
         n = min(ideal_heads, len(heads))
         cut = lambda a: None if a is None else a[:, :n]
-        m = ideal_bf16_pipeline(cut(Qh), cut(Kh), cut(Vh), cut(dOh), scale=att_scale(cfg),
-                                qtok=row_tokens(cfg), causal=cfg.causal)
+        if mode == rsa.MODE_STAGED:
+            m = strip_bf16_pipeline(cut(Qh), cut(Kh), cut(Vh), cut(dOh), scale=att_scale(cfg),
+                                    qtok=row_tokens(cfg), causal=cfg.causal)
+        else:
+            m = ideal_bf16_pipeline(cut(Qh), cut(Kh), cut(Vh), cut(dOh), scale=att_scale(cfg),
+                                    qtok=row_tokens(cfg), causal=cfg.causal, reference="running_max")
         model = dict(O=m[0])
         if backward:
             model.update(dQ=m[2], dK=m[3], dV=m[4])
         for name in got:
             errs[name] = check(name, cut(got[name]), cut(refs[name]), cfg.dtype, ideal=model[name],
-                               extra=cut(dq_x) if name == "dQ" else None)
+                               extra=cut(dq_x) if name == "dQ" else None, strip=mode == rsa.MODE_STAGED)
     return errs
 
 

@@ -3,27 +3,44 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import (BF16_REL_RMS, LSE_ATOL, check, compare_heads, describe, download,
+from helpers import (BF16_REL_RMS, LSE_ATOL, check, compare_heads, describe, download, dq_extra,
                      gpu_forward_backward, heads_view)
 from paper_2105_13120_amd import inputs, rsa
 
 pytestmark = pytest.mark.gpu
 
 
-def test_bert_base_all_heads_sampled():
+def test_bert_base_all_heads():
+    """Every one of the 192 (batch, head) pairs of the BERT-Base-shaped workload."""
     cfg = inputs.CONFIGS["bert_base"]
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x)
-    heads = [0, 1, 11, 12, 95, 96, 190, 191]
-    print(describe(compare_heads(cfg, x, out, heads)))
+    check_sum_rules(cfg, x, out)
+    print(describe(compare_heads(cfg, x, out, list(range(cfg.B * cfg.Z)), ideal_heads=32)))
 
 
-def test_bert_large_sampled_heads():
+def test_bert_large_all_heads():
+    """Every one of the 128 (batch, head) pairs of the BERT-Large-shaped workload (the one
+    bench.py times by default)."""
     cfg = inputs.CONFIGS["bert_large"]
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x)
     check_sum_rules(cfg, x, out)
-    print(describe(compare_heads(cfg, x, out, [0, 15, 64, 127])))
+    print(describe(compare_heads(cfg, x, out, list(range(cfg.B * cfg.Z)), ideal_heads=8)))
+
+
+def forward_all_rows(cfg, x, out, heads):
+    """O and LSE on every local row of the listed heads."""
+    Qh, Kh, Vh = (heads_view(x[k], heads) for k in ("Q", "K", "V"))
+    O = heads_view(download(out["O"]), heads)
+    LSE = download(out["LSE"]).reshape(-1, cfg.Lq)[heads][None]
+    for s0, t0, n in cfg.segments():
+        O_ref, LSE_ref = oracle.forward(np.ascontiguousarray(Qh[:, :, s0:s0 + n]), Kh, Vh, q0=t0,
+                                        causal=cfg.causal)
+        e = check("O", O[:, :, s0:s0 + n], O_ref, cfg.dtype)
+        err = np.abs(LSE[:, :, s0:s0 + n] - LSE_ref).max()
+        assert err <= LSE_ATOL, f"LSE: {err:.3e}"
+        print(f"heads {heads} rows {s0}..{s0 + n}: O {e.describe()}, LSE {err:.2e}")
 
 
 def sampled_check(cfg, x, out, head, row_blocks, cols):
@@ -37,18 +54,26 @@ def sampled_check(cfg, x, out, head, row_blocks, cols):
     # the RMS that normalises the error is that of the whole head, from the full backward below;
     # one oracle call per run of consecutive tokens (one run unless ownership is zig-zag)
     dQ_ref = np.empty_like(Qh)
+    dq_x = np.zeros_like(Qh)
     dK_ref = dV_ref = None
     for s0, t0, n in cfg.segments():
-        g = oracle.backward(np.ascontiguousarray(Qh[:, :, s0:s0 + n]), Kh, Vh,
-                            np.ascontiguousarray(dOh[:, :, s0:s0 + n]), q0=t0, causal=cfg.causal, cols=cols)
+        Qs, dOs = (np.ascontiguousarray(a[:, :, s0:s0 + n]) for a in (Qh, dOh))
+        g = oracle.backward(Qs, Kh, Vh, dOs, q0=t0, causal=cfg.causal, cols=cols)
         dQ_ref[:, :, s0:s0 + n] = g[0]
         dK_ref = g[1] if dK_ref is None else dK_ref + g[1]
         dV_ref = g[2] if dV_ref is None else dV_ref + g[2]
-    check("dQ", dQ[None, None], dQ_ref, cfg.dtype)
+        if cfg.causal:
+            # the allowance for the rounding of O inside D matters on rows that see few keys:
+            # the first 256 tokens of a run that starts the sequence
+            m = min(n, max(0, 256 - t0))
+            if m > 0:
+                O_ref = oracle.forward(Qs[:, :, :m], Kh, Vh, q0=t0, causal=True)[0]
+                dq_x[:, :, s0:s0 + m] = dq_extra(Qs[:, :, :m], Kh, Vh, dOs[:, :, :m], O_ref, t0, True)
+    print("dQ", check("dQ", dQ[None, None], dQ_ref, cfg.dtype, extra=dq_x).describe())
     dK = download(out["dK"]).reshape(-1, cfg.L, cfg.A)[head][cols]
     dV = download(out["dV"]).reshape(-1, cfg.L, cfg.A)[head][cols]
-    check("dK", dK[None, None], dK_ref, cfg.dtype)
-    check("dV", dV[None, None], dV_ref, cfg.dtype)
+    print("dK", check("dK", dK[None, None], dK_ref, cfg.dtype).describe())
+    print("dV", check("dV", dV[None, None], dV_ref, cfg.dtype).describe())
     for r0, nr in row_blocks:
         s0, t0, n = next(s for s in cfg.segments() if s[0] <= r0 and r0 + nr <= s[0] + s[2])
         O_ref, LSE_ref = oracle.forward(np.ascontiguousarray(Qh[:, :, r0:r0 + nr]), Kh, Vh,
@@ -80,6 +105,8 @@ def test_long_32k_sampled():
     rng = np.random.Generator(np.random.PCG64(1))
     cols = np.concatenate([[0, 63, 64, 2047, 2048, 32767], rng.integers(0, cfg.L, 250)])
     sampled_check(cfg, x, out, head=5, row_blocks=[(0, 64), (2016, 64), (32768 - 96, 96)], cols=cols)
+    sampled_check(cfg, x, out, head=12, row_blocks=[], cols=cols[::2])
+    forward_all_rows(cfg, x, out, [0, 5, 10, 15])
 
 
 def test_rank15_of_64k_causal_sampled():
@@ -90,6 +117,7 @@ def test_rank15_of_64k_causal_sampled():
     cols = np.concatenate([[0, 4095, 4096, 61439, 61440, 61503, 65535],
                            rng.integers(0, cfg.L, 150), rng.integers(61440, cfg.L, 100)])
     sampled_check(cfg, x, out, head=11, row_blocks=[(0, 64), (2000, 100), (4096 - 64, 64)], cols=cols)
+    forward_all_rows(cfg, x, out, [0, 6, 11])
 
 
 def test_causal_ring_32k_sampled():
@@ -142,4 +170,4 @@ def test_bert_large_staged_layout_sampled_heads():
     cfg = inputs.CONFIGS["bert_large"]
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED)
-    print(describe(compare_heads(cfg, x, out, [0, 77, 127])))
+    print(describe(compare_heads(cfg, x, out, [0, 77, 127], mode=rsa.MODE_STAGED)))

@@ -76,6 +76,55 @@ def test_linformer_chain(B, Z, L, N, ranks, Kp, A):
     assert not download(dK)[:, :, other].any() and not download(dE)[other].any()
 
 
+def test_linformer_chain_at_the_benchmark_size():
+    """The setting bench.py times (section 4.4's upper bound: 114688 tokens, batch 4, 12 heads of 64,
+    32 ranks, 256 projected keys), every stage on the GPU's own rounded inputs; the oracle runs on
+    sampled heads (and, for dE, which sums over heads, on sampled token rows over all heads)."""
+    B, Z, L, N, Kp, A = 4, 12, 114688, 32, 256, 64
+    heads = [0, 13, 29, 47]
+
+    def big(seed):   # (B, Z, L, A) drawn head by head in fp32 to bound the host memory
+        rng = np.random.Generator(np.random.PCG64(seed))
+        out = np.empty((B * Z, L, A), dtype=np.float32)
+        for h in range(B * Z):
+            out[h] = inputs.round_to_bf16(rng.standard_normal((L, A), dtype=np.float32))
+        return out.reshape(B, Z, L, A)
+
+    K, V, Q, dO = big(1), big(2), big(5), big(6)
+    E, F = draw((L, Kp), 3, L ** -0.5), draw((L, Kp), 4, L ** -0.5)
+    t = {k: upload(v, "bf16") for k, v in dict(K=K, V=V, E=E, F=F, Q=Q, dO=dO).items()}
+    desc = rsa.make_desc(t["K"], N)
+    hv = lambda a: np.ascontiguousarray(a.reshape(B * Z, *a.shape[2:])[heads][None].astype(np.float64))
+
+    Kp_ = rsa.linformer_project(desc, t["K"], t["E"])
+    Vp_ = rsa.linformer_project(desc, t["V"], t["F"])
+    torch.cuda.synchronize()
+    check("Kp", hv(download(Kp_)), LF.project(hv(K), E), "bf16")
+    check("Vp", hv(download(Vp_)), LF.project(hv(V), F), "bf16")
+
+    O, LSE = rsa.linformer_forward(desc, t["Q"], Kp_, Vp_)
+    dQ, dKp, dVp = rsa.linformer_backward(desc, t["dO"], t["Q"], Kp_, Vp_, O, LSE)
+    dK, dE = rsa.linformer_project_bwd(desc, dKp, t["K"], t["E"])
+    torch.cuda.synchronize()
+    Kp_h, Vp_h = hv(download(Kp_)), hv(download(Vp_))
+    O_ref, LSE_ref = LF.forward(hv(Q), Kp_h, Vp_h)
+    check("O", hv(download(O)), O_ref, "bf16")
+    assert np.abs(download(LSE).reshape(B * Z, L)[heads][None] - LSE_ref).max() <= LSE_ATOL
+    dQ_ref, dKp_ref, dVp_ref = LF.backward(hv(Q), Kp_h, Vp_h, hv(dO))
+    check("dQ", hv(download(dQ)), dQ_ref, "bf16")
+    check("dKp", hv(download(dKp)), dKp_ref, "bf16")
+    check("dVp", hv(download(dVp)), dVp_ref, "bf16")
+    dKp_h = download(dKp)
+    dK_ref, _ = LF.project_bwd(hv(dKp_h), hv(K), E)
+    check("dK", hv(download(dK)), dK_ref, "bf16")
+    # dE[l, :] = sum over all heads of X[b, z, l, :] dXp[b, z]^T, on sampled token rows
+    rows = np.concatenate([[0, 63, 64, 3583, 3584, L - 1],
+                           np.random.Generator(np.random.PCG64(9)).integers(0, L, 250)])
+    Xr = K[:, :, rows].astype(np.float64)                       # (B, Z, rows, A)
+    dE_ref = np.einsum("bzra,bzka->rk", Xr, dKp_h)
+    check_f32("dE", download(dE)[rows], dE_ref)
+
+
 def test_linformer_error_codes():
     K = torch.zeros((1, 2, 256, 64), dtype=torch.bfloat16, device="cuda")
     E = torch.zeros((256, 96), dtype=torch.bfloat16, device="cuda")      # Kp = 96: not a multiple of 64

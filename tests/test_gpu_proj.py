@@ -38,6 +38,7 @@ CASES = [
     (2, 3, 320, 5, (1, 4), 192, 128),
     (2, 5, 512, 4, (0, 4), 320, 128),     # 15 column tiles per output: work-groups straddle Q | K | V
     (1, 8, 2048, 8, (0, 8), 1024, 128),
+    (8, 16, 2048, 8, (0, 8), 1024, 64),   # the size bench.py times: 16384 rows, BERT Large's hidden size
 ]
 
 

@@ -81,8 +81,14 @@ def test_each_step_against_the_oracle(dtype, causal):
 
     dS = torch.empty_like(P)
     rsa.softmax_bwd(desc, n, P, dP, D, dS)
-    dS_tol = 1e-5 if dtype == "f32" else 0.03 * np.abs(dS_ref).max()
-    assert np.abs(download(dS) - dS_ref).max() < dS_tol
+    if dtype == "f32":
+        assert np.abs(download(dS) - dS_ref).max() < 1e-5
+    else:
+        # element by element: dS = bf16(bf16(P) (dP - D)) is two roundings of unit roundoff 2^-8
+        # each, plus P times the error that the rounding of O left in D
+        dD = np.abs(download(D)[:, :, rows] - (do64 * O_ref).sum(-1))[..., None]
+        bound = 2.05 * 2.0 ** -8 * np.abs(dS_ref) + 1.01 * P_ref * dD + 1e-7
+        assert (np.abs(download(dS) - dS_ref) <= bound).all()
 
     dQacc = torch.empty((cfg.B, cfg.Z, c, 64), dtype=torch.float32, device=dev)
     dKacc = torch.zeros((cfg.B, cfg.Z, L, 64), dtype=torch.float32, device=dev)
@@ -104,7 +110,7 @@ def test_config_tiny_f32_forward():
     cfg = inputs.CONFIGS["tiny_f32"]
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED, backward=False)
-    errs = compare_heads(cfg, x, out, [0, 1], backward=False)
+    errs = compare_heads(cfg, x, out, [0, 1], backward=False, mode=rsa.MODE_STAGED)
     assert errs["O"] <= 1e-4
 
 
@@ -114,7 +120,7 @@ def test_staged_forward_backward(dtype, causal, rb, re):
     cfg = small_cfg(dtype, causal, B=1, Z=3, L=384, N=6, rb=rb, re=re, seed=11)
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED)
-    compare_heads(cfg, x, out, [0, 1, 2])
+    compare_heads(cfg, x, out, [0, 1, 2], mode=rsa.MODE_STAGED)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -124,7 +130,7 @@ def test_staged_heads_wider_than_64(dtype, A, causal, rb, re):
     cfg = small_cfg(dtype, causal, B=1, Z=2, L=384, N=3, rb=rb, re=re, seed=29, A=A)
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED)
-    compare_heads(cfg, x, out, [0, 1])
+    compare_heads(cfg, x, out, [0, 1], mode=rsa.MODE_STAGED)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -134,4 +140,14 @@ def test_staged_forward_with_long_rows(dtype, L, N, causal):
     cfg = small_cfg(dtype, causal, B=1, Z=1, L=L, N=N, rb=N - 1, re=N, seed=31)
     x = inputs.make_inputs(cfg)
     out = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED, backward=False)
-    compare_heads(cfg, x, out, [0], backward=False)
+    compare_heads(cfg, x, out, [0], backward=False, mode=rsa.MODE_STAGED)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_staged_explicit_softmax_scale(dtype):
+    """rsa_desc.scale other than 1/sqrt(A) through the two-pass kernels."""
+    import dataclasses
+    cfg = dataclasses.replace(small_cfg(dtype, True, B=1, Z=2, L=384, N=3, seed=73), att_scale=0.2)
+    x = inputs.make_inputs(cfg)
+    out = gpu_forward_backward(cfg, x, mode=rsa.MODE_STAGED)
+    compare_heads(cfg, x, out, [0, 1], mode=rsa.MODE_STAGED)
