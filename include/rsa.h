@@ -198,6 +198,24 @@ int rsa_bwd_dq(const rsa_desc *d, const void *dO, const void *Q, const void *K,
                const void *V, void *ws, size_t ws_bytes, void *dQ, void *stream);
 
 /*
+ * rsa_backward for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels,
+ * with the workspace in a static device array of RSA_STATIC_SCRATCH_BYTES inside the
+ * library instead of a caller's buffer.  The call allocates and frees nothing.
+ * Descriptors whose rsa_workspace_bytes(d, 1) exceeds that size are rejected with
+ * RSA_ERR_WORKSPACE before anything is launched (RSA_DETERMINISTIC needs the least:
+ * 8 bytes per query row unless the key walk is split).  Every call on a GPU uses
+ * that GPU's one array: calls that overlap on one GPU (two streams, two threads) race,
+ * and the array keeps the previous call's contents (the kernels clear what they
+ * need cleared).  The first call on a device looks the array's address up
+ * (hipGetSymbolAddress); make that call outside a stream capture.
+ */
+#define RSA_STATIC_SCRATCH_BYTES (32u << 20)
+int rsa_backward_static(const rsa_desc *d, const void *dO, const void *Q, const void *K,
+                        const void *V, const void *O, const float *LSE, void *dQ,
+                        void *dK, void *dV, void *stream);
+
+/*
  * The two linear maps around RSA on the simulated ranks' rows (Table 2, sequence
  * parallelism rows "Q/K/V" and "Linear"), bf16 with fp32 accumulation, fused mode
  * descriptors only.  H is the hidden size (a multiple of 64).  X, Y and their

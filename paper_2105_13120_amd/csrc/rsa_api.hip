@@ -1,6 +1,7 @@
 // C ABI of the RSA library: argument validation and dispatch (declared in rsa.h).
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "rsa_kernels.h"
 
@@ -268,6 +269,42 @@ int rsa_backward(const rsa_desc *d, const void *dO, const void *Q, const void *K
   return hip_status(rsa::fused_backward(dm, dO, Q, K, V, O, LSE, dQ, dK, dV, fused_nD(ws),
                                         fused_nL(dm, ws), st, fused_part(dm, ws), 1,
                                         rsa::fused_key_splits(dm)));
+}
+
+// The workspace of rsa_backward_static: one array per GPU, inside the library's code object.
+// In host code the array's name is only a handle; its device address is looked up once per
+// device (with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[RSA_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_addr[kMaxDevices] = {};
+
+int scratch_of_current_device(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RSA_ERR_HIP;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_addr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return RSA_ERR_HIP;
+    scratch_addr[dev] = p;
+  }
+  *out = scratch_addr[dev];
+  return RSA_OK;
+}
+}  // namespace
+
+int rsa_backward_static(const rsa_desc *d, const void *dO, const void *Q, const void *K, const void *V,
+                        const void *O, const float *LSE, void *dQ, void *dK, void *dV, void *stream) {
+  Dims dm;
+  int rc = validate(d, &dm);
+  if (rc != RSA_OK) return rc;
+  if (dm.mode != RSA_MODE_FUSED) return RSA_ERR_UNSUPPORTED;  // the staged strip is far larger
+  if (workspace_bytes(dm, d->dtype, 1) > (size_t)RSA_STATIC_SCRATCH_BYTES) return RSA_ERR_WORKSPACE;
+  void *ws = nullptr;
+  if ((rc = scratch_of_current_device(&ws)) != RSA_OK) return rc;
+  return rsa_backward(d, dO, Q, K, V, O, LSE, dQ, dK, dV, ws, RSA_STATIC_SCRATCH_BYTES, stream);
 }
 
 // ------------------------------------------------------------ step level ----

@@ -16,12 +16,13 @@ RSA_F32, RSA_BF16 = 0, 1
 MODE_FUSED, MODE_STAGED = 0, 1
 OWN_ZIGZAG = 2   # flag bit: rank n owns half-chunks n and 2N-1-n
 DETERMINISTIC = 4   # flag bit: dQ from a kernel of its own (fixed summation order, no atomics)
+STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = (
     "rsa_version", "rsa_strerror", "rsa_workspace_bytes", "rsa_forward", "rsa_backward",
     "rsa_qk_step", "rsa_row_softmax", "rsa_av_step", "rsa_bwd_rowdot", "rsa_dv_step",
     "rsa_dp_step", "rsa_softmax_bwd", "rsa_dq_step", "rsa_dk_step", "rsa_store",
-    "rsa_bwd_preprocess", "rsa_bwd_dkdv", "rsa_bwd_dq",
+    "rsa_bwd_preprocess", "rsa_bwd_dkdv", "rsa_bwd_dq", "rsa_backward_static",
     "rsa_proj_workspace_bytes", "rsa_qkv_proj", "rsa_out_proj", "rsa_out_proj_bwd", "rsa_qkv_proj_bwd",
     "rsa_linformer_workspace_bytes", "rsa_linformer_project", "rsa_linformer_forward",
     "rsa_linformer_backward", "rsa_linformer_project_bwd",
@@ -80,6 +81,7 @@ def lib():
         L.rsa_bwd_preprocess.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         L.rsa_bwd_dkdv.argtypes = [dp] + [vp] * 5 + [sz] + [vp] * 3
         L.rsa_bwd_dq.argtypes = [dp] + [vp] * 5 + [sz] + [vp] * 2
+        L.rsa_backward_static.argtypes = [dp] + [vp] * 10
         L.rsa_proj_workspace_bytes.argtypes = [dp, i]
         L.rsa_qkv_proj.argtypes = [dp, i] + [vp] * 6
         L.rsa_out_proj.argtypes = [dp, i] + [vp] * 4
@@ -245,6 +247,14 @@ def bwd_dkdv(desc, dO, Q, K, V, ws, dK, dV):
 def bwd_dq(desc, dO, Q, K, V, ws, dQ):
     _check(lib().rsa_bwd_dq(ctypes.byref(desc), _p(dO), _p(Q), _p(K), _p(V), _p(ws), ws.numel(),
                             _p(dQ), _stream()))
+
+
+def backward_static(desc, dO, Q, K, V, O, LSE, dQ, dK, dV):
+    """rsa_backward_static: the workspace is the library's static device array; every buffer,
+    outputs included, is the caller's, so nothing is allocated here either."""
+    _check(lib().rsa_backward_static(ctypes.byref(desc), _p(dO), _p(Q), _p(K), _p(V), _p(O), _p(LSE),
+                                     _p(dQ), _p(dK), _p(dV), _stream()))
+    return dQ, dK, dV
 
 
 # ---- the linear maps around RSA (Table 2, rows Q/K/V and Linear) ----

@@ -80,6 +80,12 @@ def test_validation_happens_before_any_launch():
     assert L.rsa_bwd_preprocess(ctypes.byref(desc()), p, p, p, p, need - 1, None) == -4
     split = desc(B=1, Z=2, L=4096, N=4, rank_begin=3, rank_end=4)   # split key walk: partial dQ behind the row terms
     assert L.rsa_bwd_dq(ctypes.byref(split), p, p, p, p, p, 2 * 2048 * 4, p, None) == -4
+    # the variant with the static workspace rejects what does not fit, before touching the device
+    big = desc(B=64, Z=16, L=65536, N=4)
+    assert rsa.workspace_bytes(big, True) > rsa.STATIC_SCRATCH_BYTES
+    assert L.rsa_backward_static(ctypes.byref(big), p, p, p, p, p, p, p, p, p, None) == -4
+    assert L.rsa_backward_static(ctypes.byref(desc(N=3)), p, p, p, p, p, p, p, p, p, None) == -2
+    assert L.rsa_backward_static(ctypes.byref(desc(flags=rsa.MODE_STAGED)), p, p, p, p, p, p, p, p, p, None) == -3
     step = rsa.lib().rsa_qk_step(ctypes.byref(staged), 4, 0, p, p, p, None)
     assert step == -2                                         # rank outside [begin, end)
     step = rsa.lib().rsa_qk_step(ctypes.byref(staged), 0, 7, p, p, p, None)
