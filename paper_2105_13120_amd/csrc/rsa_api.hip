@@ -50,7 +50,6 @@ int validate(const rsa_desc *d, Dims *out) {
     if (st[t][0] != dense[0] || st[t][1] != dense[1] || st[t][2] != dense[2]) out->strided = 1;
   }
   if (out->strided && mode == RSA_MODE_STAGED) return RSA_ERR_UNSUPPORTED;
-  if (out->strided) return RSA_ERR_UNSUPPORTED;  // TODO(strides): until the fused kernels take them
   return RSA_OK;
 }
 

@@ -132,6 +132,28 @@ struct Dims {
   int strided;
 };
 
+// Element offset of row 0 of flat head index head = b * Z + z in a tensor whose batch, head and
+// row strides are st[0], st[1], st[2].
+__host__ __device__ inline int64_t head_offset(int64_t head, int Z, const int64_t *st) {
+  return (head / Z) * st[0] + (head % Z) * st[1];
+}
+
+// Where a row of a strided output tensor lives, for kernels that walk (head, row) pairs flat:
+// flat_row = head * rows_per_head + row.
+struct OutLayout {
+  int64_t st[3], rows_per_head;
+  int Z;
+  __host__ __device__ int64_t row_off(int64_t flat_row) const {
+    return head_offset(flat_row / rows_per_head, Z, st) + (flat_row % rows_per_head) * st[2];
+  }
+};
+inline OutLayout make_out_layout(const int64_t *st, int64_t rows_per_head, int Z) {
+  OutLayout l;
+  for (int k = 0; k < 3; ++k) l.st[k] = st[k];
+  l.rows_per_head = rows_per_head; l.Z = Z;
+  return l;
+}
+
 // Which global token a local query row is.  Contiguous ownership (the paper, section 3.1):
 // rank n owns rows [n c, (n+1) c).  Zig-zag ownership: the sequence is cut into 2N
 // half-chunks of h = c/2 rows and rank n owns half-chunks n and 2N-1-n, stored in that

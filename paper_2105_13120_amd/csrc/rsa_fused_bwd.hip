@@ -39,8 +39,9 @@ struct BwdArgs {
   // dQ of the dQ kernel with a split key walk
   float *part;
   int64_t L, c, Lq;
+  int64_t qs[3], ks[3], os[3];  // element strides (batch, head, row) of Q, dQ; K, V, dK, dV; O, dO
   RowMap map;  // local query row -> global token index
-  int N, tiles_per_head;
+  int N, Z, tiles_per_head;
   float cl2, scale, inv_scale;  // scale log2(e), scale, 1 / scale
 };
 
@@ -48,14 +49,16 @@ struct BwdArgs {
 // nD_i = -sum_a dO_ia O_ia and nL_i = -LSE_i / scale: 8 lanes per row, 8 elements of every 64 each.
 __global__ void __launch_bounds__(256) bwd_preprocess_kernel(const uint16_t *dO, const uint16_t *O,
                                                              const float *LSE, float *nD, float *nL,
-                                                             int64_t rows, int A, float inv_scale) {
+                                                             int64_t rows, int A, float inv_scale,
+                                                             OutLayout lay) {
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t row = gid >> 3;
   const int sub = (int)(gid & 7);
   float acc = 0.f;
   if (row < rows) {
+    const int64_t base = lay.row_off(row);
     for (int a0 = 0; a0 < A; a0 += 64) {
-      const int64_t off = row * A + a0 + sub * 8;
+      const int64_t off = base + a0 + sub * 8;
       const u32x4 x = *reinterpret_cast<const u32x4 *>(dO + off);
       const u32x4 y = *reinterpret_cast<const u32x4 *>(O + off);
 #pragma unroll
@@ -106,12 +109,14 @@ __global__ void __launch_bounds__(256, AH == 2 ? 1 : 2) fused_bwd_dkdv_kernel(Bw
   const int64_t key0 = (wg % a.tiles_per_head) * BK;  // first key of the work-group
   const int64_t wkey0 = key0 + wave * KW;             // first key of this wave
 
-  const uint16_t *Qh = a.Q + head * a.Lq * A;
-  const uint16_t *dOh = a.dO + head * a.Lq * A;
-  const uint16_t *Kh = a.K + head * a.L * A;
-  const uint16_t *Vh = a.V + head * a.L * A;
+  const int64_t kv_off = head_offset(head, a.Z, a.ks);
+  const uint16_t *Qh = a.Q + head_offset(head, a.Z, a.qs);
+  const uint16_t *dOh = a.dO + head_offset(head, a.Z, a.os);
+  const uint16_t *Kh = a.K + kv_off;
+  const uint16_t *Vh = a.V + kv_off;
   const float *nLh = a.nL + head * a.Lq;
   const float *nDh = a.nD + head * a.Lq;
+  const int64_t q_ld = a.qs[2], kv_ld = a.ks[2], o_ld = a.os[2];
 
   // K and V rows of this wave as B operands:
   // lane (col, half) holds row key = wkey0 + col, elements dk*16 + half*8 .. +8.
@@ -121,8 +126,8 @@ __global__ void __launch_bounds__(256, AH == 2 ? 1 : 2) fused_bwd_dkdv_kernel(Bw
     if (key >= a.L) key = a.L - 1;  // ragged tail: clamped here, not stored below
 #pragma unroll
     for (int dk = 0; dk < 4 * AH; ++dk) {
-      kreg[dk] = *reinterpret_cast<const bf16x8 *>(Kh + key * A + dk * 16 + half * 8);
-      vreg[dk] = *reinterpret_cast<const bf16x8 *>(Vh + key * A + dk * 16 + half * 8);
+      kreg[dk] = *reinterpret_cast<const bf16x8 *>(Kh + key * kv_ld + dk * 16 + half * 8);
+      vreg[dk] = *reinterpret_cast<const bf16x8 *>(Vh + key * kv_ld + dk * 16 + half * 8);
     }
   }
 
@@ -160,7 +165,7 @@ __global__ void __launch_bounds__(256, AH == 2 ? 1 : 2) fused_bwd_dkdv_kernel(Bw
   const int i_end = i_begin + per_split < nst ? i_begin + per_split : nst;
   auto advance = [&](int i) { ++i; while (i < i_end && !visible(i)) ++i; return i; };
 
-  const TileDMA dma(wave, lane);
+  const TileDMA dma_q(wave, lane, (int)q_ld), dma_o(wave, lane, (int)o_ld);
   auto load_stage = [&](int i, Stage &sn) __attribute__((always_inline)) {
     const int st = st_of(i);
 #pragma unroll
@@ -170,13 +175,8 @@ __global__ void __launch_bounds__(256, AH == 2 ? 1 : 2) fused_bwd_dkdv_kernel(Bw
       const int64_t r0 = (int64_t)qt * 64;
 #pragma unroll
       for (int ah = 0; ah < AH; ++ah) {
-        if constexpr (AH == 1) {
-          dma.load(Qh + r0 * 64, sn.Qt[u][0]);
-          dma.load(dOh + r0 * 64, sn.dOs[u][0]);
-        } else {
-          dma.load(Qh + r0 * A + ah * 64, sn.Qt[u][ah], A);
-          dma.load(dOh + r0 * A + ah * 64, sn.dOs[u][ah], A);
-        }
+        dma_q.load(Qh + r0 * q_ld + ah * 64, sn.Qt[u][ah]);
+        dma_o.load(dOh + r0 * o_ld + ah * 64, sn.dOs[u][ah]);
       }
       // the 64 row terms of the tile, one dword per lane: waves 0/1 fetch -LSE / scale, 2/3 fetch -D
       if ((wave & 1) == (u & 1)) {
@@ -338,8 +338,8 @@ __global__ void __launch_bounds__(256, AH == 2 ? 1 : 2) fused_bwd_dkdv_kernel(Bw
   for (int ah = 0; ah < AH; ++ah) {  // one half of the head at a time through the wave's tile
     stage_block_T(ot, 0, dv[2 * ah], dv[2 * ah + 1], 1.0f, lane);
     stage_block_T(ot, 32, dk_[2 * ah], dk_[2 * ah + 1], a.scale, lane);
-    flush_rows<32>(ot, 0, a.dV + (head * a.L + wkey0) * A + ah * 64, a.L - wkey0, lane, A);
-    flush_rows<32>(ot, 32, a.dK + (head * a.L + wkey0) * A + ah * 64, a.L - wkey0, lane, A);
+    flush_rows<32>(ot, 0, a.dV + kv_off + wkey0 * kv_ld + ah * 64, a.L - wkey0, lane, (int)kv_ld);
+    flush_rows<32>(ot, 32, a.dK + kv_off + wkey0 * kv_ld + ah * 64, a.L - wkey0, lane, (int)kv_ld);
   }
 }
 
@@ -374,10 +374,13 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   const int tpc = (int)(a.c / kTileKeys);
   const int tpr = a.map.zigzag ? tpc / 2 : tpc;
 
-  const uint16_t *Qh = a.Q + head * a.Lq * A;
-  const uint16_t *dOh = a.dO + head * a.Lq * A;
-  const uint16_t *Kh = a.K + head * a.L * A;
-  const uint16_t *Vh = a.V + head * a.L * A;
+  const int64_t kv_off = head_offset(head, a.Z, a.ks), q_off = head_offset(head, a.Z, a.qs);
+  const int64_t o_off = head_offset(head, a.Z, a.os);
+  const uint16_t *Qh = a.Q + q_off;
+  const uint16_t *dOh = a.dO + o_off;
+  const uint16_t *Kh = a.K + kv_off;
+  const uint16_t *Vh = a.V + kv_off;
+  const int64_t q_ld = a.qs[2], kv_ld = a.ks[2], o_ld = a.os[2];
 
   // Q and dO as B operands; -LSE / scale and -D of the lane's row, broadcast
   // over an accumulator, are what S'^T and dP'^T start from.
@@ -393,8 +396,8 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
     qtok[qb] = a.map(blk < a.Lq ? blk : a.Lq - 32) + col;
 #pragma unroll
     for (int dk = 0; dk < 4 * AH; ++dk) {
-      qreg[qb][dk] = *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * A + dk * 16 + half * 8);
-      greg[qb][dk] = *reinterpret_cast<const bf16x8 *>(dOh + qrow[qb] * A + dk * 16 + half * 8);
+      qreg[qb][dk] = *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * q_ld + dk * 16 + half * 8);
+      greg[qb][dk] = *reinterpret_cast<const bf16x8 *>(dOh + qrow[qb] * o_ld + dk * 16 + half * 8);
     }
     float l2, dd;
     if (PRE) {
@@ -403,7 +406,7 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
 #pragma unroll
       for (int dk = 0; dk < 4 * AH; ++dk) {
         const u32x4 x = __builtin_bit_cast(u32x4, greg[qb][dk]);
-        const u32x4 y = *reinterpret_cast<const u32x4 *>(a.O + (head * a.Lq + qrow[qb]) * A + dk * 16 + half * 8);
+        const u32x4 y = *reinterpret_cast<const u32x4 *>(a.O + o_off + qrow[qb] * o_ld + dk * 16 + half * 8);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           acc = fmaf(bf16_to_f32(x[e] & 0xffffu), bf16_to_f32(y[e] & 0xffffu), acc);
@@ -462,20 +465,15 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
       ks = spc;
     }
   };
-  const TileDMA dma(wave, lane);
+  const TileDMA dma(wave, lane, (int)kv_ld);
   auto load_stage = [&](int64_t k0, auto &Kn, auto &Vn) __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < NK; ++u) {
       if (u < nk) {
 #pragma unroll
         for (int ah = 0; ah < AH; ++ah) {
-          if constexpr (AH == 1) {
-            dma.load(Kh + (k0 + u * kTileKeys) * 64, Kn[u][0]);
-            dma.load(Vh + (k0 + u * kTileKeys) * 64, Vn[u][0]);
-          } else {
-            dma.load(Kh + (k0 + u * kTileKeys) * A + ah * 64, Kn[u][ah], A);
-            dma.load(Vh + (k0 + u * kTileKeys) * A + ah * 64, Vn[u][ah], A);
-          }
+          dma.load(Kh + (k0 + u * kTileKeys) * kv_ld + ah * 64, Kn[u][ah]);
+          dma.load(Vh + (k0 + u * kTileKeys) * kv_ld + ah * 64, Vn[u][ah]);
         }
       }
     }
@@ -585,19 +583,21 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   for (int ah = 0; ah < AH; ++ah) {  // one half of the head at a time through the wave's tile
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) stage_block_T(ot, qb * 32, dq[2 * ah][qb], dq[2 * ah + 1][qb], a.scale, lane);
-    flush_rows<R>(ot, 0, a.dQ + (head * a.Lq + wr0) * A + ah * 64, a.Lq - wr0, lane, A);
+    flush_rows<R>(ot, 0, a.dQ + q_off + wr0 * q_ld + ah * 64, a.Lq - wr0, lane, (int)q_ld);
   }
 }
 
 // out (bf16) = sum over the splits of part[s][i], in a fixed order; n4 groups of four per split
+// (the partial sums are dense (head, row, A); `lay` says where a row of the output tensor lives)
 __global__ void __launch_bounds__(256) qsplit_reduce_kernel(const float *part, uint16_t *out, int64_t n4,
-                                                            int splits) {
+                                                            int splits, int A, OutLayout lay) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n4) return;
   f32x4 s = reinterpret_cast<const f32x4 *>(part)[i];
   for (int k = 1; k < splits; ++k) s += reinterpret_cast<const f32x4 *>(part)[(int64_t)k * n4 + i];
   const u32x2 w = {pack_bf16(s[0], s[1]), pack_bf16(s[2], s[3])};
-  reinterpret_cast<u32x2 *>(out)[i] = w;
+  const int64_t e = i * 4;
+  *reinterpret_cast<u32x2 *>(out + lay.row_off(e / A) + e % A) = w;
 }
 
 static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const void *K,
@@ -611,7 +611,8 @@ static BwdArgs make_bwd_args(const Dims &d, const void *dO, const void *Q, const
   a.part = nullptr;
   a.O = nullptr; a.LSE = nullptr; a.nL_out = nullptr; a.nD_out = nullptr;
   a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.map = make_row_map(d);
-  a.N = d.N; a.cl2 = d.scale * kLog2e; a.scale = d.scale; a.inv_scale = 1.0f / d.scale;
+  a.N = d.N; a.Z = d.Z; a.cl2 = d.scale * kLog2e; a.scale = d.scale; a.inv_scale = 1.0f / d.scale;
+  for (int k = 0; k < 3; ++k) { a.qs[k] = d.qs[k]; a.ks[k] = d.ks[k]; a.os[k] = d.os[k]; }
   a.tiles_per_head = 0;
   return a;
 }
@@ -621,7 +622,8 @@ hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, co
   const int64_t rows = (int64_t)d.B * d.Z * d.Lq;
   dim3 grid((unsigned)((rows * 8 + 255) / 256));
   hipLaunchKernelGGL(bwd_preprocess_kernel, grid, dim3(256), 0, st, (const uint16_t *)dO,
-                     (const uint16_t *)O, LSE, nD, nL, rows, d.A, 1.0f / d.scale);
+                     (const uint16_t *)O, LSE, nD, nL, rows, d.A, 1.0f / d.scale,
+                     make_out_layout(d.os, d.Lq, d.Z));
   return hipGetLastError();
 }
 
@@ -655,9 +657,10 @@ hipError_t fused_bwd_dkdv(const Dims &d, const void *dO, const void *Q, const vo
   if (e != hipSuccess || splits == 1) return e;
   const int64_t n4 = (int64_t)d.B * d.Z * d.L * (d.A / 4);
   const dim3 rg((unsigned)((n4 + 255) / 256));
-  hipLaunchKernelGGL(qsplit_reduce_kernel, rg, dim3(256), 0, st, part, (uint16_t *)dV, n4, splits);
+  const OutLayout lay = make_out_layout(d.ks, d.L, d.Z);
+  hipLaunchKernelGGL(qsplit_reduce_kernel, rg, dim3(256), 0, st, part, (uint16_t *)dV, n4, splits, d.A, lay);
   hipLaunchKernelGGL(qsplit_reduce_kernel, rg, dim3(256), 0, st, part + (int64_t)splits * n4 * 4,
-                     (uint16_t *)dK, n4, splits);
+                     (uint16_t *)dK, n4, splits, d.A, lay);
   return hipGetLastError();
 }
 
@@ -679,7 +682,7 @@ static void launch_dq(const Dims &d, const BwdArgs &a, dim3 grid, hipStream_t st
 static hipError_t dq_reduce(const Dims &d, const float *part, void *dQ, int splits, hipStream_t st) {
   const int64_t n4 = (int64_t)d.B * d.Z * d.Lq * (d.A / 4);
   hipLaunchKernelGGL(qsplit_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, part,
-                     (uint16_t *)dQ, n4, splits);
+                     (uint16_t *)dQ, n4, splits, d.A, make_out_layout(d.qs, d.Lq, d.Z));
   return hipGetLastError();
 }
 

@@ -28,8 +28,9 @@ struct FwdArgs {
   uint16_t *O;
   float *LSE;
   int64_t L, c, Lq;
+  int64_t qs[3], ks[3], os[3];  // element strides (batch, head, row) of Q; K and V; O
   RowMap map;            // local query row -> global token index
-  int N, tiles_per_head;
+  int N, Z, tiles_per_head;
   float cl2;             // scale * log2(e)
   // split key walk (gridDim.y > 1): per split, head and row the unnormalised fp32 O and the pair
   // (stale max * cl2, row sum) it is relative to
@@ -70,9 +71,11 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
   const int tpc = (int)(a.c / kTileKeys);
   const int tpr = a.map.zigzag ? tpc / 2 : tpc;
 
-  const uint16_t *Qh = a.Q + head * a.Lq * A;
-  const uint16_t *Kh = a.K + head * a.L * A;
-  const uint16_t *Vh = a.V + head * a.L * A;
+  const int64_t kv_off = head_offset(head, a.Z, a.ks);
+  const uint16_t *Qh = a.Q + head_offset(head, a.Z, a.qs);
+  const uint16_t *Kh = a.K + kv_off;
+  const uint16_t *Vh = a.V + kv_off;
+  const int64_t q_ld = a.qs[2], kv_ld = a.ks[2], o_ld = a.os[2];
 
   // Q^T operand: lane (col, half) holds Q[row][dk*16 + half*8 .. +8]
   bf16x8 qreg[QB][4 * AH];
@@ -86,7 +89,7 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
     qtok[qb] = a.map(blk < a.Lq ? blk : a.Lq - 32) + col;
 #pragma unroll
     for (int dk = 0; dk < 4 * AH; ++dk)
-      qreg[qb][dk] = *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * A + dk * 16 + half * 8);
+      qreg[qb][dk] = *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * q_ld + dk * 16 + half * 8);
   }
   // first and last token of this wave's rows (R <= 64 rows inside one tile: a run of tokens)
   const int64_t wrow = row0 + wave * R < a.Lq ? row0 + wave * R : a.Lq - R;
@@ -130,20 +133,15 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
       ks = spc;  // later stages of this chunk start even further right
     }
   };
-  const TileDMA dma(wave, lane);
+  const TileDMA dma(wave, lane, (int)kv_ld);
   auto load_stage = [&](int64_t k0, auto &Kn, auto &Vn) __attribute__((always_inline)) {
 #pragma unroll
     for (int u = 0; u < NK; ++u) {
       if (u < nk) {
 #pragma unroll
         for (int ah = 0; ah < AH; ++ah) {
-          if constexpr (AH == 1) {
-            dma.load(Kh + (k0 + u * kTileKeys) * 64, Kn[u][0]);
-            dma.load(Vh + (k0 + u * kTileKeys) * 64, Vn[u][0]);
-          } else {
-            dma.load(Kh + (k0 + u * kTileKeys) * A + ah * 64, Kn[u][ah], A);
-            dma.load(Vh + (k0 + u * kTileKeys) * A + ah * 64, Vn[u][ah], A);
-          }
+          dma.load(Kh + (k0 + u * kTileKeys) * kv_ld + ah * 64, Kn[u][ah]);
+          dma.load(Vh + (k0 + u * kTileKeys) * kv_ld + ah * 64, Vn[u][ah]);
         }
       }
     }
@@ -311,7 +309,7 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
   for (int ah = 0; ah < AH; ++ah) {  // one half of the head at a time through the wave's tile
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) stage_block_T(ot, qb * 32, o[2 * ah][qb], o[2 * ah + 1][qb], inv[qb], lane);
-    flush_rows<R>(ot, 0, a.O + (head * a.Lq + wr0) * A + ah * 64, a.Lq - wr0, lane, A);
+    flush_rows<R>(ot, 0, a.O + head_offset(head, a.Z, a.os) + wr0 * o_ld + ah * 64, a.Lq - wr0, lane, (int)o_ld);
   }
 }
 
@@ -320,7 +318,7 @@ __global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
 // A split that saw no key of the row has mc = -inf and is left out.  A/4 lanes x 4 columns per row.
 __global__ void __launch_bounds__(256) fwd_combine_kernel(const float *part_o, const float *part_ml,
                                                           uint16_t *O, float *LSE, int64_t rows, int splits,
-                                                          int A) {
+                                                          int A, OutLayout lay) {
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int lanes = A >> 2;
   const int64_t row = gid / lanes;
@@ -341,7 +339,7 @@ __global__ void __launch_bounds__(256) fwd_combine_kernel(const float *part_o, c
   }
   const float inv = 1.0f / lsum;
   const u32x2 w = {pack_bf16(acc[0] * inv, acc[1] * inv), pack_bf16(acc[2] * inv, acc[3] * inv)};
-  *reinterpret_cast<u32x2 *>(O + row * A + sub * 4) = w;
+  *reinterpret_cast<u32x2 *>(O + lay.row_off(row) + sub * 4) = w;
   if (sub == 0) LSE[row] = (M + __builtin_amdgcn_logf(lsum)) * kLn2;
 }
 
@@ -402,7 +400,8 @@ hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void
   a.Q = (const uint16_t *)Q; a.K = (const uint16_t *)K; a.V = (const uint16_t *)V;
   a.O = (uint16_t *)O; a.LSE = LSE;
   a.L = d.L; a.c = d.c; a.Lq = d.Lq; a.map = make_row_map(d);
-  a.N = d.N;
+  a.N = d.N; a.Z = d.Z;
+  for (int k = 0; k < 3; ++k) { a.qs[k] = d.qs[k]; a.ks[k] = d.ks[k]; a.os[k] = d.os[k]; }
   a.cl2 = d.scale * kLog2e;
   const int64_t heads = (int64_t)d.B * d.Z;
   bool big;
@@ -417,8 +416,9 @@ hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void
                  : big      ? launch_fwd<64, 1, 2>(d, a, heads, splits, st)
                             : launch_fwd<32, 1, 2>(d, a, heads, splits, st);
   if (e != hipSuccess || splits == 1) return e;
+  const OutLayout lay = make_out_layout(d.os, d.Lq, d.Z);
   hipLaunchKernelGGL(fwd_combine_kernel, dim3((unsigned)((rows * (d.A / 4) + 255) / 256)), dim3(256), 0, st,
-                     a.part_o, a.part_ml, (uint16_t *)O, LSE, rows, splits, d.A);
+                     a.part_o, a.part_ml, (uint16_t *)O, LSE, rows, splits, d.A, lay);
   return hipGetLastError();
 }
 

@@ -81,7 +81,7 @@ struct TileLanes {
 // wave w moves the 16-byte pieces (PER w + j) * 64 + lane, j < PER = 8 / WAVES; the piece at LDS position
 // p = 8 row + pc holds logical chunk pc ^ rot(row) of that row, so the tile lands in the
 // swizzled layout above.  `g` points at element [0][0] of the tile in global memory
-// (rows 64 elements apart, or `ld` elements apart in the second form of load).
+// (rows `ld` elements apart).
 // Completion: wait_vmem(), then a barrier.
 // A wave's block of 32 output rows x 64 columns, held transposed in two accumulators
 // (acc[db]: rows = columns db*32 .. +32 of the output, column = output row), is put into rows
@@ -118,25 +118,20 @@ __device__ __forceinline__ void flush_rows(const unsigned char *tile, int first,
 template <int WAVES>
 struct TileDMAT {
   static constexpr int PER = 8 / WAVES;
-  int g_off[PER], l_off[PER], g_row[PER], g_col[PER];
-  __device__ __forceinline__ TileDMAT(int wave, int lane) {
+  int g_off[PER], l_off[PER];
+  // ld: elements between consecutive rows of the tile in global memory (at most 2^24)
+  __device__ __forceinline__ TileDMAT(int wave, int lane, int ld) {
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
       const int p = (wave * PER + j) * 64 + lane;
       const int row = p >> 3, cc = (p & 7) ^ swz_rot(row);
-      g_row[j] = row;
-      g_col[j] = cc * 8;
-      g_off[j] = row * 64 + cc * 8;
+      g_off[j] = row * ld + cc * 8;
       l_off[j] = (wave * PER + j) * 1024;
     }
   }
   __device__ __forceinline__ void load(const uint16_t *g, unsigned char *tile) const {
 #pragma unroll
     for (int j = 0; j < PER; ++j) lds_dma16(g + g_off[j], tile + l_off[j]);
-  }
-  __device__ __forceinline__ void load(const uint16_t *g, unsigned char *tile, int64_t ld) const {
-#pragma unroll
-    for (int j = 0; j < PER; ++j) lds_dma16(g + g_row[j] * ld + g_col[j], tile + l_off[j]);
   }
 };
 using TileDMA = TileDMAT<4>;

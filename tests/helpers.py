@@ -43,7 +43,9 @@ from paper_2105_13120_amd import inputs, rsa
 #  vanishes; on the first rows of a causal mask (one or two keys, O_i of the size of a value vector)
 #  it is the largest error in the tensor, so the dQ bound is widened by four standard deviations of
 #  that term, computed from the oracle's own O and P (dq_extra below; the ideal pipeline reaches
-#  0.8 to 0.9 of the widened bound on such rows).
+#  0.8 to 0.9 of the widened bound on such rows).  The same delta_i reaches dK_j = s sum_i dS_ij Q_i
+#  of the keys those first rows see, i.e. the first keys of the sequence (dk_extra, same four
+#  standard deviations, causal mask only).
 F32_ATOL = 1e-4
 BF16_REL_RMS = 2e-2
 BF16_RTOL = 2.0 ** -7
@@ -85,6 +87,27 @@ def dq_extra(Q, K, V, dO, O_ref, q0, causal, scale=None):
     PK, _ = oracle.forward(Q, K, K, q0=q0, causal=causal, scale=scale)   # attention-weighted mean key
     sigma = 2.0 ** -9 / np.sqrt(3.0) * np.sqrt(np.sum(np.square(dO * O_ref), axis=-1, keepdims=True))
     return 4.0 * sigma * s * np.abs(PK)
+
+
+def dk_extra(Q, K, V, dO, O_ref, q0, scale=None, first=256):
+    """The same rounding of the stored O inside D, seen from the keys (causal mask only): row i's
+    error delta_i moves dK_j = s sum_i dS_ij Q_i by s delta_i P_ij Q_i for every key j <= i.  It
+    matters where rows see few keys, i.e. for the first tokens of the sequence, and lands on their
+    keys.  Returns 4 standard deviations, 4 s sqrt(sum_i sigma_i^2 P_ij^2 Q_ia^2) over the rows of
+    tokens below `first`, as (B, Z, first, A) for keys [0, first) (zeros if no such row)."""
+    s = 1.0 / np.sqrt(Q.shape[-1]) if scale is None else scale
+    B, Z, n, A = Q.shape
+    m = int(min(n, max(0, first - q0)))
+    out = np.zeros((B, Z, first, A))
+    if m == 0:
+        return out
+    Qs, dOs, Os = Q[:, :, :m], dO[:, :, :m], O_ref[:, :, :m]
+    Kf, Vf = K[:, :, :first], V[:, :, :first]       # tokens below `first` see no later key
+    P = oracle.forward(np.ascontiguousarray(Qs), np.ascontiguousarray(Kf), np.ascontiguousarray(Vf),
+                       q0=q0, causal=True, scale=scale, want_scores=True)[3]        # (B, Z, m, first')
+    var = (2.0 ** -9) ** 2 / 3.0 * np.sum(np.square(dOs * Os), axis=-1)             # sigma_i^2, (B, Z, m)
+    out[:, :, :Kf.shape[2]] = 4.0 * s * np.sqrt(np.einsum("bzi,bzij,bzia->bzja", var, P ** 2, Qs ** 2))
+    return out
 
 
 class Err(float):
@@ -183,6 +206,7 @@ def oracle_on_segments(cfg, Qh, Kh, Vh, dOh=None):
     dQ = np.empty_like(Qh) if dOh is not None else None
     extra = np.empty_like(Qh) if dOh is not None else None
     dK = dV = None
+    dk_var = None     # variance-like sum of the runs' dk_extra terms (independent rows)
     sc = att_scale(cfg)
     for r0, t0, n in cfg.segments():
         Qs = np.ascontiguousarray(Qh[:, :, r0:r0 + n])
@@ -194,7 +218,15 @@ def oracle_on_segments(cfg, Qh, Kh, Vh, dOh=None):
             dK = g[1] if dK is None else dK + g[1]
             dV = g[2] if dV is None else dV + g[2]
             extra[:, :, r0:r0 + n] = dq_extra(Qs, Kh, Vh, dOs, O[:, :, r0:r0 + n], t0, cfg.causal, scale=sc)
-    return O, LSE, dQ, dK, dV, extra
+            if cfg.causal:
+                x_ = dk_extra(Qs, Kh, Vh, dOs, O[:, :, r0:r0 + n], t0, scale=sc) ** 2
+                dk_var = x_ if dk_var is None else dk_var + x_
+    dk_x = None
+    if dk_var is not None:
+        dk_x = np.zeros_like(Kh)
+        w = min(dk_var.shape[2], Kh.shape[2])
+        dk_x[:, :, :w] = np.sqrt(dk_var[:, :, :w])
+    return O, LSE, dQ, dK, dV, extra, dk_x
 
 
 def compare_heads(cfg, x, out, heads, backward=True, ideal=True, ideal_heads=16, mode=rsa.MODE_FUSED):
@@ -204,13 +236,14 @@ def compare_heads(cfg, x, out, heads, backward=True, ideal=True, ideal_heads=16,
     to a running maximum for the fused kernels, the bf16-strip pipeline for the two-pass layout."""
     Qh, Kh, Vh = (heads_view(x[k], heads) for k in ("Q", "K", "V"))
     dOh = heads_view(x["dO"], heads) if backward else None
-    O_ref, LSE_ref, dQ_ref, dK_ref, dV_ref, dq_x = oracle_on_segments(cfg, Qh, Kh, Vh, dOh)
+    O_ref, LSE_ref, dQ_ref, dK_ref, dV_ref, dq_x, dk_x = oracle_on_segments(cfg, Qh, Kh, Vh, dOh)
+    extras = dict(dQ=dq_x, dK=dk_x)
     got = {k: heads_view(download(out[k]), heads) for k in (("O", "dQ", "dK", "dV") if backward else ("O",))}
     refs = dict(O=O_ref, dQ=dQ_ref, dK=dK_ref, dV=dV_ref)
     errs = {}
     for name in got:
         errs[name] = check(name, got[name], refs[name], cfg.dtype, strip=mode == rsa.MODE_STAGED,
-                           extra=dq_x if name == "dQ" and cfg.dtype == "bf16" else None)
+                           extra=extras.get(name) if cfg.dtype == "bf16" else None)
     lse = download(out["LSE"]).reshape(-1, cfg.Lq)[heads][None]
     err = float(np.abs(lse - LSE_ref).max())
     assert err <= LSE_ATOL, f"LSE: max abs err {err:.3e}"
@@ -229,7 +262,7 @@ def compare_heads(cfg, x, out, heads, backward=True, ideal=True, ideal_heads=16,
             model.update(dQ=m[2], dK=m[3], dV=m[4])
         for name in got:
             errs[name] = check(name, cut(got[name]), cut(refs[name]), cfg.dtype, ideal=model[name],
-                               extra=cut(dq_x) if name == "dQ" else None, strip=mode == rsa.MODE_STAGED)
+                               extra=cut(extras.get(name)), strip=mode == rsa.MODE_STAGED)
     return errs
 
 

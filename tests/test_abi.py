@@ -59,6 +59,16 @@ def test_validation_happens_before_any_launch():
     assert fwd_status(desc(flags=rsa.MODE_STAGED | rsa.OWN_ZIGZAG)) == -3   # zig-zag: fused mode only
     assert fwd_status(desc(L=256, N=4, flags=rsa.OWN_ZIGZAG)) == -3          # half-chunk of 32 rows
     assert rsa.workspace_bytes(desc(L=512, N=4, flags=rsa.OWN_ZIGZAG), True) > 0
+    # strides: all zero = dense; otherwise positive, row stride >= A, multiples of 8 elements
+    dense = dict(q_stride=(2 * 256 * 64, 256 * 64, 64), kv_stride=(2 * 256 * 64, 256 * 64, 64))
+    assert rsa.workspace_bytes(desc(**dense), True) == rsa.workspace_bytes(desc(), True)
+    inter = dict(o_stride=(256 * 2 * 64, 64, 2 * 64))                   # heads interleaved (B, rows, Z, A)
+    assert rsa.workspace_bytes(desc(**inter), True) > 0
+    assert fwd_status(desc(kv_stride=(2 * 256 * 64, 256 * 64, 32))) == -2           # rows overlap
+    assert fwd_status(desc(kv_stride=(2 * 256 * 64, 0, 64))) == -2
+    assert fwd_status(desc(kv_stride=(2 * 256 * 68, 256 * 68, 68))) == -3           # not a multiple of 16 bytes
+    assert fwd_status(desc(kv_stride=(1 << 40, 1 << 32, 1 << 25))) == -3            # row stride beyond 2^24
+    assert fwd_status(desc(flags=rsa.MODE_STAGED, **inter)) == -3                   # the two-pass kernels are dense only
     assert fwd_status(desc(), ptr=0) == -1
     assert fwd_status(desc(), ptr=0x1008) == -3              # misaligned
     staged = desc(flags=rsa.MODE_STAGED)

@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 import oracle
-from helpers import (BF16_REL_RMS, LSE_ATOL, check, compare_heads, describe, download, dq_extra,
+from helpers import (BF16_REL_RMS, LSE_ATOL, check, compare_heads, describe, download, dk_extra, dq_extra,
                      gpu_forward_backward, heads_view)
 from paper_2105_13120_amd import inputs, rsa
 
@@ -55,6 +55,7 @@ def sampled_check(cfg, x, out, head, row_blocks, cols):
     # one oracle call per run of consecutive tokens (one run unless ownership is zig-zag)
     dQ_ref = np.empty_like(Qh)
     dq_x = np.zeros_like(Qh)
+    dk_x = np.zeros((1, 1, len(cols), cfg.A))
     dK_ref = dV_ref = None
     for s0, t0, n in cfg.segments():
         Qs, dOs = (np.ascontiguousarray(a[:, :, s0:s0 + n]) for a in (Qh, dOh))
@@ -69,10 +70,13 @@ def sampled_check(cfg, x, out, head, row_blocks, cols):
             if m > 0:
                 O_ref = oracle.forward(Qs[:, :, :m], Kh, Vh, q0=t0, causal=True)[0]
                 dq_x[:, :, s0:s0 + m] = dq_extra(Qs[:, :, :m], Kh, Vh, dOs[:, :, :m], O_ref, t0, True)
+                dk_first = dk_extra(Qs[:, :, :m], Kh, Vh, dOs[:, :, :m], O_ref, t0)     # keys 0..255
+                early = np.asarray(cols) < dk_first.shape[2]
+                dk_x[:, :, early] = np.sqrt(dk_x[:, :, early] ** 2 + dk_first[:, :, np.asarray(cols)[early]] ** 2)
     print("dQ", check("dQ", dQ[None, None], dQ_ref, cfg.dtype, extra=dq_x).describe())
     dK = download(out["dK"]).reshape(-1, cfg.L, cfg.A)[head][cols]
     dV = download(out["dV"]).reshape(-1, cfg.L, cfg.A)[head][cols]
-    print("dK", check("dK", dK[None, None], dK_ref, cfg.dtype).describe())
+    print("dK", check("dK", dK[None, None], dK_ref, cfg.dtype, extra=dk_x).describe())
     print("dV", check("dV", dV[None, None], dV_ref, cfg.dtype).describe())
     for r0, nr in row_blocks:
         s0, t0, n = next(s for s in cfg.segments() if s[0] <= r0 and r0 + nr <= s[0] + s[2])

@@ -65,6 +65,48 @@ def test_explicit_softmax_scale(A, att_scale, causal, rb, re):
     assert not torch.equal(out["O"], ref["O"])
 
 
+@pytest.mark.parametrize("A", [64, 128])
+@pytest.mark.parametrize("causal,rb,re,zigzag", [(False, 0, -1, False), (True, 0, -1, True), (True, 3, 4, False)])
+def test_strided_layouts(A, causal, rb, re, zigzag):
+    """Q, K, V as slices of one packed projection output (B, rows, 3, Z, A), O and dO with the heads
+    interleaved (B, rows, Z, A) -- the layouts the linear maps either side of RSA produce and consume
+    without a transpose -- and dQ, dK, dV written back into a packed buffer.  The strides travel in
+    the descriptor; the results are those of the dense layout bit for bit."""
+    B, Z, L, N = 2, 3, 2048, 4
+    cfg = cfg_of(B, Z, L, N, causal, rb=rb, re=re, seed=83, zigzag=zigzag, A=A)
+    x = inputs.make_inputs(cfg)
+    dense = {k: upload(x[k], "bf16") for k in ("Q", "K", "V", "dO")}
+    Lq = cfg.Lq
+    # packed (B, L, 3, Z, A): Q lives in slot 0 of the first Lq rows (a rank share has fewer query rows)
+    packed = torch.zeros((B, L, 3, Z, A), dtype=torch.bfloat16, device="cuda")
+    view = lambda t, i, rows: t[:, :rows, i].permute(0, 2, 1, 3)          # (B, Z, rows, A), not contiguous
+    Q, K, V = view(packed, 0, Lq), view(packed, 1, L), view(packed, 2, L)
+    Q.copy_(dense["Q"]); K.copy_(dense["K"]); V.copy_(dense["V"])
+    inter = lambda: torch.full((B, Lq, Z, A), float("nan"), dtype=torch.bfloat16, device="cuda").permute(0, 2, 1, 3)
+    O, dO = inter(), inter()
+    dO.copy_(dense["dO"])
+    grads = torch.full_like(packed, float("nan"))
+    dQ, dK, dV = view(grads, 0, Lq), view(grads, 1, L), view(grads, 2, L)
+    assert not Q.is_contiguous() and not O.is_contiguous()
+    kw = dict(causal=causal, rank_begin=cfg.ranks[0], rank_end=cfg.ranks[1], zigzag=zigzag)
+    desc = rsa.make_desc(K, N, Q=Q, O=O, **kw)
+    LSE = torch.empty((B, Z, Lq), dtype=torch.float32, device="cuda")
+    rsa.forward(desc, Q, K, V, O=O, LSE=LSE)
+    rsa.backward(desc, dO, Q, K, V, O, LSE, dQ=dQ, dK=dK, dV=dV)
+    # the dense layout through the same kernels
+    ddesc = rsa.make_desc(dense["K"], N, **kw)
+    O2, LSE2 = rsa.forward(ddesc, dense["Q"], dense["K"], dense["V"])
+    g2 = rsa.backward(ddesc, dense["dO"], dense["Q"], dense["K"], dense["V"], O2, LSE2)
+    torch.cuda.synchronize()
+    for name, a, b in (("O", O, O2), ("LSE", LSE, LSE2), ("dQ", dQ, g2[0]), ("dK", dK, g2[1]), ("dV", dV, g2[2])):
+        assert torch.equal(a.contiguous(), b), name
+    # nothing outside the views was written: the unused slots of the packed gradient stay NaN
+    if Lq < L:
+        assert torch.isnan(grads[:, Lq:, 0]).all()
+    out = dict(O=O.contiguous(), LSE=LSE, dQ=dQ.contiguous(), dK=dK.contiguous(), dV=dV.contiguous())
+    compare_heads(cfg, x, out, list(range(B * Z)))
+
+
 def test_kernel_error_matches_the_model_of_its_roundings():
     """The ideal bf16 pipeline (tests/bf16_model.py) makes exactly the roundings the fused kernels
     make, so on the same inputs the two errors agree as distributions: RMS within 10 % and the
