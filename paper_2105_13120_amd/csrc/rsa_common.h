@@ -126,7 +126,7 @@ struct Dims {
   int zigzag;  // 1: rank n owns half-chunks n and 2N-1-n (RSA_OWN_ZIGZAG)
   int64_t L, c, Lq;
   float scale;
-  int deterministic;  // RSA_DETERMINISTIC: dQ from its own kernel, no atomics
+  int deterministic;  // RSA_DETERMINISTIC was asked for (every path is deterministic already)
   // element strides of (batch, head, row) for Q/dQ, K/V/dK/dV and O/dO; strided = any not dense
   int64_t qs[3], ks[3], os[3];
   int strided;
