@@ -29,8 +29,8 @@ def test_bert_large_all_heads():
     print(describe(compare_heads(cfg, x, out, list(range(cfg.B * cfg.Z)), ideal_heads=8)))
 
 
-def forward_all_rows(cfg, x, out, heads):
-    """O and LSE on every local row of the listed heads."""
+def forward_all_rows(cfg, x, out, heads, literal=False):
+    """O and LSE on every local row of the listed heads (literal: see sampled_check)."""
     Qh, Kh, Vh = (heads_view(x[k], heads) for k in ("Q", "K", "V"))
     O = heads_view(download(out["O"]), heads)
     LSE = download(out["LSE"]).reshape(-1, cfg.Lq)[heads][None]
@@ -41,10 +41,13 @@ def forward_all_rows(cfg, x, out, heads):
         err = np.abs(LSE[:, :, s0:s0 + n] - LSE_ref).max()
         assert err <= LSE_ATOL, f"LSE: {err:.3e}"
         print(f"heads {heads} rows {s0}..{s0 + n}: O {e.describe()}, LSE {err:.2e}")
+        assert not literal or e <= BF16_REL_RMS, f"O: {e:.3e}"
 
 
-def sampled_check(cfg, x, out, head, row_blocks, cols):
-    """One head of a long configuration: O/LSE/dQ on row blocks, dK/dV on key columns."""
+def sampled_check(cfg, x, out, head, row_blocks, cols, literal=False):
+    """One head of a long configuration: O/LSE/dQ on row blocks, dK/dV on key columns.
+    literal: also assert the stated bar as it reads, max abs err <= 2e-2 of the RMS, for dQ, dK, dV
+    (the long non-Bert workloads meet it: one head, no heavy tail)."""
     Kh, Vh = heads_view(x["K"], [head]), heads_view(x["V"], [head])
     Qh, dOh = heads_view(x["Q"], [head]), heads_view(x["dO"], [head])
     O, LSE, dQ = (download(out[k]) for k in ("O", "LSE", "dQ"))
@@ -73,11 +76,15 @@ def sampled_check(cfg, x, out, head, row_blocks, cols):
                 dk_first = dk_extra(Qs[:, :, :m], Kh, Vh, dOs[:, :, :m], O_ref, t0)     # keys 0..255
                 early = np.asarray(cols) < dk_first.shape[2]
                 dk_x[:, :, early] = np.sqrt(dk_x[:, :, early] ** 2 + dk_first[:, :, np.asarray(cols)[early]] ** 2)
-    print("dQ", check("dQ", dQ[None, None], dQ_ref, cfg.dtype, extra=dq_x).describe())
+    e = check("dQ", dQ[None, None], dQ_ref, cfg.dtype, extra=dq_x)
+    print("dQ", e.describe())
+    assert not literal or e <= BF16_REL_RMS, f"dQ: {e:.3e}"
     dK = download(out["dK"]).reshape(-1, cfg.L, cfg.A)[head][cols]
     dV = download(out["dV"]).reshape(-1, cfg.L, cfg.A)[head][cols]
-    print("dK", check("dK", dK[None, None], dK_ref, cfg.dtype, extra=dk_x).describe())
-    print("dV", check("dV", dV[None, None], dV_ref, cfg.dtype).describe())
+    for name, got, ref, ex in (("dK", dK, dK_ref, dk_x), ("dV", dV, dV_ref, None)):
+        e = check(name, got[None, None], ref, cfg.dtype, extra=ex)
+        print(name, e.describe())
+        assert not literal or e <= BF16_REL_RMS, f"{name}: {e:.3e}"
     for r0, nr in row_blocks:
         s0, t0, n = next(s for s in cfg.segments() if s[0] <= r0 and r0 + nr <= s[0] + s[2])
         O_ref, LSE_ref = oracle.forward(np.ascontiguousarray(Qh[:, :, r0:r0 + nr]), Kh, Vh,
@@ -108,9 +115,9 @@ def test_long_32k_sampled():
     check_sum_rules(cfg, x, out)
     rng = np.random.Generator(np.random.PCG64(1))
     cols = np.concatenate([[0, 63, 64, 2047, 2048, 32767], rng.integers(0, cfg.L, 250)])
-    sampled_check(cfg, x, out, head=5, row_blocks=[(0, 64), (2016, 64), (32768 - 96, 96)], cols=cols)
-    sampled_check(cfg, x, out, head=12, row_blocks=[], cols=cols[::2])
-    forward_all_rows(cfg, x, out, [0, 5, 10, 15])
+    sampled_check(cfg, x, out, head=5, row_blocks=[(0, 64), (2016, 64), (32768 - 96, 96)], cols=cols, literal=True)
+    sampled_check(cfg, x, out, head=12, row_blocks=[], cols=cols[::2], literal=True)
+    forward_all_rows(cfg, x, out, [0, 5, 10, 15], literal=True)
 
 
 def test_rank15_of_64k_causal_sampled():
@@ -120,8 +127,8 @@ def test_rank15_of_64k_causal_sampled():
     rng = np.random.Generator(np.random.PCG64(2))
     cols = np.concatenate([[0, 4095, 4096, 61439, 61440, 61503, 65535],
                            rng.integers(0, cfg.L, 150), rng.integers(61440, cfg.L, 100)])
-    sampled_check(cfg, x, out, head=11, row_blocks=[(0, 64), (2000, 100), (4096 - 64, 64)], cols=cols)
-    forward_all_rows(cfg, x, out, [0, 6, 11])
+    sampled_check(cfg, x, out, head=11, row_blocks=[(0, 64), (2000, 100), (4096 - 64, 64)], cols=cols, literal=True)
+    forward_all_rows(cfg, x, out, [0, 6, 11], literal=True)
 
 
 def test_causal_ring_32k_sampled():
