@@ -282,7 +282,9 @@ __global__ void __launch_bounds__(256, AH == 2 ? 1 : 2) fused_bwd_dkdv_kernel(Bw
               dk_[db] = mfma_32x32x16(qt2[qb][k2][db], sf[qb * 2 + k2], dk_[db]);
             }
         };
-        fetch(u, 0);
+        // without a mask the tiles of a stage are all walked, and the first reads of every tile
+        // after the stage's first were issued beside the previous tile's last MFMA group
+        if (CAUSAL || u == 0) fetch(u, 0);
         __builtin_amdgcn_sched_barrier(0);
         fetch(u, 1);
         g12(0);
@@ -295,6 +297,10 @@ __global__ void __launch_bounds__(256, AH == 2 ? 1 : 2) fused_bwd_dkdv_kernel(Bw
         g34(0);
         softmax_bwd(1);
         __builtin_amdgcn_sched_barrier(0);
+        // the first reads of the stage's next tile go beside this tile's last eight MFMAs
+        // (their registers are free again), so that tile does not start by waiting for LDS
+        // (past the end of the rows the tile is not walked and what was read is dropped)
+        if (!CAUSAL && u + 1 < NQ) fetch(u + 1, 0);
         g34(1);
         __builtin_amdgcn_sched_barrier(0);
       }
