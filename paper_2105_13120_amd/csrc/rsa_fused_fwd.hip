@@ -38,7 +38,7 @@ struct FwdArgs {
 };
 
 template <int R, bool CAUSAL, int AH, int NK>  // NK: key tiles per stage (one barrier per stage)
-__global__ void __launch_bounds__(256, 2) fused_fwd_kernel(FwdArgs a) {
+__global__ void __launch_bounds__(256, (R == 32 && NK == 1 && AH == 1) ? 4 : 2) fused_fwd_kernel(FwdArgs a) {
   constexpr int QB = R / 32;
   constexpr int BM = 4 * R;
   constexpr int A = 64 * AH;
@@ -414,7 +414,7 @@ hipError_t fused_forward(const Dims &d, const void *Q, const void *K, const void
   a.tiles_per_head = big ? (int)(d.Lq / 256) : (int)((d.Lq + 127) / 128);
   hipError_t e = d.A == 128 ? launch_fwd<32, 2, 1>(d, a, heads, splits, st)
                  : big      ? launch_fwd<64, 1, 2>(d, a, heads, splits, st)
-                            : launch_fwd<32, 1, 2>(d, a, heads, splits, st);
+                            : launch_fwd<32, 1, 1>(d, a, heads, splits, st);
   if (e != hipSuccess || splits == 1) return e;
   const OutLayout lay = make_out_layout(d.os, d.Lq, d.Z);
   hipLaunchKernelGGL(fwd_combine_kernel, dim3((unsigned)((rows * (d.A / 4) + 255) / 256)), dim3(256), 0, st,
