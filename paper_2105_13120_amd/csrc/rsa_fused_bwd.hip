@@ -394,46 +394,6 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   int64_t qrow[QB];
   int64_t qtok[QB];  // global token index of the lane's row
   f32x16 negl[QB], negd[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const int64_t r = row0 + wave * R + qb * 32 + col;
-    qrow[qb] = r < a.Lq ? r : a.Lq - 1;
-    const int64_t blk = row0 + wave * R + qb * 32;  // the block of 32 rows is whole or absent
-    qtok[qb] = a.map(blk < a.Lq ? blk : a.Lq - 32) + col;
-#pragma unroll
-    for (int dk = 0; dk < 4 * AH; ++dk) {
-      qreg[qb][dk] = *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * q_ld + dk * 16 + half * 8);
-      greg[qb][dk] = *reinterpret_cast<const bf16x8 *>(dOh + qrow[qb] * o_ld + dk * 16 + half * 8);
-    }
-    float l2, dd;
-    if (PRE) {
-      // D = sum_a dO_a O_a: this lane holds half of the row's elements, the lane 32 away the rest
-      float acc = 0.f;
-#pragma unroll
-      for (int dk = 0; dk < 4 * AH; ++dk) {
-        const u32x4 x = __builtin_bit_cast(u32x4, greg[qb][dk]);
-        const u32x4 y = *reinterpret_cast<const u32x4 *>(a.O + o_off + qrow[qb] * o_ld + dk * 16 + half * 8);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          acc = fmaf(bf16_to_f32(x[e] & 0xffffu), bf16_to_f32(y[e] & 0xffffu), acc);
-          acc = fmaf(bf16_to_f32(x[e] >> 16), bf16_to_f32(y[e] >> 16), acc);
-        }
-      }
-      dd = -xhalf_sum(acc);
-      l2 = -a.LSE[head * a.Lq + qrow[qb]] * a.inv_scale;
-      if (r < a.Lq && blockIdx.y == 0) {
-        if (half == 0) {
-          a.nD_out[head * a.Lq + r] = dd;
-          a.nL_out[head * a.Lq + r] = l2;
-        }
-      }
-    } else {
-      l2 = a.nL[head * a.Lq + qrow[qb]];
-      dd = a.nD[head * a.Lq + qrow[qb]];
-    }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) { negl[qb][v] = l2; negd[qb][v] = dd; }
-  }
   // first and last token of this wave's rows (R <= 64 rows inside one tile: a run of tokens)
   const int64_t wrow = row0 + wave * R < a.Lq ? row0 + wave * R : a.Lq - R;
   const int64_t wq_first = a.map(wrow);
@@ -489,6 +449,49 @@ __global__ void __launch_bounds__(256, R == 64 ? 1 : 2) fused_bwd_dq_kernel(BwdA
   bool have = f_begin < f_end;
   if (CAUSAL && have && k0_of(t, kt) > q_last) have = advance(t, kt);
   if (have) load_stage(k0_of(t, kt), Ks0, Vs0);
+  // The rows this wave keeps in registers are fetched after the first stage's tiles are on their
+  // way, so that the two latencies overlap (short walks, e.g. a few hundred projected keys, are
+  // mostly prologue).
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int64_t r = row0 + wave * R + qb * 32 + col;
+    qrow[qb] = r < a.Lq ? r : a.Lq - 1;
+    const int64_t blk = row0 + wave * R + qb * 32;  // the block of 32 rows is whole or absent
+    qtok[qb] = a.map(blk < a.Lq ? blk : a.Lq - 32) + col;
+#pragma unroll
+    for (int dk = 0; dk < 4 * AH; ++dk) {
+      qreg[qb][dk] = *reinterpret_cast<const bf16x8 *>(Qh + qrow[qb] * q_ld + dk * 16 + half * 8);
+      greg[qb][dk] = *reinterpret_cast<const bf16x8 *>(dOh + qrow[qb] * o_ld + dk * 16 + half * 8);
+    }
+    float l2, dd;
+    if (PRE) {
+      // D = sum_a dO_a O_a: this lane holds half of the row's elements, the lane 32 away the rest
+      float acc = 0.f;
+#pragma unroll
+      for (int dk = 0; dk < 4 * AH; ++dk) {
+        const u32x4 x = __builtin_bit_cast(u32x4, greg[qb][dk]);
+        const u32x4 y = *reinterpret_cast<const u32x4 *>(a.O + o_off + qrow[qb] * o_ld + dk * 16 + half * 8);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc = fmaf(bf16_to_f32(x[e] & 0xffffu), bf16_to_f32(y[e] & 0xffffu), acc);
+          acc = fmaf(bf16_to_f32(x[e] >> 16), bf16_to_f32(y[e] >> 16), acc);
+        }
+      }
+      dd = -xhalf_sum(acc);
+      l2 = -a.LSE[head * a.Lq + qrow[qb]] * a.inv_scale;
+      if (r < a.Lq && blockIdx.y == 0) {
+        if (half == 0) {
+          a.nD_out[head * a.Lq + r] = dd;
+          a.nL_out[head * a.Lq + r] = l2;
+        }
+      }
+    } else {
+      l2 = a.nL[head * a.Lq + qrow[qb]];
+      dd = a.nD[head * a.Lq + qrow[qb]];
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { negl[qb][v] = l2; negd[qb][v] = dd; }
+  }
   wait_vmem();
   __syncthreads();
   // one stage: start the loads of the next stage into (Kn, Vn), compute on (Kc, Vc)

@@ -14,9 +14,13 @@ pytestmark = pytest.mark.gpu
     (rsa.MODE_FUSED, dict(B=1, Z=2, L=4096, N=4, causal=False, rank_begin=3, rank_end=4)),   # split key walk
     (rsa.MODE_FUSED, dict(B=1, Z=2, L=1024, N=4, causal=True, zigzag=True, A=128)),
     (rsa.MODE_STAGED, dict(B=1, Z=2, L=256, N=2, causal=False)),
+    # the backward whose workspace is the library's static device array (its address is looked up by
+    # the warm-up call, outside the capture)
+    (rsa.MODE_FUSED, dict(B=1, Z=2, L=4096, N=4, causal=True, rank_begin=3, rank_end=4, static_ws=True)),
 ])
 def test_forward_backward_under_graph_capture(mode, kw):
     kw = dict(kw)
+    static_ws = kw.pop("static_ws", False)
     A = kw.pop("A", 64)
     cfg = inputs.RSAConfig("g", A=A, dtype="bf16", seed=61, **kw)
     x = inputs.make_inputs(cfg)
@@ -32,7 +36,10 @@ def test_forward_backward_under_graph_capture(mode, kw):
 
     def run(b):
         rsa.forward(desc, Q, K, V, O=b["O"], LSE=b["LSE"], ws=wf)
-        rsa.backward(desc, dO, Q, K, V, b["O"], b["LSE"], dQ=b["dQ"], dK=b["dK"], dV=b["dV"], ws=wb)
+        if static_ws:
+            rsa.backward_static(desc, dO, Q, K, V, b["O"], b["LSE"], b["dQ"], b["dK"], b["dV"])
+        else:
+            rsa.backward(desc, dO, Q, K, V, b["O"], b["LSE"], dQ=b["dQ"], dK=b["dK"], dV=b["dV"], ws=wb)
 
     eager = buffers()
     run(eager)
