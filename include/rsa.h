@@ -10,8 +10,9 @@
  * j = (n - t) mod N, local chunk first.  There is no inter-GPU traffic.
  *
  * Conventions for every entry point
- *  - All tensor pointers are DEVICE pointers, dense row-major, last index
- *    contiguous, 16-byte aligned.  The caller owns every buffer; the library
+ *  - All tensor pointers are DEVICE pointers, row-major with the last index
+ *    contiguous, 16-byte aligned; dense unless the descriptor's stride fields
+ *    say otherwise (fused mode).  The caller owns every buffer; the library
  *    never allocates, frees or keeps a pointer.
  *  - K, V, dK, dV are (B, Z, L, A).  Q, O, dO, dQ are (B, Z, Lq, A) with
  *    Lq = (rank_end - rank_begin) * c: the rows of ranks [rank_begin,

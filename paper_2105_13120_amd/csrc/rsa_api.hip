@@ -318,12 +318,14 @@ int rsa_backward_static(const rsa_desc *d, const void *dO, const void *Q, const 
 
 int rsa_qk_step(const rsa_desc *d, int n, int j, const void *Q, const void *K, float *S, void *stream) {
   RSA_STEP_PROLOGUE(Q && K && S, Q, K, S);
+  if (dm.strided) return RSA_ERR_UNSUPPORTED;  // the two-pass kernels take dense tensors only
   if ((rc = check_rank_chunk(dm, n, j)) != RSA_OK) return rc;
   return hip_status(rsa::staged_qk_step(dm, d->dtype, n, j, Q, K, S, st));
 }
 
 int rsa_row_softmax(const rsa_desc *d, int n, const float *S, void *P, float *LSE, void *stream) {
   RSA_STEP_PROLOGUE(S && P && LSE, S, P, LSE);
+  if (dm.strided) return RSA_ERR_UNSUPPORTED;  // the two-pass kernels take dense tensors only
   if ((rc = check_rank_chunk(dm, n, 0)) != RSA_OK) return rc;
   return hip_status(rsa::staged_row_softmax(dm, d->dtype, n, S, P, LSE, st));
 }
@@ -331,12 +333,14 @@ int rsa_row_softmax(const rsa_desc *d, int n, const float *S, void *P, float *LS
 int rsa_av_step(const rsa_desc *d, int n, int j, const void *P, const void *V, float *Oacc,
                 int accumulate, void *stream) {
   RSA_STEP_PROLOGUE(P && V && Oacc, P, V, Oacc);
+  if (dm.strided) return RSA_ERR_UNSUPPORTED;  // the two-pass kernels take dense tensors only
   if ((rc = check_rank_chunk(dm, n, j)) != RSA_OK) return rc;
   return hip_status(rsa::staged_av_step(dm, d->dtype, n, j, P, V, Oacc, accumulate != 0, st));
 }
 
 int rsa_bwd_rowdot(const rsa_desc *d, int n, const void *dO, const void *O, float *D, void *stream) {
   RSA_STEP_PROLOGUE(dO && O && D, dO, O, D);
+  if (dm.strided) return RSA_ERR_UNSUPPORTED;  // the two-pass kernels take dense tensors only
   if (n == -1) return hip_status(rsa::rowdot(dm, d->dtype, 0, dm.Lq, dO, O, D, st));
   if ((rc = check_rank_chunk(dm, n, 0)) != RSA_OK) return rc;
   return hip_status(rsa::rowdot(dm, d->dtype, (int64_t)(n - dm.rank_begin) * dm.c, dm.c, dO, O, D, st));
@@ -345,12 +349,14 @@ int rsa_bwd_rowdot(const rsa_desc *d, int n, const void *dO, const void *O, floa
 int rsa_dv_step(const rsa_desc *d, int n, int j, const void *P, const void *dO, float *dVacc,
                 int accumulate, void *stream) {
   RSA_STEP_PROLOGUE(P && dO && dVacc, P, dO, dVacc);
+  if (dm.strided) return RSA_ERR_UNSUPPORTED;  // the two-pass kernels take dense tensors only
   if ((rc = check_rank_chunk(dm, n, j)) != RSA_OK) return rc;
   return hip_status(rsa::staged_dv_step(dm, d->dtype, n, j, P, dO, dVacc, accumulate != 0, st));
 }
 
 int rsa_dp_step(const rsa_desc *d, int n, int j, const void *dO, const void *V, float *dP, void *stream) {
   RSA_STEP_PROLOGUE(dO && V && dP, dO, V, dP);
+  if (dm.strided) return RSA_ERR_UNSUPPORTED;  // the two-pass kernels take dense tensors only
   if ((rc = check_rank_chunk(dm, n, j)) != RSA_OK) return rc;
   return hip_status(rsa::staged_dp_step(dm, d->dtype, n, j, dO, V, dP, st));
 }
@@ -358,6 +364,7 @@ int rsa_dp_step(const rsa_desc *d, int n, int j, const void *dO, const void *V, 
 int rsa_softmax_bwd(const rsa_desc *d, int n, const void *P, const float *dP, const float *D,
                     void *dS, void *stream) {
   RSA_STEP_PROLOGUE(P && dP && D && dS, P, dP, D, dS);
+  if (dm.strided) return RSA_ERR_UNSUPPORTED;  // the two-pass kernels take dense tensors only
   if ((rc = check_rank_chunk(dm, n, 0)) != RSA_OK) return rc;
   return hip_status(rsa::staged_softmax_bwd(dm, d->dtype, n, P, dP, D, dS, st));
 }
@@ -365,6 +372,7 @@ int rsa_softmax_bwd(const rsa_desc *d, int n, const void *P, const float *dP, co
 int rsa_dq_step(const rsa_desc *d, int n, int j, const void *dS, const void *K, float *dQacc,
                 int accumulate, void *stream) {
   RSA_STEP_PROLOGUE(dS && K && dQacc, dS, K, dQacc);
+  if (dm.strided) return RSA_ERR_UNSUPPORTED;  // the two-pass kernels take dense tensors only
   if ((rc = check_rank_chunk(dm, n, j)) != RSA_OK) return rc;
   return hip_status(rsa::staged_dq_step(dm, d->dtype, n, j, dS, K, dQacc, accumulate != 0, st));
 }
@@ -372,6 +380,7 @@ int rsa_dq_step(const rsa_desc *d, int n, int j, const void *dS, const void *K, 
 int rsa_dk_step(const rsa_desc *d, int n, int j, const void *dS, const void *Q, float *dKacc,
                 int accumulate, void *stream) {
   RSA_STEP_PROLOGUE(dS && Q && dKacc, dS, Q, dKacc);
+  if (dm.strided) return RSA_ERR_UNSUPPORTED;  // the two-pass kernels take dense tensors only
   if ((rc = check_rank_chunk(dm, n, j)) != RSA_OK) return rc;
   return hip_status(rsa::staged_dk_step(dm, d->dtype, n, j, dS, Q, dKacc, accumulate != 0, st));
 }

@@ -69,6 +69,8 @@ def test_validation_happens_before_any_launch():
     assert fwd_status(desc(kv_stride=(2 * 256 * 68, 256 * 68, 68))) == -3           # not a multiple of 16 bytes
     assert fwd_status(desc(kv_stride=(1 << 40, 1 << 32, 1 << 25))) == -3            # row stride beyond 2^24
     assert fwd_status(desc(flags=rsa.MODE_STAGED, **inter)) == -3                   # the two-pass kernels are dense only
+    pp = ctypes.c_void_p(0x1000)
+    assert rsa.lib().rsa_qk_step(ctypes.byref(desc(**inter)), 0, 0, pp, pp, pp, None) == -3   # also step by step
     assert fwd_status(desc(), ptr=0) == -1
     assert fwd_status(desc(), ptr=0x1008) == -3              # misaligned
     staged = desc(flags=rsa.MODE_STAGED)
