@@ -73,7 +73,7 @@ def sampled_check(cfg, x, out, head, row_blocks, cols, literal=False):
             if m > 0:
                 O_ref = oracle.forward(Qs[:, :, :m], Kh, Vh, q0=t0, causal=True)[0]
                 dq_x[:, :, s0:s0 + m] = dq_extra(Qs[:, :, :m], Kh, Vh, dOs[:, :, :m], O_ref, t0, True)
-                dk_first = dk_extra(Qs[:, :, :m], Kh, Vh, dOs[:, :, :m], O_ref, t0)     # keys 0..255
+                dk_first = dk_extra(Qs[:, :, :m], Kh, Vh, dOs[:, :, :m], O_ref, t0, causal=True)     # keys 0..255
                 early = np.asarray(cols) < dk_first.shape[2]
                 dk_x[:, :, early] = np.sqrt(dk_x[:, :, early] ** 2 + dk_first[:, :, np.asarray(cols)[early]] ** 2)
     e = check("dQ", dQ[None, None], dQ_ref, cfg.dtype, extra=dq_x)

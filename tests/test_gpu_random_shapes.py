@@ -1,5 +1,6 @@
 """Seeded random shapes through the fused path: ring sizes, rank sub-ranges, masks and ownerships
-drawn at random, every head compared with the oracle.  Catches what the hand-picked cases miss."""
+drawn at random, a third of them with an explicit softmax scale and half with strided tensors, every head
+compared with the oracle.  Catches what the hand-picked cases miss."""
 import numpy as np
 import pytest
 
@@ -16,21 +17,32 @@ def draw_case(rng):
     c = unit * int(rng.integers(1, 5))
     rb = int(rng.integers(0, N))
     re = int(rng.integers(rb + 1, N + 1))
-    return dict(B=int(rng.integers(1, 3)), Z=int(rng.integers(1, 4)), L=N * c, N=N, rb=rb, re=re,
+    case = dict(B=int(rng.integers(1, 3)), Z=int(rng.integers(1, 4)), L=N * c, N=N, rb=rb, re=re,
                 causal=bool(rng.integers(0, 2)), zigzag=zigzag, seed=int(rng.integers(0, 1 << 30)))
+    # drawn last, so that the shapes above are those of earlier versions of this list:
+    # a third of the cases with an explicit softmax scale, half with strided (head-interleaved) tensors
+    # (the scale as a multiple of 1/sqrt(A), between 0.5 and 1.5: well above that, rows sit on single
+    # keys and the error of any bf16 backward -- the CPU model's too -- outgrows bounds made for
+    # scores of unit spread)
+    case["scale_factor"] = float(rng.uniform(0.5, 1.5)) if rng.integers(0, 3) == 0 else 0.0
+    case["interleaved"] = bool(rng.integers(0, 2))
+    return case
 
 
-# 24 cases with heads of 64 elements, then 12 (other seeds) with heads of 128
-CASES = [dict(draw_case(np.random.Generator(np.random.PCG64(1000 + i))), A=64) for i in range(24)] + \
-        [dict(draw_case(np.random.Generator(np.random.PCG64(2000 + i))), A=128) for i in range(12)]
+# 40 cases with heads of 64 elements, then 20 (other seeds) with heads of 128
+CASES = [dict(draw_case(np.random.Generator(np.random.PCG64(1000 + i))), A=64) for i in range(40)] + \
+        [dict(draw_case(np.random.Generator(np.random.PCG64(2000 + i))), A=128) for i in range(20)]
+for _c in CASES:
+    _c["att_scale"] = _c["scale_factor"] / np.sqrt(_c["A"])
 
 
-@pytest.mark.parametrize("case", CASES, ids=lambda c: "A{A}B{B}Z{Z}L{L}N{N}r{rb}-{re}{c}{z}".format(
-    c="c" if c["causal"] else "", z="z" if c["zigzag"] else "", **c))
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "A{A}B{B}Z{Z}L{L}N{N}r{rb}-{re}{c}{z}{s}{i}".format(
+    c="c" if c["causal"] else "", z="z" if c["zigzag"] else "", s="s" if c["att_scale"] else "",
+    i="i" if c["interleaved"] else "", **c))
 def test_random_shape(case):
     cfg = inputs.RSAConfig("r", B=case["B"], Z=case["Z"], L=case["L"], A=case["A"], N=case["N"], dtype="bf16",
                            causal=case["causal"], rank_begin=case["rb"], rank_end=case["re"],
-                           seed=case["seed"], zigzag=case["zigzag"])
+                           seed=case["seed"], zigzag=case["zigzag"], att_scale=case["att_scale"])
     x = inputs.make_inputs(cfg)
-    out = gpu_forward_backward(cfg, x)
+    out = gpu_forward_backward(cfg, x, interleaved=case["interleaved"])
     compare_heads(cfg, x, out, list(range(cfg.B * cfg.Z)))
