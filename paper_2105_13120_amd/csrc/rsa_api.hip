@@ -503,8 +503,8 @@ size_t linformer_ws(const Dims &own, const Dims &att, int64_t Kp) {
   const size_t part = (size_t)rsa::linformer_splits(Kp, Zt, own.Lq, own.A) * Kp * Zt * own.A * 4;
   // backward: row terms, then the fp32 partial dV, dK of the split query walk
   const int qs = rsa::fused_bwd_dkdv_splits(att);
-  const size_t bwd = fused_bwd_base(att) +
-                     (qs > 1 ? (size_t)2 * qs * Zt * Kp * own.A * 4 : 0);
+  size_t bwd = fused_bwd_base(att) + (qs > 1 ? (size_t)2 * qs * Zt * Kp * own.A * 4 : 0);
+  if (rsa::shortkeys_supported(att)) bwd = rsa::shortkeys_bwd_ws_bytes(att);  // the one-kernel backward
   return align256(part > bwd ? part : bwd);
 }
 }  // namespace
@@ -547,6 +547,9 @@ int rsa_linformer_backward(const rsa_desc *d, int32_t Kp, const void *dO, const 
   RSA_LINF_PROLOGUE(dO && Q && Kp_ && Vp_ && O && LSE && dQ && dKp && dVp && ws, dO, Q, Kp_, Vp_, O, LSE,
                     dQ, dKp, dVp, ws);
   if (ws_bytes < linformer_ws(own, att, Kp)) return RSA_ERR_WORKSPACE;
+  if (rsa::shortkeys_supported(att))
+    return hip_status(rsa::shortkeys_backward(att, dO, Q, Kp_, Vp_, O, LSE, dQ, dKp, dVp,
+                                              static_cast<float *>(ws), st));
   const int qs = rsa::fused_bwd_dkdv_splits(att);
   float *part = qs > 1 ? fused_part(att, ws) : nullptr;
   return hip_status(rsa::fused_backward(att, dO, Q, Kp_, Vp_, O, LSE, dQ, dKp, dVp, fused_nD(ws),

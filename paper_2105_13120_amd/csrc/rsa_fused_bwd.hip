@@ -636,6 +636,13 @@ hipError_t fused_bwd_preprocess(const Dims &d, const void *dO, const void *O, co
   return hipGetLastError();
 }
 
+hipError_t qsplit_reduce(const float *part, void *out, int64_t n4, int splits, int A, const OutLayout &lay,
+                         hipStream_t st) {
+  hipLaunchKernelGGL(qsplit_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, part,
+                     (uint16_t *)out, n4, splits, A, lay);
+  return hipGetLastError();
+}
+
 int fused_bwd_dkdv_splits(const Dims &d) {
   const int64_t wgs = (int64_t)d.B * d.Z * ((d.L + 127) / 128), stages = (d.Lq / 64 + 1) / 2;
   int64_t s = 1024 / wgs;  // aim at two work-groups per CU's worth of them

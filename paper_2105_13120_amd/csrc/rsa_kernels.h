@@ -59,6 +59,21 @@ hipError_t fused_backward(const Dims &d, const void *dO, const void *Q, const vo
                           void *dV, float *nD, float *nL, hipStream_t st,
                           float *part = nullptr, int qsplits = 1, int ksplits = 1);
 
+// out (bf16, layout lay) = the sum over `splits` fp32 partial results of n4 * 4 floats each, in a
+// fixed order
+hipError_t qsplit_reduce(const float *part, void *out, int64_t n4, int splits, int A, const OutLayout &lay,
+                         hipStream_t st);
+
+// --- attention to Kp = 128 or 256 keys that one work-group holds (Table 3's shape), bf16, A = 64 ---
+// att: the dimensions with L = Kp keys, one chunk, Lq query rows.  The backward is one kernel (S, dP,
+// dV, dK and dQ); part: fp32 partial dV, dK of the work-groups that share a head,
+// shortkeys_bwd_ws_bytes(att) bytes (0: none needed).
+bool shortkeys_supported(const Dims &att);
+size_t shortkeys_bwd_ws_bytes(const Dims &att);
+hipError_t shortkeys_backward(const Dims &att, const void *dO, const void *Q, const void *K, const void *V,
+                              const void *O, const float *LSE, void *dQ, void *dK, void *dV, float *part,
+                              hipStream_t st);
+
 // --- the linear maps around RSA (Table 2, rows Q/K/V and Linear), bf16, A = 64 or 128 ---
 // X, dX, Y, dY: (B, Lq, H); W: (H, 3*Z*A), columns [Q | K | V] head-major; Wo: (Z*A, H);
 // Q, K, V, O and their gradients: (B, Z, Lq, A); dW, dWo: fp32; part: k-split partial sums.
