@@ -74,6 +74,11 @@ hipError_t shortkeys_backward(const Dims &att, const void *dO, const void *Q, co
                               const void *O, const float *LSE, void *dQ, void *dK, void *dV, float *part,
                               hipStream_t st);
 
+// dX (Zt, L, A) rows [0, rows) from the pointer passed = E (rows, Kp) dXp (Zt, Kp, A), Kp <= 256
+bool linformer_dx_supported(int64_t Kp, int A);
+hipError_t linformer_dx(int64_t Zt, int64_t L, int64_t rows, int64_t Kp, int A, const void *dXp, const void *E,
+                        void *dX, hipStream_t st);
+
 // --- the linear maps around RSA (Table 2, rows Q/K/V and Linear), bf16, A = 64 or 128 ---
 // X, dX, Y, dY: (B, Lq, H); W: (H, 3*Z*A), columns [Q | K | V] head-major; Wo: (Z*A, H);
 // Q, K, V, O and their gradients: (B, Z, Lq, A); dW, dWo: fp32; part: k-split partial sums.

@@ -450,7 +450,10 @@ hipError_t linformer_project(int64_t Zt, int64_t L, int64_t rows, int64_t Kp, in
 // dX rows (Zt, L, A) from row0 on = E dXp, and dE (rows, Kp) fp32 = sum over heads of X dXp^T
 hipError_t linformer_project_bwd(int64_t Zt, int64_t L, int64_t rows, int64_t Kp, int A, const void *dXp,
                                  const void *X, const void *E, void *dX, float *dE, hipStream_t st) {
-  {
+  if (linformer_dx_supported(Kp, A)) {
+    hipError_t e = linformer_dx(Zt, L, rows, Kp, A, dXp, E, dX, st);
+    if (e != hipSuccess) return e;
+  } else {
     GemmArgs g{};
     g.M = rows; g.N = Zt * A; g.K = Kp;
     g.A = plain(E, Kp);                                  // [M = token][K = k]

@@ -367,6 +367,133 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
   }
 }
 
+// ---------------------------------------------------------------- dX = E dXp ---
+// The input gradient of the Linformer projection (Table 3, row Projection): for every head,
+// dX (rows, A) = E (rows, Kp) dXp (Kp, A) with Kp <= 256.  As a GEMM its contraction is only Kp long, so a
+// tiled kernel spends its time filling and draining its pipeline; here a work-group keeps its 128
+// rows of E in registers (as B operands: wave w owns rows 32 w .. 32 w + 31) and streams the heads'
+// dXp tiles through LDS, double-buffered, one barrier per 64 output columns:
+//     dX^T (64 dims x 32 rows) += dXp^T (dims x 16 k) E^T (16 k x rows)     (A: LDS transpose reads)
+// and the block leaves through the wave's LDS tile as whole 128-byte rows.
+struct DxArgs {
+  const uint16_t *E, *dXp;
+  uint16_t *dX;
+  int64_t rows, L, Kp;
+  int A, AH, ntiles, tiles_per_group, groups;  // ntiles = heads * AH column tiles of 64
+};
+
+template <int KT>
+__global__ void __launch_bounds__(256, 2) linformer_dx_kernel(DxArgs g) {
+  struct Buf { unsigned char t[KT][kTileBytes]; };
+  __shared__ __attribute__((aligned(16))) Buf buf0, buf1;
+  __shared__ __attribute__((aligned(16))) unsigned char stg[4][32 * 128];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int64_t blk = blockIdx.x / g.groups;
+  const int grp = blockIdx.x % g.groups;
+  const int64_t row0 = blk * 128;
+  const int ct_begin = grp * g.tiles_per_group;
+  const int nct = min(g.tiles_per_group, g.ntiles - ct_begin);
+  if (nct <= 0) return;
+  const TileLanes tl(lane);
+  const TileDMAT<4> dma_e(wave, lane, (int)g.Kp), dma_b(wave, lane, g.A);
+
+  // E rows of the block -> LDS (its 2 x KT tiles fill the two buffers) -> registers
+  const int64_t last_rt = g.rows / 64 - 1;
+#pragma unroll
+  for (int kt = 0; kt < KT; ++kt) {
+    const int64_t rt0 = min(row0 / 64, last_rt), rt1 = min(row0 / 64 + 1, last_rt);  // past the end: refetch
+    dma_e.load(g.E + rt0 * 64 * g.Kp + kt * 64, buf0.t[kt]);
+    dma_e.load(g.E + rt1 * 64 * g.Kp + kt * 64, buf1.t[kt]);
+  }
+  wait_vmem();
+  __syncthreads();
+  bf16x8 efrag[KT * 4];
+#pragma unroll
+  for (int ks = 0; ks < KT * 4; ++ks) {
+    const unsigned char *te = (wave >> 1) ? buf1.t[ks >> 2] : buf0.t[ks >> 2];
+    efrag[ks] = tl.read_rows_perm(te, (wave & 1) * 32, ks & 3);
+  }
+  __syncthreads();  // the buffers are free again
+
+  auto load_b = [&](int ct, Buf &b) __attribute__((always_inline)) {
+    const int head = ct / g.AH, ah = ct % g.AH;
+    const uint16_t *src = g.dXp + (int64_t)head * g.Kp * g.A + ah * 64;
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) dma_b.load(src + (int64_t)kt * 64 * g.A, b.t[kt]);
+  };
+  unsigned char *ot = stg[wave];
+  const int64_t wrow0 = row0 + wave * 32;
+  auto tile = [&](int ct, const Buf &b) __attribute__((always_inline)) {
+    f32x16 acc[2];
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
+    bf16x8 af[2][2];
+    auto frags = [&](int ks) __attribute__((always_inline)) {
+#pragma unroll
+      for (int db = 0; db < 2; ++db) af[ks & 1][db] = tl.read_cols(b.t[ks >> 2], (ks & 3) * 16, db);
+    };
+    frags(0);
+#pragma unroll
+    for (int ks = 0; ks < KT * 4; ++ks) {
+      if (ks + 1 < KT * 4) frags(ks + 1);
+#pragma unroll
+      for (int db = 0; db < 2; ++db) acc[db] = mfma_32x32x16(af[ks & 1][db], efrag[ks], acc[db]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    const int head = ct / g.AH, ah = ct % g.AH;
+    stage_block_T(ot, 0, acc[0], acc[1], 1.0f, lane);
+    flush_rows<32>(ot, 0, g.dX + ((int64_t)head * g.L + wrow0) * g.A + ah * 64, g.rows - wrow0, lane, g.A);
+  };
+
+  load_b(ct_begin, buf0);
+  int i = 0;
+  auto step = [&](Buf &cur, Buf &nxt) __attribute__((always_inline)) {
+    wait_vmem();
+    __syncthreads();
+    if (i + 1 < nct) load_b(ct_begin + i + 1, nxt);
+    tile(ct_begin + i, cur);
+    ++i;
+  };
+  while (i < nct) {
+    step(buf0, buf1);
+    if (i >= nct) break;
+    step(buf1, buf0);
+  }
+}
+
+bool linformer_dx_supported(int64_t Kp, int A) { return Kp % 64 == 0 && Kp <= 256 && (A == 64 || A == 128); }
+
+hipError_t linformer_dx(int64_t Zt, int64_t L, int64_t rows, int64_t Kp, int A, const void *dXp, const void *E,
+                        void *dX, hipStream_t st) {
+  DxArgs g;
+  g.E = (const uint16_t *)E; g.dXp = (const uint16_t *)dXp; g.dX = (uint16_t *)dX;
+  g.rows = rows; g.L = L; g.Kp = Kp; g.A = A; g.AH = A / 64; g.ntiles = (int)(Zt * g.AH);
+  const int64_t blocks = (rows + 127) / 128;
+  // groups of column tiles per row block: few, even rounds of the 512 work-groups the chip holds
+  int best = 1;
+  double best_cost = 1e30;
+  for (int gr = 1; gr <= 16 && gr <= g.ntiles; ++gr) {
+    const int per = (g.ntiles + gr - 1) / gr;
+    if ((int64_t)per * (gr - 1) >= g.ntiles) continue;
+    const double cost = (double)((blocks * gr + 511) / 512) * (per + 2);
+    if (cost < best_cost) { best_cost = cost; best = gr; }
+  }
+  g.groups = best;
+  g.tiles_per_group = (g.ntiles + best - 1) / best;
+  const dim3 grid((unsigned)(blocks * best));
+  switch (Kp / 64) {
+    case 1: hipLaunchKernelGGL(linformer_dx_kernel<1>, grid, dim3(256), 0, st, g); break;
+    case 2: hipLaunchKernelGGL(linformer_dx_kernel<2>, grid, dim3(256), 0, st, g); break;
+    case 3: hipLaunchKernelGGL(linformer_dx_kernel<3>, grid, dim3(256), 0, st, g); break;
+    default: hipLaunchKernelGGL(linformer_dx_kernel<4>, grid, dim3(256), 0, st, g); break;
+  }
+  return hipGetLastError();
+}
+
 bool shortkeys_supported(const Dims &att) {
   return att.A == 64 && (att.L == 128 || att.L == 256) && !att.causal && !att.strided && att.N == 1 &&
          att.Lq >= 64;
