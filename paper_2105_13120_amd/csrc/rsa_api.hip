@@ -538,6 +538,7 @@ int rsa_linformer_project(const rsa_desc *d, int32_t Kp, const void *X, const vo
 int rsa_linformer_forward(const rsa_desc *d, int32_t Kp, const void *Q, const void *Kp_, const void *Vp_,
                           void *O, float *LSE, void *stream) {
   RSA_LINF_PROLOGUE(Q && Kp_ && Vp_ && O && LSE, Q, Kp_, Vp_, O, LSE);
+  if (rsa::shortkeys_supported(att)) return hip_status(rsa::shortkeys_forward(att, Q, Kp_, Vp_, O, LSE, st));
   return hip_status(rsa::fused_forward(att, Q, Kp_, Vp_, O, LSE, st, nullptr));
 }
 

@@ -69,6 +69,8 @@ hipError_t qsplit_reduce(const float *part, void *out, int64_t n4, int splits, i
 // dV, dK and dQ); part: fp32 partial dV, dK of the work-groups that share a head,
 // shortkeys_bwd_ws_bytes(att) bytes (0: none needed).
 bool shortkeys_supported(const Dims &att);
+hipError_t shortkeys_forward(const Dims &att, const void *Q, const void *K, const void *V, void *O, float *LSE,
+                             hipStream_t st);
 size_t shortkeys_bwd_ws_bytes(const Dims &att);
 hipError_t shortkeys_backward(const Dims &att, const void *dO, const void *Q, const void *K, const void *V,
                               const void *O, const float *LSE, void *dQ, void *dK, void *dV, float *part,

@@ -367,6 +367,205 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
   }
 }
 
+// ------------------------------------------------------------------ forward ---
+// Eq. 1 for query rows that all attend to the same Kp <= 256 keys of their head: the keys' K and V
+// tiles are loaded into LDS once per work-group, which then walks blocks of 256 query rows of the head
+// (wave w: rows 64 w .. 64 w + 63 of the block) with no barrier and no load but the rows' own Q:
+//   S^T = K Q^T (A: K tile rows from LDS, B: Q^T in registers), running max and sum per row
+//   (lane = query column), O^T += V^T P^T (A: LDS transpose reads, B: P^T from the accumulator).
+// The waves of a work-group drift apart, so one wave's row loads and stores run beside the others'
+// matrix work.
+struct SkFwdArgs {
+  const uint16_t *Q, *K, *V;
+  uint16_t *O;
+  float *LSE;
+  int64_t Lq;
+  int64_t qs[3], ks[3], os[3];
+  int Z, splits, blocks_per_split;
+  float cl2;
+};
+
+template <int KT>
+__global__ void __launch_bounds__(256, 2) shortkeys_fwd_kernel(SkFwdArgs a) {
+  __shared__ __attribute__((aligned(16))) unsigned char Kt[KT][kTileBytes], Vt[KT][kTileBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char stg[4][32 * 128];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int col = lane & 31, half = lane >> 5;
+  const int64_t head = blockIdx.x / a.splits;
+  const int split = blockIdx.x % a.splits;
+  const int nblk = (int)((a.Lq + 255) / 256);
+  const int b_begin = split * a.blocks_per_split;
+  const int b_end = min(b_begin + a.blocks_per_split, nblk);
+  if (b_begin >= b_end) return;
+
+  const int64_t kv_off = head_offset(head, a.Z, a.ks);
+  const int64_t q_ld = a.qs[2], kv_ld = a.ks[2], o_ld = a.os[2];
+  const uint16_t *Qh = a.Q + head_offset(head, a.Z, a.qs);
+  uint16_t *Oh = a.O + head_offset(head, a.Z, a.os);
+  float *LSEh = a.LSE + head * a.Lq;
+  {
+    const TileDMA dma(wave, lane, (int)kv_ld);
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      dma.load(a.K + kv_off + (int64_t)kt * 64 * kv_ld, Kt[kt]);
+      dma.load(a.V + kv_off + (int64_t)kt * 64 * kv_ld, Vt[kt]);
+    }
+  }
+  const TileLanes tl(lane);
+  unsigned char *ot = stg[wave];
+  const int q_lane = col * (int)q_ld + half * 8;  // lane part of a Q row address (32-bit)
+  wait_vmem();
+  __syncthreads();
+
+  // Q^T operand: lane (col, half) holds Q[row][dk*16 + half*8 .. +8]; the rows of the next block are
+  // fetched as soon as the last S^T of the current one has been issued
+  bf16x8 qreg[2][4];
+  auto load_q = [&](int64_t r0) __attribute__((always_inline)) {
+    if (r0 >= a.Lq) r0 = a.Lq - 64;  // past the end: any valid rows (not used)
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const uint16_t *qp = Qh + (r0 + qb * 32) * q_ld;
+#pragma unroll
+      for (int dk = 0; dk < 4; ++dk) qreg[qb][dk] = *reinterpret_cast<const bf16x8 *>(qp + (q_lane + dk * 16));
+    }
+  };
+  load_q((int64_t)b_begin * 256 + wave * 64);
+  for (int b = b_begin; b < b_end; ++b) {
+    const int64_t wr0 = (int64_t)b * 256 + wave * 64;  // the wave's first row
+    if (wr0 >= a.Lq) break;                             // (rows come in multiples of 64)
+    f32x16 o[2][2];
+    float m[2], mc[2], l[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      m[qb] = -INFINITY; mc[qb] = 0.f; l[qb] = 0.f;
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[db][qb][v] = 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < KT; ++u) {
+      f32x16 sc[2][2];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        bf16x8 ka[4];
+#pragma unroll
+        for (int dk = 0; dk < 4; ++dk) ka[dk] = tl.read_rows(Kt[u], kb * 32, dk);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sc[kb][qb][v] = 0.f;
+#pragma unroll
+          for (int dk = 0; dk < 4; ++dk) sc[kb][qb] = mfma_32x32x16(ka[dk], qreg[qb][dk], sc[kb][qb]);
+        }
+      }
+      if (u == KT - 1) {
+        __builtin_amdgcn_sched_barrier(0);
+        load_q(wr0 + 256);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // running max; the accumulators are rescaled only when some row's max grew by more than
+      // 2^8 in the exp2 domain (exact: l and O share the stale max)
+      float tm[2];
+      bool need = false;
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        float x = sc[0][qb][0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) x = fmaxf(x, sc[0][qb][v]);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) x = fmaxf(x, sc[1][qb][v]);
+        tm[qb] = xhalf_max(x);
+        need |= (tm[qb] - m[qb]) * a.cl2 > 8.0f;
+      }
+      if (__builtin_amdgcn_ballot_w64(need) != 0) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+          const float mn = fmaxf(m[qb], tm[qb]);
+          const float alpha = __builtin_amdgcn_exp2f((m[qb] - mn) * a.cl2);  // first tile: exp2(-inf) = 0
+          m[qb] = mn;
+          mc[qb] = mn * a.cl2;
+          l[qb] *= alpha;
+#pragma unroll
+          for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][qb][v] *= alpha;
+        }
+      }
+      bf16x8 pf[2][4];
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        float ls = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          float p[16];
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            p[v] = __builtin_amdgcn_exp2f(fmaf(sc[kb][qb][v], a.cl2, -mc[qb]));
+            ls += p[v];
+          }
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            u32x4 w = {pack_bf16(p[h * 8 + 0], p[h * 8 + 1]), pack_bf16(p[h * 8 + 2], p[h * 8 + 3]),
+                       pack_bf16(p[h * 8 + 4], p[h * 8 + 5]), pack_bf16(p[h * 8 + 6], p[h * 8 + 7])};
+            pf[qb][kb * 2 + h] = __builtin_bit_cast(bf16x8, w);
+          }
+        }
+        l[qb] += ls;
+      }
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const bf16x8 va = tl.read_cols(Vt[u], kk * 16, db);
+#pragma unroll
+          for (int qb = 0; qb < 2; ++qb) o[db][qb] = mfma_32x32x16(va, pf[qb][kk], o[db][qb]);
+        }
+    }
+    // O = O^T / l, LSE = (m cl2 + log2 l) ln 2; 32 rows at a time through the wave's LDS tile
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const float lt = xhalf_sum(l[qb]);
+      const float inv = 1.0f / lt;
+      if (half == 0) LSEh[wr0 + qb * 32 + col] = (mc[qb] + __builtin_amdgcn_logf(lt)) * kLn2;
+      stage_block_T(ot, 0, o[0][qb], o[1][qb], inv, lane);
+      flush_rows<32>(ot, 0, Oh + (wr0 + qb * 32) * o_ld, 32, lane, (int)o_ld);
+    }
+  }
+}
+
+int shortkeys_fwd_splits(const Dims &att) {
+  const int64_t heads = (int64_t)att.B * att.Z, blocks = (att.Lq + 255) / 256;
+  int best = 1;
+  double best_cost = 1e30;
+  for (int s = 1; s <= 128 && s <= blocks; ++s) {
+    const int64_t per = (blocks + s - 1) / s;
+    if (per * (s - 1) >= blocks) continue;
+    const double cost = (double)((heads * s + 511) / 512) * (per + 1);  // + 1: the K/V load, in blocks
+    if (cost < best_cost) { best_cost = cost; best = s; }
+  }
+  return best;
+}
+
+hipError_t shortkeys_forward(const Dims &att, const void *Q, const void *K, const void *V, void *O, float *LSE,
+                             hipStream_t st) {
+  SkFwdArgs a;
+  a.Q = (const uint16_t *)Q; a.K = (const uint16_t *)K; a.V = (const uint16_t *)V;
+  a.O = (uint16_t *)O; a.LSE = LSE; a.Lq = att.Lq; a.Z = att.Z;
+  for (int k = 0; k < 3; ++k) { a.qs[k] = att.qs[k]; a.ks[k] = att.ks[k]; a.os[k] = att.os[k]; }
+  a.splits = shortkeys_fwd_splits(att);
+  a.blocks_per_split = (int)(((att.Lq + 255) / 256 + a.splits - 1) / a.splits);
+  a.cl2 = att.scale * kLog2e;
+  const dim3 grid((unsigned)((int64_t)att.B * att.Z * a.splits));
+  if (att.L == 256)
+    hipLaunchKernelGGL(shortkeys_fwd_kernel<4>, grid, dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL(shortkeys_fwd_kernel<2>, grid, dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- dX = E dXp ---
 // The input gradient of the Linformer projection (Table 3, row Projection): for every head,
 // dX (rows, A) = E (rows, Kp) dXp (Kp, A) with Kp <= 256.  As a GEMM its contraction is only Kp long, so a
