@@ -172,25 +172,23 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
   // dQ of the previous tile from its dS^T
   const int dq_rows = (wave / WPR) * 16;          // the wave's 16 query rows
   const int dq_dim0 = (wave % WPR) * (16 * DB);   // its first dim
-  auto dq_tile = [&](const unsigned char(*ds)[kTileBytes], int t) __attribute__((always_inline)) {
-    f32x4 dq[DB];
+  // in two parts (k slices of 32 keys: [0, KT) and [KT, 2 KT)) that ride in the last phase of the next
+  // tile's main sweep, whose eight MFMAs fill the gaps of this chain of LDS reads and small MFMAs
+  f32x4 dq[DB];
+  auto dq_part = [&](const unsigned char(*ds)[kTileBytes], int part) __attribute__((always_inline)) {
+    if (part == 0) {
 #pragma unroll
-    for (int b = 0; b < DB; ++b) dq[b] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // k slices of 32 keys; the fragments of slice ks + 1 are read while the MFMAs of slice ks run
-    bf16x8 bfrag[2], afrag[2][DB];
-    auto frags = [&](int ks) __attribute__((always_inline)) {
-      bfrag[ks & 1] = tl16.read(ds[ks >> 1], (ks & 1) * 32, dq_rows >> 4);
-#pragma unroll
-      for (int b = 0; b < DB; ++b) afrag[ks & 1][b] = tl16.read(Kt[ks >> 1], (ks & 1) * 32, (dq_dim0 >> 4) + b);
-    };
-    frags(0);
-#pragma unroll
-    for (int ks = 0; ks < 2 * KT; ++ks) {
-      if (ks + 1 < 2 * KT) frags(ks + 1);
-#pragma unroll
-      for (int b = 0; b < DB; ++b) dq[b] = mfma_16x16x32(afrag[ks & 1][b], bfrag[ks & 1], dq[b]);
-      __builtin_amdgcn_sched_barrier(0);
+      for (int b = 0; b < DB; ++b) dq[b] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+#pragma unroll
+    for (int ks = part * KT; ks < (part + 1) * KT; ++ks) {
+      const bf16x8 bfrag = tl16.read(ds[ks >> 1], (ks & 1) * 32, dq_rows >> 4);
+#pragma unroll
+      for (int b = 0; b < DB; ++b)
+        dq[b] = mfma_16x16x32(tl16.read(Kt[ks >> 1], (ks & 1) * 32, (dq_dim0 >> 4) + b), bfrag, dq[b]);
+    }
+  };
+  auto dq_store = [&](int t) __attribute__((always_inline)) {
     // lane (n = l%16, mg = l/16) holds dims dq_dim0 + b*16 + mg*4 .. +3 of query row dq_rows + n
     unsigned char *st = qst[wave];
     const int n = lane & 15, mg = lane >> 4;
@@ -215,7 +213,8 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
   // S', dP', P, dS, dV, dK of one tile of 64 rows (in rg, row terms in slot) against the wave's keys,
   // one block of 32 rows after the other with one set of registers (the two waves of a SIMD overlap
   // each other's matrix and vector phases); every LDS read is issued a phase before its use.
-  auto main_tile = [&](const Ring &rg, int slot, unsigned char *ds) __attribute__((always_inline)) {
+  auto main_tile = [&](const Ring &rg, int slot, unsigned char *ds, const unsigned char(*ds_prev)[kTileBytes])
+      __attribute__((always_inline)) {
     bf16x8 qa[4], ga[4];
     f32x16 sacc, dpacc;
     bf16x8 pf[2], sf[2];
@@ -301,6 +300,8 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
     softmax_bwd(1);
     __builtin_amdgcn_sched_barrier(0);
     g34();
+    dq_part(ds_prev, 0);
+    dq_part(ds_prev, 1);
     __builtin_amdgcn_sched_barrier(0);
   };
 
@@ -323,9 +324,9 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
     if (t + 1 < T) row_terms(nxt, slot == 2 ? 0 : slot + 1);
     if (t + 2 < T) load_o(t + 2);
     __builtin_amdgcn_sched_barrier(0);
-    if (t > 0) dq_tile(dST[(t - 1) & 1], t - 1);
-    __builtin_amdgcn_sched_barrier(0);
-    main_tile(cur, slot, &dST[t & 1][0][0]);
+    // (the first tile has no predecessor: its dQ parts run on whatever the buffer holds and are dropped)
+    main_tile(cur, slot, &dST[t & 1][0][0], dST[(t - 1) & 1]);
+    if (t > 0) dq_store(t - 1);
     ++t;
   };
   while (t < T) {
@@ -336,7 +337,9 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
     step(ring2, ring0, ring1, 2);
   }
   __syncthreads();
-  dq_tile(dST[(T - 1) & 1], T - 1);
+  dq_part(dST[(T - 1) & 1], 0);
+  dq_part(dST[(T - 1) & 1], 1);
+  dq_store(T - 1);
 
   // dV, dK of the wave's 32 keys
   const int64_t key0 = wave * 32;

@@ -30,6 +30,9 @@ CASES = [
     (1, 3, 640, 5, (0, 5), 128, 64),
     (1, 2, 1024, 4, (1, 3), 192, 64),      # two ranks' share: partial projections and gradients
     (2, 4, 4096, 8, (0, 8), 256, 64),
+    (1, 2, 64, 1, (0, 1), 256, 64),        # one tile of rows: the one-kernel backward without partial sums
+    (1, 1, 256, 4, (1, 2), 128, 64),
+    (3, 1, 1856, 1, (0, 1), 256, 64),      # 29 tiles per head: uneven shares of the rows
     (1, 1, 64, 1, (0, 1), 64, 128),        # heads of 128 elements
     (1, 3, 640, 5, (1, 4), 128, 128),
     (2, 2, 2048, 8, (0, 8), 256, 128),
