@@ -188,7 +188,10 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
         dq[b] = mfma_16x16x32(tl16.read(Kt[ks >> 1], (ks & 1) * 32, (dq_dim0 >> 4) + b), bfrag, dq[b]);
     }
   };
-  auto dq_store = [&](int t) __attribute__((always_inline)) {
+  // the wave's dQ block goes to its LDS staging block as bf16 (dq_stage) and leaves from there as
+  // 16-byte pieces (dq_flush: a step later, behind the step's barrier, so that the wait for the
+  // step's tile loads never waits for stores just issued)
+  auto dq_stage = [&]() __attribute__((always_inline)) {
     // lane (n = l%16, mg = l/16) holds dims dq_dim0 + b*16 + mg*4 .. +3 of query row dq_rows + n
     unsigned char *st = qst[wave];
     const int n = lane & 15, mg = lane >> 4;
@@ -198,7 +201,10 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
                        pack_bf16(dq[b][2] * a.scale, dq[b][3] * a.scale)};
       *reinterpret_cast<u32x2 *>(st + n * OST + b * 32 + mg * 8) = w;
     }
-    // 16 rows of 32 DB bytes leave as 16-byte pieces (same wave: LDS operations complete in order)
+  };
+  auto dq_flush = [&](int t) __attribute__((always_inline)) {
+    // 16 rows of 32 DB bytes (same wave: LDS operations complete in order)
+    const unsigned char *st = qst[wave];
     constexpr int PPR = 2 * DB;  // pieces per row
     uint16_t *dq_t = dQh + ((int64_t)t * 64 + dq_rows) * q_ld + dq_dim0;
 #pragma unroll
@@ -323,10 +329,11 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
     if (t + 2 < T) load_tile(t + 2, nn);
     if (t + 1 < T) row_terms(nxt, slot == 2 ? 0 : slot + 1);
     if (t + 2 < T) load_o(t + 2);
+    if (t > 1) dq_flush(t - 2);  // staged at the end of the previous step
     __builtin_amdgcn_sched_barrier(0);
     // (the first tile has no predecessor: its dQ parts run on whatever the buffer holds and are dropped)
     main_tile(cur, slot, &dST[t & 1][0][0], dST[(t - 1) & 1]);
-    if (t > 0) dq_store(t - 1);
+    if (t > 0) dq_stage();  // dQ of tile t - 1
     ++t;
   };
   while (t < T) {
@@ -337,9 +344,11 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
     step(ring2, ring0, ring1, 2);
   }
   __syncthreads();
+  if (T > 1) dq_flush(T - 2);
   dq_part(dST[(T - 1) & 1], 0);
   dq_part(dST[(T - 1) & 1], 1);
-  dq_store(T - 1);
+  dq_stage();
+  dq_flush(T - 1);
 
   // dV, dK of the wave's 32 keys
   const int64_t key0 = wave * 32;
@@ -646,8 +655,11 @@ __global__ void __launch_bounds__(256, 2) linformer_dx_kernel(DxArgs g) {
       for (int db = 0; db < 2; ++db) acc[db] = mfma_32x32x16(af[ks & 1][db], efrag[ks], acc[db]);
       __builtin_amdgcn_sched_barrier(0);
     }
-    const int head = ct / g.AH, ah = ct % g.AH;
     stage_block_T(ot, 0, acc[0], acc[1], 1.0f, lane);
+  };
+  // the staged block leaves a step later, behind the step's barrier and beside the next tile's MFMAs
+  auto flush = [&](int ct) __attribute__((always_inline)) {
+    const int head = ct / g.AH, ah = ct % g.AH;
     flush_rows<32>(ot, 0, g.dX + ((int64_t)head * g.L + wrow0) * g.A + ah * 64, g.rows - wrow0, lane, g.A);
   };
 
@@ -657,6 +669,7 @@ __global__ void __launch_bounds__(256, 2) linformer_dx_kernel(DxArgs g) {
     wait_vmem();
     __syncthreads();
     if (i + 1 < nct) load_b(ct_begin + i + 1, nxt);
+    if (i > 0) flush(ct_begin + i - 1);
     tile(ct_begin + i, cur);
     ++i;
   };
@@ -665,6 +678,7 @@ __global__ void __launch_bounds__(256, 2) linformer_dx_kernel(DxArgs g) {
     if (i >= nct) break;
     step(buf1, buf0);
   }
+  flush(ct_begin + nct - 1);
 }
 
 bool linformer_dx_supported(int64_t Kp, int A) { return Kp % 64 == 0 && Kp <= 256 && (A == 64 || A == 128); }
