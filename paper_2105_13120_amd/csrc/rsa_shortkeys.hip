@@ -642,17 +642,22 @@ __global__ void __launch_bounds__(256, 2) linformer_dx_kernel(DxArgs g) {
     for (int db = 0; db < 2; ++db)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[db][v] = 0.f;
-    bf16x8 af[2][2];
+    // a k slice is only two MFMAs, far less than the latency of an LDS read: the fragments are read
+    // DEPTH slices ahead
+    constexpr int DEPTH = 6, NS = KT * 4;
+    bf16x8 af[NS][2];
     auto frags = [&](int ks) __attribute__((always_inline)) {
 #pragma unroll
-      for (int db = 0; db < 2; ++db) af[ks & 1][db] = tl.read_cols(b.t[ks >> 2], (ks & 3) * 16, db);
+      for (int db = 0; db < 2; ++db) af[ks][db] = tl.read_cols(b.t[ks >> 2], (ks & 3) * 16, db);
     };
-    frags(0);
 #pragma unroll
-    for (int ks = 0; ks < KT * 4; ++ks) {
-      if (ks + 1 < KT * 4) frags(ks + 1);
+    for (int ks = 0; ks < DEPTH && ks < NS; ++ks) frags(ks);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int db = 0; db < 2; ++db) acc[db] = mfma_32x32x16(af[ks & 1][db], efrag[ks], acc[db]);
+    for (int ks = 0; ks < NS; ++ks) {
+      if (ks + DEPTH < NS) frags(ks + DEPTH);
+#pragma unroll
+      for (int db = 0; db < 2; ++db) acc[db] = mfma_32x32x16(af[ks][db], efrag[ks], acc[db]);
       __builtin_amdgcn_sched_barrier(0);
     }
     stage_block_T(ot, 0, acc[0], acc[1], 1.0f, lane);
