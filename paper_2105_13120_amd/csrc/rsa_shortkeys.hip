@@ -65,6 +65,19 @@ struct TileLanes16 {
   }
 };
 
+// An 8-byte LDS store that the compiler does not see as a memory access.  For this kernel's dS^T stores it
+// cannot tell that they miss the ring buffers, and it would wait for every direct load in flight before the
+// first of them: the tile requested at the top of a step would be waited for in the middle of that step.
+// The stores are ordered by hand instead: a wave's LDS operations complete in order, and the wait at the top of
+// every step names lgkmcnt(0) before the barrier that publishes them.
+__device__ __forceinline__ void lds_store_b64_unseen(unsigned char *lds_ptr, u32x2 v) {
+  typedef __attribute__((address_space(3))) unsigned char *lptr_t;
+  const uint32_t addr = (uint32_t)(uintptr_t)(lptr_t)lds_ptr;
+  asm volatile("ds_write_b64 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+// vmcnt(0) and lgkmcnt(0): before a barrier behind which other waves read what this wave stored that way
+__device__ __forceinline__ void wait_vmem_lds() { __builtin_amdgcn_s_waitcnt(0x0070); }
+
 template <int NW>
 __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
   constexpr int KT = NW / 2;        // 64-key tiles
@@ -193,13 +206,13 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
   // step's tile loads never waits for stores just issued)
   auto dq_stage = [&]() __attribute__((always_inline)) {
     // lane (n = l%16, mg = l/16) holds dims dq_dim0 + b*16 + mg*4 .. +3 of query row dq_rows + n
-    unsigned char *st = qst[wave];
     const int n = lane & 15, mg = lane >> 4;
+    const int st_off = wave * (16 * OST) + n * OST + mg * 8;
 #pragma unroll
     for (int b = 0; b < DB; ++b) {
       const u32x2 w = {pack_bf16(dq[b][0] * a.scale, dq[b][1] * a.scale),
                        pack_bf16(dq[b][2] * a.scale, dq[b][3] * a.scale)};
-      *reinterpret_cast<u32x2 *>(st + n * OST + b * 32 + mg * 8) = w;
+      *reinterpret_cast<u32x2 *>(&qst[0][st_off + b * 32]) = w;
     }
   };
   auto dq_flush = [&](int t) __attribute__((always_inline)) {
@@ -219,8 +232,9 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
   // S', dP', P, dS, dV, dK of one tile of 64 rows (in rg, row terms in slot) against the wave's keys,
   // one block of 32 rows after the other with one set of registers (the two waves of a SIMD overlap
   // each other's matrix and vector phases); every LDS read is issued a phase before its use.
-  auto main_tile = [&](const Ring &rg, int slot, unsigned char *ds, const unsigned char(*ds_prev)[kTileBytes])
+  auto main_tile = [&](const Ring &rg, int slot, int par, const unsigned char(*ds_prev)[kTileBytes])
       __attribute__((always_inline)) {
+    const int ds_off = par * (KT * kTileBytes) + ds_base;
     bf16x8 qa[4], ga[4];
     f32x16 sacc, dpacc;
     bf16x8 pf[2], sf[2];
@@ -266,7 +280,7 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
         for (int gg = 0; gg < 2; ++gg) {
           const int cc = qb * 4 + w2 * 2 + gg;
           const u32x2 piece = {x[2 * gg], x[2 * gg + 1]};
-          *reinterpret_cast<u32x2 *>(ds + ds_base + ((cc << 4) ^ ds_rot)) = piece;
+          lds_store_b64_unseen(&dST[0][0][ds_off + ((cc << 4) ^ ds_rot)], piece);
         }
       }
     };
@@ -324,7 +338,7 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
   // tile t: cur holds it, nxt holds tile t + 1 (arrived by the barrier), nn takes tile t + 2
   int t = 0;
   auto step = [&](Ring &cur, Ring &nxt, Ring &nn, int slot) __attribute__((always_inline)) {
-    wait_vmem();
+    wait_vmem_lds();
     __syncthreads();
     if (t + 2 < T) load_tile(t + 2, nn);
     if (t + 1 < T) row_terms(nxt, slot == 2 ? 0 : slot + 1);
@@ -332,7 +346,7 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
     if (t > 1) dq_flush(t - 2);  // staged at the end of the previous step
     __builtin_amdgcn_sched_barrier(0);
     // (the first tile has no predecessor: its dQ parts run on whatever the buffer holds and are dropped)
-    main_tile(cur, slot, &dST[t & 1][0][0], dST[(t - 1) & 1]);
+    main_tile(cur, slot, t & 1, dST[(t - 1) & 1]);
     if (t > 0) dq_stage();  // dQ of tile t - 1
     ++t;
   };
@@ -343,6 +357,7 @@ __global__ void __launch_bounds__(64 * NW, 1) shortkeys_bwd_kernel(SkArgs a) {
     if (t >= T) break;
     step(ring2, ring0, ring1, 2);
   }
+  wait_vmem_lds();
   __syncthreads();
   if (T > 1) dq_flush(T - 2);
   dq_part(dST[(T - 1) & 1], 0);
